@@ -1,0 +1,242 @@
+/*
+ * CPU oracle for one AdaGC optimizer step (arxiv 2502.11034).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It is never part of the product path, it
+ * shares no code with the HIP sources, and it is written for readability, not
+ * speed: one thread, scalar loops, every floating-point scalar in double.
+ *
+ * What follows the paper:
+ *   - l2 norm of one gradient tensor ............ Sec. 4.1 (notation), Eq. 3
+ *   - AdaGC coefficient h_{t,i} and EMA gamma .... Eq. 3, Alg. 1 (AdaGC branch)
+ *   - warm-up: GlobalGC + running minimum ........ Eq. 2, Alg. 1 (warm-up branch)
+ *   - AdamW moments, bias correction, update ..... Alg. 1 (last four statements)
+ * What the paper does not print and is taken from its citation:
+ *   - Lion update rule (Chen et al., "Symbolic discovery of optimization
+ *     algorithms"): c = b1 m + (1-b1) g; theta -= lr (sign(c) + wd theta);
+ *     m = b2 m + (1-b2) g.          "parity unpinned by the paper" for the rule
+ *     itself; its arithmetic is pinned by hand-worked cases in the tests.
+ *
+ * Readings taken where the paper is silent (each also listed in the design
+ * notes of the repository):
+ *   - the EMA takes the CLIPPED norm (sentence after Eq. 3, Alg. 1), evaluated
+ *     analytically: lambda_rel*gamma when clipped, the raw norm otherwise;
+ *   - the clip is active only for norm > lambda_rel*gamma (strict);
+ *   - the step counter passed in is 1-based and is the t of the bias
+ *     correction; warm-up covers steps 1..T_start ("the first T_start steps"),
+ *     and on step 1 gamma is set to the (globally clipped) norm of that step;
+ *   - gamma, theta, m, v are stored as 32-bit floats; each is rounded exactly
+ *     once per step, from the double result;
+ *   - a bf16 copy of theta is the round-to-nearest-even of the stored float;
+ *   - a bf16 gradient is widened exactly before use.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+/* ---- bf16 <-> float, from the format definition (1-8-7 bits, the top half
+ *      of an IEEE binary32) -------------------------------------------------- */
+
+float oracle_bf16_to_float(uint16_t b)
+{
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* Round to nearest, ties to even, by comparing the discarded 16 bits with one
+ * half unit in the last kept place.  NaN stays NaN (quiet bit forced). */
+uint16_t oracle_float_to_bf16_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu) != 0u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t kept = u >> 16;
+    uint32_t dropped = u & 0xFFFFu;
+    if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u)))
+        kept += 1u; /* carry into the exponent is the correct rounding, up to inf */
+    return (uint16_t)kept;
+}
+
+/* ---- Sec. 4.1 / Eq. 3: l2 norm of one tensor ------------------------------ */
+
+/* grad_dtype: 0 = float32, 1 = bf16.  Sum of squares in index order. */
+double oracle_sum_squares(const void *g, int64_t numel, int grad_dtype)
+{
+    double s = 0.0;
+    if (grad_dtype == 0) {
+        const float *gf = (const float *)g;
+        for (int64_t j = 0; j < numel; ++j) {
+            double x = (double)gf[j];
+            s += x * x;
+        }
+    } else {
+        const uint16_t *gb = (const uint16_t *)g;
+        for (int64_t j = 0; j < numel; ++j) {
+            double x = (double)oracle_bf16_to_float(gb[j]);
+            s += x * x;
+        }
+    }
+    return s;
+}
+
+double oracle_l2_norm(const void *g, int64_t numel, int grad_dtype)
+{
+    return sqrt(oracle_sum_squares(g, numel, grad_dtype));
+}
+
+/* ---- Eq. 3, Alg. 1 AdaGC branch: one tensor's scalars --------------------- */
+
+/* norm = ||g_{t,i}||, gamma_prev = gamma_{t-1,i}.
+ * Outputs h_{t,i}, gamma_{t,i}, and whether the clip was active. */
+void oracle_adagc_rule(double norm, double gamma_prev, double lambda_rel, double beta,
+                       double *h, double *gamma_new, int *clipped)
+{
+    double threshold = lambda_rel * gamma_prev;
+    int active = (norm > threshold);       /* strict; false for NaN operands */
+    double coef = active ? threshold / norm : 1.0;
+    double clipped_norm = active ? threshold : norm; /* = ||h g|| */
+    *h = coef;
+    *gamma_new = beta * gamma_prev + (1.0 - beta) * clipped_norm;
+    *clipped = active;
+}
+
+/* ---- Eq. 2, Alg. 1 warm-up branch ----------------------------------------- */
+
+/* h_t = min{lambda_abs / ||g_t||, 1}. */
+double oracle_globalgc_coef(double global_norm, double lambda_abs)
+{
+    int active = (global_norm > lambda_abs);
+    return active ? lambda_abs / global_norm : 1.0;
+}
+
+/* gamma_{t,i} = min{gamma_{t-1,i}, ||ghat_{t,i}||}; on the very first step
+ * gamma is the clipped norm of that step. */
+double oracle_warmup_gamma(double gamma_prev, double clipped_norm, int first_step)
+{
+    if (first_step)
+        return clipped_norm;
+    return clipped_norm < gamma_prev ? clipped_norm : gamma_prev;
+}
+
+/* ---- Alg. 1, last four statements: AdamW on the clipped gradient ----------- */
+
+typedef struct {
+    double lr, beta1, beta2, eps, weight_decay;
+} oracle_opt_hyper;
+
+static double grad_at(const void *g, int64_t j, int grad_dtype)
+{
+    if (grad_dtype == 0)
+        return (double)((const float *)g)[j];
+    return (double)oracle_bf16_to_float(((const uint16_t *)g)[j]);
+}
+
+void oracle_adamw_update(float *theta, float *m, float *v, const void *g, int grad_dtype,
+                         int64_t numel, double h, const oracle_opt_hyper *hp, int64_t t,
+                         uint16_t *theta_bf16 /* may be NULL */)
+{
+    double bias1 = 1.0 - pow(hp->beta1, (double)t);
+    double bias2 = 1.0 - pow(hp->beta2, (double)t);
+    for (int64_t j = 0; j < numel; ++j) {
+        double ghat = h * grad_at(g, j, grad_dtype);
+        double mj = hp->beta1 * (double)m[j] + (1.0 - hp->beta1) * ghat;
+        double vj = hp->beta2 * (double)v[j] + (1.0 - hp->beta2) * ghat * ghat;
+        double mhat = mj / bias1;
+        double vhat = vj / bias2;
+        double th = (double)theta[j];
+        th = th - hp->lr * hp->weight_decay * th - hp->lr * mhat / (sqrt(vhat) + hp->eps);
+        m[j] = (float)mj;
+        v[j] = (float)vj;
+        theta[j] = (float)th;
+        if (theta_bf16)
+            theta_bf16[j] = oracle_float_to_bf16_rne(theta[j]);
+    }
+}
+
+/* ---- Lion on the clipped gradient (rule imported from its own paper) ------- */
+
+void oracle_lion_update(float *theta, float *m, const void *g, int grad_dtype, int64_t numel,
+                        double h, const oracle_opt_hyper *hp, uint16_t *theta_bf16)
+{
+    for (int64_t j = 0; j < numel; ++j) {
+        double ghat = h * grad_at(g, j, grad_dtype);
+        double mprev = (double)m[j];
+        double c = hp->beta1 * mprev + (1.0 - hp->beta1) * ghat;
+        double sgn = (c > 0.0) ? 1.0 : ((c < 0.0) ? -1.0 : 0.0);
+        double th = (double)theta[j];
+        th = th - hp->lr * (sgn + hp->weight_decay * th);
+        double mj = hp->beta2 * mprev + (1.0 - hp->beta2) * ghat;
+        theta[j] = (float)th;
+        m[j] = (float)mj;
+        if (theta_bf16)
+            theta_bf16[j] = oracle_float_to_bf16_rne(theta[j]);
+    }
+}
+
+/* ---- Alg. 1, one pass of the repeat-loop body over a list of tensors ------- */
+
+typedef struct {
+    double lr, beta1, beta2, eps, weight_decay; /* eta_t, beta_1, beta_2, epsilon, lambda_w */
+    double lambda_rel, ema_beta;                /* lambda_rel, beta                        */
+    double lambda_abs;                          /* GlobalGC threshold of the warm-up        */
+    int64_t t_start;                            /* number of warm-up steps                  */
+    int32_t optimizer;                          /* 0 = AdamW, 1 = Lion                      */
+    int32_t grad_dtype;                         /* 0 = float32, 1 = bf16                    */
+} oracle_step_hyper;
+
+/* Arrays of per-tensor pointers; state is updated in place.  v may be NULL for
+ * Lion, theta_bf16 may be NULL.  step is the 1-based t.  out_* receive the
+ * per-tensor pre-clip norm, coefficient, and clip flag (each may be NULL).
+ * Returns 0, or -1 on a bad argument. */
+int oracle_adagc_step(int64_t n_tensors, const int64_t *numel, float *const *theta,
+                      const void *const *grad, float *const *m, float *const *v,
+                      uint16_t *const *theta_bf16, float *gamma, const oracle_step_hyper *hp,
+                      int64_t step, double *out_norm, double *out_coef, uint8_t *out_clipped)
+{
+    if (n_tensors <= 0 || step < 1 || !numel || !theta || !grad || !m || !gamma || !hp)
+        return -1;
+    if (hp->optimizer == 0 && !v)
+        return -1;
+
+    oracle_opt_hyper oh = { hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay };
+    int warmup = (step - 1) < hp->t_start; /* steps 1..T_start */
+
+    double h_global = 1.0;
+    if (warmup) {
+        /* ||g_t|| over the whole model: tensors in list order, elements in index order */
+        double s = 0.0;
+        for (int64_t i = 0; i < n_tensors; ++i)
+            s += oracle_sum_squares(grad[i], numel[i], hp->grad_dtype);
+        h_global = oracle_globalgc_coef(sqrt(s), hp->lambda_abs);
+    }
+
+    for (int64_t i = 0; i < n_tensors; ++i) {
+        double norm = oracle_l2_norm(grad[i], numel[i], hp->grad_dtype);
+        double gamma_prev = (double)gamma[i];
+        double h, gamma_new;
+        int clipped;
+        if (warmup) {
+            h = h_global;
+            clipped = (h_global < 1.0);
+            gamma_new = oracle_warmup_gamma(gamma_prev, h * norm, step == 1);
+        } else {
+            oracle_adagc_rule(norm, gamma_prev, hp->lambda_rel, hp->ema_beta, &h, &gamma_new,
+                              &clipped);
+        }
+        gamma[i] = (float)gamma_new;
+        if (out_norm) out_norm[i] = norm;
+        if (out_coef) out_coef[i] = h;
+        if (out_clipped) out_clipped[i] = (uint8_t)clipped;
+
+        uint16_t *copy = theta_bf16 ? theta_bf16[i] : NULL;
+        if (hp->optimizer == 0)
+            oracle_adamw_update(theta[i], m[i], v[i], grad[i], hp->grad_dtype, numel[i], h, &oh,
+                                step, copy);
+        else
+            oracle_lion_update(theta[i], m[i], grad[i], hp->grad_dtype, numel[i], h, &oh, copy);
+    }
+    return 0;
+}

@@ -1,0 +1,503 @@
+"""Pins for the CPU oracle: it is checked against what the paper and the
+mathematics fix (closed forms, invariants, exact dyadic hand-worked cases,
+library routines, brute force on tiny inputs), never against itself.
+
+Citations: Eq. 2 (GlobalGC), Eq. 3 (AdaGC coefficient and EMA), Alg. 1 (warm-up
+branch, AdaGC branch, AdamW statements), Sec. 4.3 (one fp32 of state per tensor).
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import Hyper
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_defaults.txt")
+
+
+def golden():
+    out = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            parts = line.split()
+            out[parts[0]] = float(parts[1])
+    return out
+
+
+def f32(x):
+    return float(np.float32(x))
+
+
+# ------------------------------------------------------------------ norm (Sec. 4.1, Eq. 3)
+
+def test_norm_hand_values():
+    assert oracle.l2_norm(np.array([3, 4], dtype=np.float32)) == 5.0
+    assert oracle.l2_norm(np.array([-5, 12], dtype=np.float32)) == 13.0
+    assert oracle.l2_norm(np.array([1, 2, 2], dtype=np.float32)) == 3.0
+    assert oracle.l2_norm(np.array([0], dtype=np.float32)) == 0.0
+    assert oracle.l2_norm(np.array([-7], dtype=np.float32)) == 7.0
+
+
+@pytest.mark.parametrize("n", [1, 4, 9, 16, 1024, 65536, 1000000])
+def test_norm_all_ones_perfect_square(n):
+    assert oracle.l2_norm(np.ones(n, dtype=np.float32)) == math.sqrt(n)
+
+
+def test_norm_exact_rational_bruteforce():
+    rng = np.random.default_rng(1)
+    for n in range(1, 17):
+        g = (rng.standard_normal(n) * 10 ** rng.uniform(-4, 2)).astype(np.float32)
+        exact = sum(Fraction(float(x)) ** 2 for x in g)
+        got = oracle.sum_squares(g)
+        assert abs(Fraction(got) - exact) <= exact * Fraction(n, 2 ** 52)
+
+
+def test_norm_vs_library_nrm2():
+    rng = np.random.default_rng(2)
+    for n in (17, 1000, 123457):
+        g = rng.standard_normal(n).astype(np.float32) * 3e-3
+        ref = np.linalg.norm(g.astype(np.float64))
+        assert oracle.l2_norm(g) == pytest.approx(ref, rel=1e-13)
+
+
+def test_norm_sign_and_order_independent():
+    rng = np.random.default_rng(3)
+    g = rng.standard_normal(1000).astype(np.float32)
+    a = oracle.l2_norm(g)
+    assert oracle.l2_norm(-g) == a
+    assert oracle.l2_norm(np.ascontiguousarray(g[::-1])) == pytest.approx(a, rel=1e-14)
+    # homogeneity with an exact scale
+    assert oracle.l2_norm(g * np.float32(4.0)) == 4.0 * a
+
+
+def test_norm_bf16_input_is_widened_exactly():
+    vals = torch.tensor([3.0, -4.0, 0.5, 1.0078125, -2.5e-3], dtype=torch.float32).to(torch.bfloat16)
+    bits = vals.view(torch.int16).numpy().view(np.uint16).copy()
+    ref = math.sqrt(sum(float(x) ** 2 for x in vals.to(torch.float64)))
+    assert oracle.l2_norm(bits) == pytest.approx(ref, rel=1e-15)
+    assert oracle.l2_norm(np.array([0x4040, 0xC080], dtype=np.uint16)) == 5.0   # bf16(3), bf16(-4)
+
+
+# ------------------------------------------------------------------ bf16 conversion (format definition)
+
+def test_bf16_rne_vs_library_cast():
+    rng = np.random.default_rng(4)
+    x = np.concatenate([
+        rng.standard_normal(5000).astype(np.float32) * 10.0 ** rng.integers(-30, 30, 5000),
+        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 1.0039063, 1.0039062,
+                  np.inf, -np.inf, 3.3895314e38, 3.4028235e38, 1e-40, -1e-45], dtype=np.float32),
+    ]).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.float_to_bf16_rne(x)
+    assert np.array_equal(got, ref)
+    # ties go to the even neighbour: 1 + 2^-8 is halfway between 1.0 (even) and 1 + 2^-7
+    assert oracle.float_to_bf16_rne(np.array([1.00390625], np.float32))[0] == 0x3F80
+    # 1 + 3*2^-8 is halfway between 1+2^-7 (odd) and 1+2^-6 (even)
+    assert oracle.float_to_bf16_rne(np.array([1.01171875], np.float32))[0] == 0x3F82
+    nan_bits = oracle.float_to_bf16_rne(np.array([np.nan], np.float32))[0]
+    assert (nan_bits & 0x7F80) == 0x7F80 and (nan_bits & 0x007F) != 0
+
+
+def test_bf16_widen_vs_library():
+    bits = np.arange(0, 65536, 7, dtype=np.uint16)
+    ref = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).to(torch.float32).numpy()
+    got = oracle.bf16_to_float(bits)
+    # NaN payloads do not survive a float -> Python float -> float round trip; compare them as NaN
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), ref[~nan].view(np.uint32))
+
+
+# ------------------------------------------------------------------ Eq. 3: coefficient, EMA
+
+def test_rule_hand_values_dyadic():
+    # gamma=1, lambda=2, beta=0.5: threshold 2.  norm 8 -> h = 1/4, EMA takes the clipped norm 2.
+    h, g, c = oracle.adagc_rule(8.0, 1.0, 2.0, 0.5)
+    assert (h, g, c) == (0.25, 1.5, True)
+    # norm 1.5 < 2: no clip, EMA takes the raw norm
+    h, g, c = oracle.adagc_rule(1.5, 1.0, 2.0, 0.5)
+    assert (h, g, c) == (1.0, 1.25, False)
+    # tie: strict inequality, not active, h = 1
+    h, g, c = oracle.adagc_rule(2.0, 1.0, 2.0, 0.5)
+    assert (h, g, c) == (1.0, 1.5, False)
+
+
+def test_rule_paper_defaults_growth_factor():
+    gold = golden()
+    lam, beta = gold["lambda_rel"], gold["ema_beta"]
+    h, g, c = oracle.adagc_rule(100.0, 1.0, lam, beta)
+    assert c and h == pytest.approx(lam / 100.0, rel=1e-15)
+    assert g == pytest.approx(gold["always_clip_growth"], rel=1e-12)
+
+
+def test_rule_clipped_norm_invariant():
+    """After scaling, the tensor's norm is at most lambda_rel*gamma, and equal to it when the
+    clip is active (sentence after Eq. 3)."""
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        n = int(rng.integers(1, 64))
+        g = (rng.standard_normal(n) * 10 ** rng.uniform(-3, 1)).astype(np.float32)
+        gamma = f32(10 ** rng.uniform(-3, 1))
+        lam = f32(1.04)
+        norm = oracle.l2_norm(g)
+        h, gnew, clipped = oracle.adagc_rule(norm, gamma, lam, f32(0.99))
+        scaled = np.linalg.norm(g.astype(np.float64) * h)
+        thr = lam * gamma
+        assert 0.0 < h <= 1.0
+        assert scaled <= thr * (1 + 1e-12)
+        if clipped:
+            assert norm > thr
+            assert scaled == pytest.approx(thr, rel=1e-12)
+        else:
+            assert h == 1.0 and norm <= thr
+
+
+def test_rule_scale_invariance():
+    for c in (0.125, 2.0, 1024.0):
+        a = oracle.adagc_rule(3.0, 1.0, 1.5, 0.75)
+        b = oracle.adagc_rule(3.0 * c, 1.0 * c, 1.5, 0.75)
+        assert a[0] == b[0] and a[2] == b[2] and b[1] == a[1] * c
+
+
+def test_rule_degenerate_cases():
+    # zero gradient: no division, h = 1, EMA decays toward 0
+    assert oracle.adagc_rule(0.0, 2.0, 1.04, 0.5) == (1.0, 1.0, False)
+    # zero EMA with a non-zero gradient: literal reading of Eq. 3 gives h = 0 and gamma stays 0
+    assert oracle.adagc_rule(3.0, 0.0, 1.04, 0.99) == (0.0, 0.0, True)
+    # both zero
+    assert oracle.adagc_rule(0.0, 0.0, 1.04, 0.99) == (1.0, 0.0, False)
+    # infinite lambda_rel: never active, also with gamma = 0 (threshold is NaN there)
+    h, g, c = oracle.adagc_rule(3.0, 2.0, math.inf, 0.5)
+    assert (h, g, c) == (1.0, 2.5, False)
+    h, g, c = oracle.adagc_rule(3.0, 0.0, math.inf, 0.5)
+    assert (h, g, c) == (1.0, 1.5, False)
+    # NaN norm: compare is false, no clip, NaN flows into the EMA as it would into AdamW
+    h, g, c = oracle.adagc_rule(math.nan, 1.0, 1.04, 0.99)
+    assert h == 1.0 and not c and math.isnan(g)
+
+
+def test_ema_closed_forms():
+    gold = golden()
+    lam, beta = gold["lambda_rel"], gold["ema_beta"]
+    k = 50
+    # (a) every step clipped: gamma_k = gamma_0 * rho^k, rho = beta + (1-beta)*lambda_rel
+    g0 = 0.7
+    gamma = g0
+    for _ in range(k):
+        h, gamma, c = oracle.adagc_rule(1e6, gamma, lam, beta)
+        assert c
+    assert gamma == pytest.approx(g0 * gold["always_clip_growth"] ** k, rel=1e-12)
+    # (b) constant norm below threshold: gamma_k = n + beta^k (gamma_0 - n)
+    n, g0 = 2.0, 2.5
+    gamma = g0
+    for _ in range(k):
+        h, gamma, c = oracle.adagc_rule(n, gamma, lam, beta)
+        assert not c and h == 1.0
+    assert gamma == pytest.approx(n + beta ** k * (g0 - n), rel=1e-12)
+    # (c) never clipped, varying norms: gamma_k = beta^k gamma_0 + (1-beta) sum beta^(k-j) n_j
+    rng = np.random.default_rng(6)
+    ns = 1.0 + 0.01 * rng.random(k)           # within 1% of 1 => below 1.04*gamma throughout
+    g0 = 1.0
+    gamma = g0
+    for j in range(k):
+        h, gamma, c = oracle.adagc_rule(float(ns[j]), gamma, lam, beta)
+        assert not c
+    closed = beta ** k * g0 + (1 - beta) * sum(beta ** (k - 1 - j) * ns[j] for j in range(k))
+    assert gamma == pytest.approx(closed, rel=1e-12)
+
+
+def test_ema_step_bounds():
+    """beta*gamma <= gamma_new <= (beta + (1-beta)*lambda_rel)*gamma, whatever the norm."""
+    rng = np.random.default_rng(7)
+    for _ in range(500):
+        gamma = 10 ** rng.uniform(-4, 2)
+        norm = gamma * 10 ** rng.uniform(-3, 3)
+        h, gnew, c = oracle.adagc_rule(norm, gamma, 1.04, 0.99)
+        assert 0.99 * gamma * (1 - 1e-15) <= gnew <= 1.0004 * gamma * (1 + 1e-15)
+
+
+# ------------------------------------------------------------------ Eq. 2 / warm-up branch of Alg. 1
+
+def test_globalgc_coef():
+    assert oracle.globalgc_coef(13.0, 6.5) == 0.5
+    assert oracle.globalgc_coef(0.5, 1.0) == 1.0
+    assert oracle.globalgc_coef(1.0, 1.0) == 1.0
+    assert oracle.globalgc_coef(0.0, 1.0) == 1.0
+    assert oracle.globalgc_coef(7.0, math.inf) == 1.0
+
+
+def test_warmup_gamma_running_min():
+    assert oracle.warmup_gamma(123.0, 5.0, True) == 5.0      # gamma_0 = ||ghat_1||
+    assert oracle.warmup_gamma(0.0, 5.0, True) == 5.0
+    assert oracle.warmup_gamma(5.0, 3.0, False) == 3.0
+    assert oracle.warmup_gamma(5.0, 8.0, False) == 5.0
+
+
+def _lists(arrs, dtype=np.float32):
+    return [np.array(a, dtype=dtype) for a in arrs]
+
+
+def test_step_warmup_branch_hand_worked():
+    """Two tensors [3,4] and [12]: global norm 13, lambda_abs 6.5 -> h = 1/2 for both.
+    Step 1 sets gamma to the clipped norms (2.5, 6); step 2 keeps the running minimum."""
+    theta = _lists([[0, 0], [0]])
+    m = _lists([[0, 0], [0]])
+    v = _lists([[0, 0], [0]])
+    gamma = np.zeros(2, dtype=np.float32)
+    hp = Hyper(lr=0.0, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.0, lambda_abs=6.5, t_start=2)
+    norms, coefs, clipped = oracle.adagc_step(theta, _lists([[3, 4], [12]]), m, v, gamma, hp, 1)
+    assert list(norms) == [5.0, 12.0] and list(coefs) == [0.5, 0.5] and list(clipped) == [1, 1]
+    assert list(gamma) == [2.5, 6.0]
+    # m takes the globally clipped gradient: (1-beta1)*h*g
+    assert list(m[0]) == [0.75, 1.0] and list(m[1]) == [3.0]
+    # v takes its square: (1-beta2)*(h*g)^2
+    assert list(v[0]) == [0.5625, 1.0] and list(v[1]) == [9.0]
+    # step 2 (still warm-up): small gradients, no global clip; min() keeps 2.5 and lowers 6 -> 4
+    norms, coefs, clipped = oracle.adagc_step(theta, _lists([[0, 3], [4]]), m, v, gamma, hp, 2)
+    assert list(coefs) == [1.0, 1.0] and list(clipped) == [0, 0]
+    assert list(gamma) == [2.5, 4.0]
+    # step 3: warm-up over (t_start = 2) -> AdaGC branch with Eq. 3
+    hp.lambda_rel, hp.ema_beta = 2.0, 0.5
+    norms, coefs, clipped = oracle.adagc_step(theta, _lists([[6, 8], [4]]), m, v, gamma, hp, 3)
+    assert list(norms) == [10.0, 4.0]
+    assert list(coefs) == [0.5, 1.0] and list(clipped) == [1, 0]      # 10 > 2*2.5 ; 4 <= 2*4
+    assert list(gamma) == [0.5 * 2.5 + 0.5 * 5.0, 0.5 * 4.0 + 0.5 * 4.0]
+
+
+def test_step_init_step_without_global_clip():
+    """t_start = 1 with infinite lambda_abs: step 1 passes gradients through and sets gamma to
+    their norms; AdaGC is live from step 2."""
+    theta, m, v = _lists([[1, 1]]), _lists([[0, 0]]), _lists([[0, 0]])
+    gamma = np.array([77.0], dtype=np.float32)
+    hp = Hyper(lr=0.0, lambda_rel=2.0, ema_beta=0.5)
+    norms, coefs, clipped = oracle.adagc_step(theta, _lists([[3, 4]]), m, v, gamma, hp, 1)
+    assert coefs[0] == 1.0 and clipped[0] == 0 and gamma[0] == 5.0
+    norms, coefs, clipped = oracle.adagc_step(theta, _lists([[30, 40]]), m, v, gamma, hp, 2)
+    assert norms[0] == 50.0 and clipped[0] == 1 and coefs[0] == 0.2 and gamma[0] == 7.5
+
+
+def test_step_t_start_zero_uses_caller_gamma():
+    theta, m, v = _lists([[1, 1]]), _lists([[0, 0]]), _lists([[0, 0]])
+    gamma = np.array([1.0], dtype=np.float32)
+    hp = Hyper(lr=0.0, lambda_rel=2.0, ema_beta=0.5, t_start=0)
+    norms, coefs, clipped = oracle.adagc_step(theta, _lists([[3, 4]]), m, v, gamma, hp, 1)
+    assert clipped[0] == 1 and coefs[0] == 0.4 and gamma[0] == 1.5
+
+
+# ------------------------------------------------------------------ AdamW statements of Alg. 1
+
+def test_adamw_dyadic_hand_worked_two_steps():
+    """beta1=1/2, beta2=3/4, lr=1/2, eps=0, wd=1/4, theta0=4, g=4 scaled by h=1/2 (ghat=2).
+    t=1: m=1, v=1, mhat=2, vhat=4, theta = 4 - 1/2*1/4*4 - 1/2*2/2 = 3.
+    t=2: m=3/2, v=7/4, mhat=2, vhat=4, theta = 3 - 3/8 - 1/2 = 17/8."""
+    hp = Hyper(lr=0.5, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.25)
+    theta, m, v = (np.array([4.0], np.float32), np.zeros(1, np.float32), np.zeros(1, np.float32))
+    g = np.array([4.0], np.float32)
+    copy = np.zeros(1, np.uint16)
+    oracle.adamw_update(theta, m, v, g, 0.5, hp, 1, copy)
+    assert (theta[0], m[0], v[0]) == (3.0, 1.0, 1.0)
+    assert copy[0] == 0x4040                                   # bf16(3.0)
+    oracle.adamw_update(theta, m, v, g, 0.5, hp, 2, copy)
+    assert (theta[0], m[0], v[0]) == (2.125, 1.5, 1.75)
+    assert copy[0] == 0x4008                                   # bf16(2.125) = 2 + 2^-3
+
+
+def test_adamw_step1_closed_form():
+    """m0=v0=0, t=1: m=(1-b1)g, v=(1-b2)g^2, theta1 = theta0(1-lr*wd) - lr*g/(|g|+eps)."""
+    rng = np.random.default_rng(8)
+    n = 257
+    hp = Hyper()
+    theta0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    theta, m, v = theta0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    oracle.adamw_update(theta, m, v, g, 1.0, hp, 1)
+    b1, b2, lr, wd, eps = map(f32, (hp.beta1, hp.beta2, hp.lr, hp.weight_decay, hp.eps))
+    gd, td = g.astype(np.float64), theta0.astype(np.float64)
+    np.testing.assert_allclose(m, (1 - b1) * gd, rtol=1e-7)
+    np.testing.assert_allclose(v, (1 - b2) * gd * gd, rtol=1e-7)
+    np.testing.assert_allclose(theta, td * (1 - lr * wd) - lr * gd / (np.abs(gd) + eps),
+                               rtol=2e-7, atol=1e-12)
+
+
+@pytest.mark.parametrize("eps", [1e-8, 1e-3])
+def test_adamw_matches_library_adamw_when_never_clipped(eps):
+    """lambda_rel = +inf: the whole step is plain AdamW.  The library routine runs in float64;
+    the oracle stores float32 after each step, so agreement is to a few float32 roundings."""
+    rng = np.random.default_rng(9)
+    sizes = [1, 5, 64, 1000]
+    hp = Hyper(lr=1e-2, beta1=0.9, beta2=0.95, eps=eps, weight_decay=0.1, lambda_rel=math.inf)
+    theta = [(rng.standard_normal(n) * 0.5).astype(np.float32) for n in sizes]
+    m = [np.zeros(n, np.float32) for n in sizes]
+    v = [np.zeros(n, np.float32) for n in sizes]
+    gamma = np.zeros(len(sizes), np.float32)
+    tp = [torch.tensor(t.astype(np.float64), requires_grad=True) for t in theta]
+    opt = torch.optim.AdamW(tp, lr=f32(hp.lr), betas=(f32(hp.beta1), f32(hp.beta2)), eps=f32(eps),
+                            weight_decay=f32(hp.weight_decay), foreach=False)
+    for step in range(1, 8):
+        grads = [(rng.standard_normal(n) * 10 ** rng.uniform(-4, 0)).astype(np.float32) for n in sizes]
+        norms, coefs, clipped = oracle.adagc_step(theta, grads, m, v, gamma, hp, step)
+        assert not clipped.any() and (coefs == 1.0).all()
+        for p, g in zip(tp, grads):
+            p.grad = torch.tensor(g.astype(np.float64))
+        opt.step()
+        for i, p in enumerate(tp):
+            st = opt.state[p]
+            # theta crosses zero under lr-sized steps: absolute slack of a few float32 roundings
+            np.testing.assert_allclose(theta[i], p.detach().numpy(), rtol=2e-6, atol=1e-6 * f32(hp.lr))
+            # m can cancel: absolute slack of a few float32 roundings of its largest entry
+            m_ref = st["exp_avg"].numpy()
+            np.testing.assert_allclose(m[i], m_ref, rtol=2e-6, atol=1e-6 * np.abs(m_ref).max())
+            np.testing.assert_allclose(v[i], st["exp_avg_sq"].numpy(), rtol=2e-6, atol=1e-20)
+
+
+def test_adamw_clip_enters_before_the_moments():
+    """The coefficient multiplies g before m and v (Alg. 1): updating with (g, h) equals updating
+    with (h*g, 1) when h*g is exact."""
+    rng = np.random.default_rng(10)
+    n = 100
+    g = rng.standard_normal(n).astype(np.float32)
+    hp = Hyper()
+    a = [np.full(n, 0.3, np.float32), np.full(n, 0.01, np.float32), np.full(n, 1e-4, np.float32)]
+    b = [x.copy() for x in a]
+    oracle.adamw_update(a[0], a[1], a[2], g, 0.25, hp, 3)
+    oracle.adamw_update(b[0], b[1], b[2], g * np.float32(0.25), 1.0, hp, 3)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+# ------------------------------------------------------------------ Lion (imported rule)
+
+def test_lion_dyadic_hand_worked():
+    """beta1=1/2, beta2=3/4, lr=1/4, wd=1/2; m=2, ghat=-4, theta=1:
+    c = 1 - 2 = -1 -> sign -1; theta = 1 - 1/4(-1 + 1/2) = 9/8; m = 3/2 - 1 = 1/2."""
+    hp = Hyper(lr=0.25, beta1=0.5, beta2=0.75, weight_decay=0.5, optimizer=oracle.LION)
+    theta, m = np.array([1.0], np.float32), np.array([2.0], np.float32)
+    copy = np.zeros(1, np.uint16)
+    oracle.lion_update(theta, m, np.array([-8.0], np.float32), 0.5, hp, copy)
+    assert (theta[0], m[0]) == (1.125, 0.5)
+    assert copy[0] == 0x3F90
+
+
+def test_lion_interpolation_uses_beta1_and_momentum_uses_beta2():
+    """m=1, g=-3: with beta1=0.9 c=+0.6 (sign +), with beta2=0.5 the new m is -1.
+    Swapping the two betas would flip the sign of the update."""
+    hp = Hyper(lr=0.125, beta1=0.9, beta2=0.5, weight_decay=0.0, optimizer=oracle.LION)
+    theta, m = np.array([0.0], np.float32), np.array([1.0], np.float32)
+    oracle.lion_update(theta, m, np.array([-3.0], np.float32), 1.0, hp)
+    assert theta[0] == -0.125 and m[0] == -1.0
+
+
+def test_lion_update_magnitude_and_sign_zero():
+    rng = np.random.default_rng(11)
+    n = 500
+    hp = Hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1, optimizer=oracle.LION)
+    theta0 = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    g = rng.standard_normal(n).astype(np.float32)
+    g[:10] = 0.0
+    theta, m = theta0.copy(), np.zeros(n, np.float32)
+    oracle.lion_update(theta, m, g, 1.0, hp)
+    lr, wd = f32(hp.lr), f32(hp.weight_decay)
+    decayed = theta0.astype(np.float64) * (1 - lr * wd)
+    delta = theta.astype(np.float64) - decayed
+    # first step, m = 0: sign(c) = sign(g); zero gradient gives sign 0 (only the decay acts)
+    np.testing.assert_allclose(delta, -lr * np.sign(g), atol=4e-9)
+    np.testing.assert_allclose(m, (1 - f32(hp.beta2)) * g.astype(np.float64), rtol=1e-7)
+
+
+# ------------------------------------------------------------------ whole step: indexing
+
+def test_step_tensors_are_independent_and_permutable():
+    rng = np.random.default_rng(12)
+    sizes = [3, 1, 16, 7, 40]
+    hp = Hyper(t_start=0)
+
+    def fresh():
+        r = np.random.default_rng(13)
+        theta = [r.standard_normal(n).astype(np.float32) for n in sizes]
+        m = [r.standard_normal(n).astype(np.float32) * 0.1 for n in sizes]
+        v = [(r.standard_normal(n).astype(np.float32) * 0.1) ** 2 for n in sizes]
+        g = [r.standard_normal(n).astype(np.float32) * (10.0 ** (i - 2)) for i, n in enumerate(sizes)]
+        gamma = np.array([0.5, 0.05, 50.0, 1.0, 1e4], np.float32)
+        return theta, g, m, v, gamma
+
+    theta, g, m, v, gamma = fresh()
+    n0, c0, f0 = oracle.adagc_step(theta, g, m, v, gamma, hp, 5)
+    assert f0.any() and not f0.all()
+    perm = [3, 0, 4, 2, 1]
+    t2, g2, m2, v2, gm2 = fresh()
+    tp, gp, mp, vp = ([x[i] for i in perm] for x in (t2, g2, m2, v2))
+    gmp = gm2[perm].copy()
+    n1, c1, f1 = oracle.adagc_step(tp, gp, mp, vp, gmp, hp, 5)
+    for k, i in enumerate(perm):
+        assert n1[k] == n0[i] and c1[k] == c0[i] and f1[k] == f0[i] and gmp[k] == gamma[i]
+        assert np.array_equal(tp[k], theta[i]) and np.array_equal(mp[k], m[i]) and np.array_equal(vp[k], v[i])
+    # each tensor alone gives the same result as inside the list (per-tensor rule)
+    t3, g3, m3, v3, gm3 = fresh()
+    for i in range(len(sizes)):
+        gi = gm3[i:i + 1].copy()
+        ni, ci, fi = oracle.adagc_step([t3[i]], [g3[i]], [m3[i]], [v3[i]], gi, hp, 5)
+        assert ni[0] == n0[i] and ci[0] == c0[i] and gi[0] == gamma[i]
+        assert np.array_equal(t3[i], theta[i])
+
+
+def test_step_equals_pieces():
+    """The list step is the composition norm -> rule -> update, tensor by tensor."""
+    rng = np.random.default_rng(14)
+    n = 33
+    hp = Hyper(t_start=0)
+    theta = rng.standard_normal(n).astype(np.float32)
+    g = rng.standard_normal(n).astype(np.float32)
+    m, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    gamma = np.array([1.0], np.float32)
+    t_ref, m_ref, v_ref = theta.copy(), m.copy(), v.copy()
+    norm = oracle.l2_norm(g)
+    h, gnew, c = oracle.adagc_rule(norm, 1.0, f32(hp.lambda_rel), f32(hp.ema_beta))
+    oracle.adamw_update(t_ref, m_ref, v_ref, g, h, hp, 4)
+    norms, coefs, clipped = oracle.adagc_step([theta], [g], [m], [v], gamma, hp, 4)
+    assert norms[0] == norm and coefs[0] == h and bool(clipped[0]) == c and c
+    assert gamma[0] == np.float32(gnew)
+    assert np.array_equal(theta, t_ref) and np.array_equal(m, m_ref) and np.array_equal(v, v_ref)
+
+
+def test_step_rejects_bad_arguments():
+    theta, m, v = _lists([[1]]), _lists([[0]]), _lists([[0]])
+    gamma = np.zeros(1, np.float32)
+    with pytest.raises(ValueError):
+        oracle.adagc_step(theta, _lists([[1]]), m, v, gamma, Hyper(), 0)       # step is 1-based
+    with pytest.raises(ValueError):
+        oracle.adagc_step(theta, _lists([[1]]), m, None, gamma, Hyper(), 1)    # AdamW needs v
+
+
+def test_gamma_state_is_one_float32_per_tensor():
+    """Sec. 4.3: the extra state is a single 32-bit float per tensor."""
+    theta, m, v = _lists([[1, 2, 3]]), _lists([[0, 0, 0]]), _lists([[0, 0, 0]])
+    gamma = np.zeros(1, np.float32)
+    g = _lists([[0.1, 0.2, 0.3]])
+    oracle.adagc_step(theta, g, m, v, gamma, Hyper(), 1)
+    assert gamma.dtype == np.float32 and gamma.nbytes == 4
+    assert gamma[0] == np.float32(oracle.l2_norm(g[0]))
+
+
+# ------------------------------------------------------------------ chunk enumeration
+
+def test_enumerate_chunks_covers_every_element_once():
+    rng = np.random.default_rng(15)
+    numels = [int(x) for x in rng.integers(1, 200, 40)] + [1, 16, 17, 32, 64]
+    for chunk in (1, 16, 17):
+        chunks, begin = oracle.enumerate_chunks(numels, chunk)
+        seen = [np.zeros(n, np.int32) for n in numels]
+        for (i, first, length) in chunks:
+            assert 1 <= length <= chunk and first % chunk == 0
+            seen[i][first:first + length] += 1
+        assert all((s == 1).all() for s in seen)
+        assert sum(c[2] for c in chunks) == sum(numels)
+        assert begin[0] == 0 and begin[-1] == len(chunks)
+        for i in range(len(numels)):
+            own = chunks[begin[i]:begin[i + 1]]
+            assert all(c[0] == i for c in own) and len(own) == -(-numels[i] // chunk)

@@ -1,0 +1,195 @@
+/*
+ * libadagc — fused AdaGC + AdamW / Lion optimizer step for AMD gfx950 (MI355X).
+ *
+ * AdaGC (arxiv 2502.11034) clips every parameter tensor's gradient against an
+ * exponential moving average of that tensor's own past (clipped) gradient
+ * norms, before the gradient enters the optimizer's moments (Sec. 4.2, Eq. 3;
+ * Alg. 1 in the appendix "Pseudocode of AdamW with AdaGC").  One call of
+ * adagc_step performs, for a whole ragged list of parameter tensors:
+ *
+ *   1. n_i = ||g_i||_2 for every tensor i                      (Sec. 4.1, Eq. 3)
+ *   2. warm-up steps (t <= T_start): one global coefficient
+ *        h = min{lambda_abs / ||g||, 1}                         (Eq. 2, Alg. 1)
+ *        gamma_i = min{gamma_i, h*n_i}  (gamma_i = h*n_i on step 1)
+ *      other steps: h_i = min{lambda_rel*gamma_i / n_i, 1},
+ *        gamma_i = beta*gamma_i + (1-beta)*||h_i g_i||          (Eq. 3, Alg. 1)
+ *   3. AdamW with the clipped gradient h_i*g_i                  (Alg. 1)
+ *      or Lion with the clipped gradient (rule of Chen et al., which the paper
+ *      cites but does not print).
+ *
+ * Conventions
+ *   - Plain C ABI.  Every pointer is marked HOST or DEVICE below.  Device
+ *     pointers belong to the GPU that was current when adagc_create ran.
+ *   - All tensor storage (params, grads, moments, bf16 copies, ema_norms) is
+ *     owned by the caller; the library never allocates or frees it.  The
+ *     context owns only its segment table, reduction scratch and per-tensor
+ *     result arrays.
+ *   - Every function returns ADAGC_OK (0) or a negative error code; nothing
+ *     throws or aborts.  Arguments are validated before any work is enqueued,
+ *     so a failed call leaves all state untouched.
+ *   - A context is not thread-safe; use one per host thread or lock around it.
+ */
+#ifndef ADAGC_H
+#define ADAGC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADAGC_OK                   0
+#define ADAGC_ERR_INVALID_ARG     (-1)  /* NULL pointer, non-positive size, bad enum, bad hyper-parameter */
+#define ADAGC_ERR_OOM             (-2)  /* host or device allocation failed */
+#define ADAGC_ERR_HIP             (-3)  /* a HIP runtime call failed (no device, launch error, ...) */
+#define ADAGC_ERR_TOO_LARGE       (-4)  /* the list needs more than 2^32-1 chunks */
+#define ADAGC_ERR_STATE           (-5)  /* call made in the wrong state (e.g. bf16 copies not set) */
+
+#define ADAGC_OPT_ADAMW 0
+#define ADAGC_OPT_LION  1
+#define ADAGC_GRAD_F32  0
+#define ADAGC_GRAD_BF16 1
+
+typedef struct adagc_ctx adagc_ctx; /* opaque; created by adagc_create, freed by adagc_destroy */
+
+/* One parameter tensor = one clipping unit (Sec. 4.2: "each parameter tensor";
+ * a fused QKV weight is one tensor).  Only its element count matters. */
+typedef struct {
+    int64_t  numel;    /* > 0 */
+    uint32_t flags;    /* must be 0 */
+    uint32_t reserved; /* must be 0 */
+} adagc_tensor_desc;
+
+typedef struct {
+    int32_t optimizer;            /* ADAGC_OPT_ADAMW or ADAGC_OPT_LION */
+    int32_t grad_dtype;           /* ADAGC_GRAD_F32 or ADAGC_GRAD_BF16 (widened exactly in-kernel) */
+    int32_t has_bf16_param_copy;  /* 1: every step also writes round-to-nearest-even bf16 copies of the
+                                     updated params to the buffers given to adagc_set_param_copies */
+    /* Launch tuning of the streaming kernels; 0 = library default for each. */
+    int32_t grid_blocks;          /* workgroups of the persistent grids */
+    int32_t unroll;               /* 128-bit vectors per lane per stream kept in flight: 1, 2 or 4 */
+    int32_t nontemporal;          /* 1 = streaming (non-temporal) loads/stores in the update kernel, 2 = off */
+} adagc_config;
+
+/* Hyper-parameters of Alg. 1, passed by the caller on every step (the learning
+ * rate schedule {eta_t} lives with the caller).  Defaults in the paper:
+ * lambda_rel 1.04, ema_beta 0.99, t_start 100, lambda_abs 1.0 (Sec. 4.2, 5.1). */
+typedef struct {
+    float   lr;            /* eta_t */
+    float   beta1, beta2;  /* AdamW: moment decay rates.  Lion: interpolation / momentum rates */
+    float   eps;           /* AdamW epsilon (added outside the square root); ignored by Lion */
+    float   weight_decay;  /* lambda_w, decoupled, applied to every tensor */
+    float   lambda_rel;    /* relative threshold of Eq. 3; +inf disables per-tensor clipping */
+    float   ema_beta;      /* beta of the EMA in Eq. 3, in [0, 1) */
+    float   lambda_abs;    /* GlobalGC threshold of the warm-up (Eq. 2); +inf disables it */
+    int32_t t_start;       /* number of warm-up steps: steps 1..t_start take the warm-up branch.
+                              0 = never (ema_norms must then be pre-filled by the caller) */
+} adagc_hyper;
+
+/* Elements per chunk of the segment table (a compile-time constant of the library). */
+int64_t adagc_chunk_elems(void);
+
+/*
+ * Host-only: cut a tensor list into chunks.  Each tensor is cut at multiples of
+ * chunk_elems counted from its own first element (the last chunk of a tensor is
+ * ragged); chunks appear in list order.  Needs no GPU.
+ *   descs        HOST  n_tensors descriptors
+ *   chunk_begin  HOST  out, n_tensors+1 entries: index of each tensor's first chunk; last = total
+ *   chunk_tensor HOST  out, capacity entries (may be NULL to only count): owning tensor of chunk c
+ *   chunk_index  HOST  out, capacity entries (may be NULL): position of chunk c inside its tensor;
+ *                      its first element is chunk_index*chunk_elems
+ *   n_chunks     HOST  out: total number of chunks
+ * Errors: INVALID_ARG (NULL descs/chunk_begin/n_chunks, n_tensors <= 0, chunk_elems <= 0,
+ * numel <= 0, non-zero flags, capacity too small while arrays are given), TOO_LARGE.
+ */
+int adagc_build_segment_table(const adagc_tensor_desc* descs, int64_t n_tensors, int64_t chunk_elems,
+                              int64_t* chunk_begin, uint32_t* chunk_tensor, uint32_t* chunk_index,
+                              int64_t capacity, int64_t* n_chunks);
+
+/*
+ * Create a context for a fixed tensor list on the current GPU: validates the
+ * descriptors, builds the segment table, allocates and uploads it together with
+ * the reduction scratch (one fp64 partial per chunk) and the per-tensor result
+ * arrays.  All device memory the library ever needs is allocated here.
+ *   out    HOST  receives the context (untouched on error)
+ *   descs  HOST  n_tensors descriptors, copied
+ *   cfg    HOST  copied
+ */
+int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int64_t n_tensors,
+                 const adagc_config* cfg);
+
+/* Free the context and its device memory.  The caller must make sure no step is still running. */
+void adagc_destroy(adagc_ctx* ctx);
+
+/*
+ * Register the bf16 parameter copies (only with has_bf16_param_copy = 1).
+ *   params_bf16  HOST array of n_tensors DEVICE pointers, tensor i holding numel_i bf16 values.
+ * The array is copied; the buffers stay owned by the caller.
+ */
+int adagc_set_param_copies(adagc_ctx* ctx, void* const* params_bf16);
+
+/*
+ * One optimizer step (one pass of the loop body of Alg. 1) over the whole list,
+ * enqueued on `stream`; returns without waiting for the GPU and allocates nothing.
+ *   params      HOST array of n_tensors DEVICE pointers, fp32, updated in place      (theta)
+ *   grads       HOST array of n_tensors DEVICE pointers, fp32 or bf16 per cfg, read only   (g_t)
+ *   exp_avg     HOST array of n_tensors DEVICE pointers, fp32, updated in place      (m)
+ *   exp_avg_sq  HOST array of n_tensors DEVICE pointers, fp32, updated in place      (v); NULL for Lion
+ *   ema_norms   DEVICE fp32[n_tensors], updated in place                              (gamma_i)
+ *   hp          HOST hyper-parameters of this step
+ *   step        1-based t of Alg. 1: drives the bias correction and the warm-up test
+ *   stream      hipStream_t (NULL = the default stream)
+ * The host pointer arrays are read during the call and may be reused afterwards.
+ * Pointers aligned to 16 bytes (8 for bf16 arrays) take the vectorised path; any
+ * other alignment is accepted and handled element by element.
+ * Non-finite gradients get no special treatment: a NaN norm compares false
+ * against the threshold, so the tensor is not clipped and the NaN propagates as
+ * it would in plain AdamW.
+ * Errors: INVALID_ARG, STATE (bf16 copies expected but not set), HIP.
+ */
+int adagc_step(adagc_ctx* ctx, void* const* params, const void* const* grads,
+               void* const* exp_avg, void* const* exp_avg_sq, float* ema_norms,
+               const adagc_hyper* hp, int64_t step, void* stream);
+
+/*
+ * Per-tensor results of the most recently enqueued step: copies them to the host
+ * and waits for `stream`.  Any of the three output arrays may be NULL.
+ *   host_norms    HOST fp32[n_tensors]   ||g_i|| before clipping
+ *   host_coefs    HOST fp32[n_tensors]   h_i (the global h during warm-up)
+ *   host_clipped  HOST u8[n_tensors]     1 where the clip was active
+ *   n_tensors     must equal the context's tensor count
+ */
+int adagc_get_norms(adagc_ctx* ctx, float* host_norms, float* host_coefs, uint8_t* host_clipped,
+                    int64_t n_tensors, void* stream);
+
+/* Number of tensors / chunks of the context's segment table (negative error code for NULL). */
+int64_t adagc_num_tensors(const adagc_ctx* ctx);
+int64_t adagc_num_chunks(const adagc_ctx* ctx);
+
+/*
+ * Read the DEVICE-resident segment table back (synchronous), in the layout of
+ * adagc_build_segment_table: chunk_begin HOST int64[n_tensors+1], chunk_tensor
+ * and chunk_index HOST uint32[adagc_num_chunks].  Any may be NULL.
+ */
+int adagc_get_segment_table(adagc_ctx* ctx, int64_t* chunk_begin, uint32_t* chunk_tensor,
+                            uint32_t* chunk_index);
+
+/*
+ * Per-kernel timing with HIP events on the step's own stream.
+ * adagc_profile_begin reserves event slots for up to max_steps steps; every
+ * following adagc_step records four events (before the norm kernel, after it,
+ * after the per-tensor finalize, after the fused update).  adagc_profile_end
+ * waits for the last recorded step, writes three durations per step in
+ * milliseconds (norm, finalize, update) to ms (HOST float[3*max_steps]), the
+ * number of recorded steps to n_steps, and releases the events.
+ */
+int adagc_profile_begin(adagc_ctx* ctx, int32_t max_steps);
+int adagc_profile_end(adagc_ctx* ctx, float* ms, int32_t* n_steps);
+
+/* Static description of an error code. */
+const char* adagc_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAGC_H */

@@ -1,0 +1,226 @@
+"""ctypes binding of libadagc: the same entry points as include/adagc.h, argument
+marshalling only.  Every step of the path runs in the library's HIP kernels; if the
+library is missing this module raises instead of falling back to anything else.
+
+PyTorch is used by callers for device memory and streams; this module only reads
+``tensor.data_ptr()``.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+ADAGC_OK = 0
+ADAGC_ERR_INVALID_ARG = -1
+ADAGC_ERR_OOM = -2
+ADAGC_ERR_HIP = -3
+ADAGC_ERR_TOO_LARGE = -4
+ADAGC_ERR_STATE = -5
+
+ADAGC_OPT_ADAMW, ADAGC_OPT_LION = 0, 1
+ADAGC_GRAD_F32, ADAGC_GRAD_BF16 = 0, 1
+
+EXPORTS = [
+    "adagc_chunk_elems", "adagc_build_segment_table", "adagc_create", "adagc_destroy",
+    "adagc_set_param_copies", "adagc_step", "adagc_get_norms", "adagc_num_tensors",
+    "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end",
+    "adagc_strerror",
+]
+
+
+class adagc_tensor_desc(ctypes.Structure):
+    _fields_ = [("numel", ctypes.c_int64), ("flags", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+class adagc_config(ctypes.Structure):
+    _fields_ = [("optimizer", ctypes.c_int32), ("grad_dtype", ctypes.c_int32),
+                ("has_bf16_param_copy", ctypes.c_int32), ("grid_blocks", ctypes.c_int32),
+                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32)]
+
+
+class adagc_hyper(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("lambda_rel", ctypes.c_float), ("ema_beta", ctypes.c_float),
+                ("lambda_abs", ctypes.c_float), ("t_start", ctypes.c_int32)]
+
+
+class AdagcError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, strerror(code), code))
+
+
+_lib = None
+
+
+def lib():
+    """Open libadagc.so (built in-tree).  Raises if it is not there: there is no fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB
+    if not os.path.exists(path):
+        raise RuntimeError("libadagc.so is not built (%s); run __graft_entry__.build() or "
+                           "python -m paper_2502_11034_amd.build" % path)
+    L = ctypes.CDLL(path)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    L.adagc_chunk_elems.restype = i64
+    L.adagc_chunk_elems.argtypes = []
+    L.adagc_build_segment_table.restype = ctypes.c_int
+    L.adagc_build_segment_table.argtypes = [vp, i64, i64, vp, vp, vp, i64, ctypes.POINTER(i64)]
+    L.adagc_create.restype = ctypes.c_int
+    L.adagc_create.argtypes = [ctypes.POINTER(vp), vp, i64, ctypes.POINTER(adagc_config)]
+    L.adagc_destroy.restype = None
+    L.adagc_destroy.argtypes = [vp]
+    L.adagc_set_param_copies.restype = ctypes.c_int
+    L.adagc_set_param_copies.argtypes = [vp, vp]
+    L.adagc_step.restype = ctypes.c_int
+    L.adagc_step.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(adagc_hyper), i64, vp]
+    L.adagc_get_norms.restype = ctypes.c_int
+    L.adagc_get_norms.argtypes = [vp, vp, vp, vp, i64, vp]
+    L.adagc_num_tensors.restype = i64
+    L.adagc_num_tensors.argtypes = [vp]
+    L.adagc_num_chunks.restype = i64
+    L.adagc_num_chunks.argtypes = [vp]
+    L.adagc_get_segment_table.restype = ctypes.c_int
+    L.adagc_get_segment_table.argtypes = [vp, vp, vp, vp]
+    L.adagc_profile_begin.restype = ctypes.c_int
+    L.adagc_profile_begin.argtypes = [vp, i32]
+    L.adagc_profile_end.restype = ctypes.c_int
+    L.adagc_profile_end.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    L.adagc_strerror.restype = ctypes.c_char_p
+    L.adagc_strerror.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+def strerror(code):
+    return lib().adagc_strerror(int(code)).decode()
+
+
+def _check(rc, where):
+    if rc != ADAGC_OK:
+        raise AdagcError(rc, where)
+
+
+def _descs(numels):
+    arr = (adagc_tensor_desc * len(numels))()
+    for i, n in enumerate(numels):
+        arr[i].numel = int(n)
+    return arr
+
+
+def ptr_array(tensors):
+    """Host array of device pointers from a list of tensors (returned as is if already one)."""
+    if isinstance(tensors, ctypes.Array):
+        return tensors
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr() if hasattr(t, "data_ptr") else int(t)
+    return arr
+
+
+def adagc_chunk_elems():
+    return int(lib().adagc_chunk_elems())
+
+
+def adagc_build_segment_table(numels, chunk_elems=None):
+    """Host-only.  Returns (chunk_begin int64[n+1], chunk_tensor uint32[c], chunk_index uint32[c])."""
+    L = lib()
+    n = len(numels)
+    chunk_elems = adagc_chunk_elems() if chunk_elems is None else int(chunk_elems)
+    descs = _descs(numels) if n else None
+    begin = np.zeros(n + 1, dtype=np.int64)
+    total = ctypes.c_int64(0)
+    _check(L.adagc_build_segment_table(ctypes.cast(descs, ctypes.c_void_p) if n else None, n, chunk_elems,
+                                       begin.ctypes.data, None, None, 0, ctypes.byref(total)),
+           "adagc_build_segment_table")
+    c = total.value
+    tensor = np.zeros(c, dtype=np.uint32)
+    index = np.zeros(c, dtype=np.uint32)
+    _check(L.adagc_build_segment_table(ctypes.cast(descs, ctypes.c_void_p), n, chunk_elems,
+                                       begin.ctypes.data, tensor.ctypes.data, index.ctypes.data, c,
+                                       ctypes.byref(total)),
+           "adagc_build_segment_table")
+    return begin, tensor, index
+
+
+class AdaGC:
+    """Owner of one adagc_ctx.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, numels, optimizer=ADAGC_OPT_ADAMW, grad_dtype=ADAGC_GRAD_F32,
+                 has_bf16_param_copy=False, grid_blocks=0, unroll=0, nontemporal=0):
+        L = lib()
+        self._ctx = ctypes.c_void_p(None)
+        self.n_tensors = len(numels)
+        self.numels = [int(n) for n in numels]
+        cfg = adagc_config(int(optimizer), int(grad_dtype), int(bool(has_bf16_param_copy)),
+                           int(grid_blocks), int(unroll), int(nontemporal))
+        descs = _descs(self.numels)
+        _check(L.adagc_create(ctypes.byref(self._ctx), ctypes.cast(descs, ctypes.c_void_p), self.n_tensors,
+                              ctypes.byref(cfg)), "adagc_create")
+        self.optimizer = int(optimizer)
+
+    # -- adagc_destroy
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            lib().adagc_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p(None)
+
+    __del__ = close
+
+    # -- adagc_set_param_copies
+    def set_param_copies(self, copies):
+        _check(lib().adagc_set_param_copies(self._ctx, ptr_array(copies)), "adagc_set_param_copies")
+
+    # -- adagc_step
+    def step(self, params, grads, exp_avg, exp_avg_sq, ema_norms, hyper, step, stream=None):
+        """params/grads/exp_avg/exp_avg_sq: lists of device tensors, or pointer arrays made once with
+        ptr_array() (saves re-marshalling long lists every step); ema_norms: device fp32[n];
+        hyper: adagc_hyper; stream: raw hipStream_t handle (int) or None for the default stream."""
+        p, g, m = (ptr_array(x) for x in (params, grads, exp_avg))
+        v = ptr_array(exp_avg_sq) if exp_avg_sq is not None else None
+        _check(lib().adagc_step(self._ctx, p, g, m, v, ema_norms.data_ptr(), ctypes.byref(hyper), int(step),
+                                ctypes.c_void_p(stream) if stream else None), "adagc_step")
+
+    # -- adagc_get_norms
+    def get_norms(self, stream=None):
+        n = self.n_tensors
+        norms = np.zeros(n, dtype=np.float32)
+        coefs = np.zeros(n, dtype=np.float32)
+        clipped = np.zeros(n, dtype=np.uint8)
+        _check(lib().adagc_get_norms(self._ctx, norms.ctypes.data, coefs.ctypes.data, clipped.ctypes.data, n,
+                                     ctypes.c_void_p(stream) if stream else None), "adagc_get_norms")
+        return norms, coefs, clipped
+
+    # -- adagc_num_chunks / adagc_get_segment_table
+    def num_chunks(self):
+        return int(lib().adagc_num_chunks(self._ctx))
+
+    def get_segment_table(self):
+        c = self.num_chunks()
+        begin = np.zeros(self.n_tensors + 1, dtype=np.int64)
+        tensor = np.zeros(c, dtype=np.uint32)
+        index = np.zeros(c, dtype=np.uint32)
+        _check(lib().adagc_get_segment_table(self._ctx, begin.ctypes.data, tensor.ctypes.data,
+                                             index.ctypes.data), "adagc_get_segment_table")
+        return begin, tensor, index
+
+    # -- adagc_profile_begin / adagc_profile_end
+    def profile_begin(self, max_steps):
+        self._prof_cap = int(max_steps)
+        _check(lib().adagc_profile_begin(self._ctx, int(max_steps)), "adagc_profile_begin")
+
+    def profile_end(self):
+        ms = np.zeros(3 * self._prof_cap, dtype=np.float32)
+        n = ctypes.c_int32(0)
+        _check(lib().adagc_profile_end(self._ctx, ms.ctypes.data, ctypes.byref(n)), "adagc_profile_end")
+        return ms[:3 * n.value].reshape(n.value, 3).copy()
+
+
+def make_hyper(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, lambda_rel=1.04,
+               ema_beta=0.99, lambda_abs=float("inf"), t_start=1):
+    return adagc_hyper(lr, beta1, beta2, eps, weight_decay, lambda_rel, ema_beta, lambda_abs, int(t_start))

@@ -1,0 +1,88 @@
+// Shared between the host API and the HIP kernels of libadagc.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "adagc.h"
+
+namespace adagc {
+
+// Elements per chunk.  Every tensor is cut at multiples of this counted from its
+// own first element, so a tensor's reduction tree depends only on its own size.
+// 16384 fp32 = 64 KiB per stream per chunk: one workgroup of 256 lanes covers a
+// full chunk with 16 independent 128-bit loads per lane per stream.
+constexpr int kChunkElems = 16384;
+constexpr int kBlock = 256;              // lanes per workgroup (4 wave64)
+constexpr int kWavesPerBlock = kBlock / 64;
+constexpr int kVecPerLane = kChunkElems / 4 / kBlock;   // 128-bit vectors per lane in a full chunk
+
+// Device-resident per-tensor record: everything a workgroup needs about the
+// tensor that owns its chunk, fetched with one scalar load burst.
+struct TensorArgs {
+    void*       param;       // fp32, in/out
+    const void* grad;        // fp32 or bf16, in
+    void*       exp_avg;     // fp32, in/out
+    void*       exp_avg_sq;  // fp32, in/out (unused by Lion)
+    void*       param_copy;  // bf16, out (optional)
+    int64_t     numel;
+    uint32_t    chunk_begin; // index of this tensor's first chunk / partial slot
+    uint32_t    chunk_count;
+    uint32_t    vec_ok;      // 1: all of this tensor's pointers allow 128-bit (64-bit for bf16) access
+    uint32_t    pad;
+};
+static_assert(sizeof(TensorArgs) == 64, "TensorArgs is one 64-byte record");
+
+struct ChunkRef {
+    uint32_t tensor;  // owning tensor
+    uint32_t index;   // position inside the tensor: first element = index * kChunkElems
+};
+
+// Scalars of the per-tensor rule (Eq. 3 / warm-up branch of Alg. 1), all widened from the
+// caller's fp32 hyper-parameters so that decisions are taken in double.
+struct RuleArgs {
+    double lambda_rel;
+    double ema_beta;
+    double lambda_abs;
+    int    first_step;   // step == 1: gamma is set, not min-ed
+};
+
+// Scalars of the elementwise update, precomputed on the host in double.
+struct UpdateArgs {
+    float  beta1, one_minus_beta1;
+    float  beta2, one_minus_beta2;
+    float  inv_bias2;      // 1 / (1 - beta2^t)
+    float  step_size;      // lr / (1 - beta1^t)
+    float  decay;          // 1 - lr * weight_decay
+    float  eps;
+    float  lr;             // Lion
+    float  weight_decay;   // Lion
+    double beta1_d, one_minus_beta1_d;   // Lion: sign decision in double
+};
+
+struct DeviceTables {
+    const ChunkRef*   chunks;
+    const TensorArgs* targs;
+    double*           partials;   // one per chunk
+    double*           sumsq;      // one per tensor
+    double*           global;     // [0] = global sum of squares, [1] = global coefficient
+    float*            norm;       // per tensor, pre-clip
+    float*            coef;       // per tensor, fp32
+    double*           coef64;     // per tensor, as computed
+    uint8_t*          flag;       // per tensor, 1 = clip active
+    uint32_t          n_chunks;
+    uint32_t          n_tensors;
+};
+
+// Resident workgroups per compute unit of the selected kernel variant (0 if the query fails).
+int sumsq_blocks_per_cu(int grad_bf16);
+int update_blocks_per_cu(int optimizer, int grad_bf16, int with_copy, int unroll, int nt);
+
+// Launchers (kernels.hip).  Each only enqueues on `stream`.
+hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int grid, hipStream_t stream);
+hipError_t launch_finalize_adagc(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
+hipError_t launch_finalize_warmup(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
+hipError_t launch_update(const DeviceTables& t, const UpdateArgs& u, int optimizer, int grad_bf16,
+                         int with_copy, int unroll, int nt, int grid, hipStream_t stream);
+
+}  // namespace adagc

@@ -1,0 +1,413 @@
+// Host side of libadagc: context, argument validation, per-step scalar preparation and
+// kernel sequencing.  See include/adagc.h for the contract of every entry point.
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "adagc_internal.h"
+
+using namespace adagc;
+
+struct adagc_ctx {
+    int          device = 0;
+    int64_t      n_tensors = 0;
+    int64_t      n_chunks = 0;
+    adagc_config cfg{};
+    int          grid_norm = 0;     // workgroups of the norm kernel
+    int          grid_update = 0;   // workgroups of the update kernel
+    int          unroll = 0;
+    int          nontemporal = 0;
+
+    std::vector<int64_t>    numel;
+    std::vector<int64_t>    chunk_begin;      // n_tensors + 1
+    std::vector<void*>      param_copies;     // device pointers, empty until set
+    std::vector<TensorArgs> cached_args;      // what the device table currently holds
+    std::vector<TensorArgs> scratch_args;     // rebuilt on every step, then compared
+    bool                    args_uploaded = false;
+
+    void*        slab = nullptr;              // single device allocation, carved below
+    DeviceTables tables{};
+    TensorArgs*  d_targs = nullptr;
+    TensorArgs*  staging = nullptr;           // pinned host mirror for the async upload
+    hipEvent_t   upload_done = nullptr;
+    bool         upload_pending = false;
+
+    std::vector<hipEvent_t> prof_events;      // 4 per step while profiling
+    int32_t                 prof_capacity = 0;
+    int32_t                 prof_steps = 0;
+};
+
+namespace {
+
+struct DeviceGuard {
+    int  prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+    }
+    ~DeviceGuard()
+    {
+        int cur = -1;
+        if (ok && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+    }
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bool hyper_ok(const adagc_hyper& h, int optimizer)
+{
+    auto unit = [](float b) { return b >= 0.0f && b < 1.0f; };   // false for NaN
+    if (!std::isfinite(h.lr) || !std::isfinite(h.weight_decay)) return false;
+    if (!unit(h.beta1) || !unit(h.beta2) || !unit(h.ema_beta)) return false;
+    if (optimizer == ADAGC_OPT_ADAMW && !(h.eps >= 0.0f && std::isfinite(h.eps))) return false;
+    if (!(h.lambda_rel >= 0.0f)) return false;    // +inf allowed, NaN not
+    if (!(h.lambda_abs > 0.0f)) return false;     // +inf allowed, NaN not
+    if (h.t_start < 0) return false;
+    return true;
+}
+
+void free_ctx(adagc_ctx* c)
+{
+    if (!c) return;
+    for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+    if (c->upload_done) (void)hipEventDestroy(c->upload_done);
+    if (c->staging) (void)hipHostFree(c->staging);
+    if (c->slab) (void)hipFree(c->slab);
+    delete c;
+}
+
+}  // namespace
+
+extern "C" int64_t adagc_chunk_elems(void) { return kChunkElems; }
+
+extern "C" const char* adagc_strerror(int code)
+{
+    switch (code) {
+    case ADAGC_OK: return "ok";
+    case ADAGC_ERR_INVALID_ARG: return "invalid argument";
+    case ADAGC_ERR_OOM: return "out of memory";
+    case ADAGC_ERR_HIP: return "HIP runtime error";
+    case ADAGC_ERR_TOO_LARGE: return "tensor list needs too many chunks";
+    case ADAGC_ERR_STATE: return "call made in the wrong state";
+    default: return "unknown error code";
+    }
+}
+
+extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int64_t n_tensors,
+                            const adagc_config* cfg)
+{
+    if (!out || !descs || !cfg || n_tensors <= 0) return ADAGC_ERR_INVALID_ARG;
+    if (cfg->optimizer != ADAGC_OPT_ADAMW && cfg->optimizer != ADAGC_OPT_LION) return ADAGC_ERR_INVALID_ARG;
+    if (cfg->grad_dtype != ADAGC_GRAD_F32 && cfg->grad_dtype != ADAGC_GRAD_BF16) return ADAGC_ERR_INVALID_ARG;
+    if (cfg->has_bf16_param_copy != 0 && cfg->has_bf16_param_copy != 1) return ADAGC_ERR_INVALID_ARG;
+    if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 2) return ADAGC_ERR_INVALID_ARG;
+    if (cfg->unroll != 0 && cfg->unroll != 1 && cfg->unroll != 2 && cfg->unroll != 4)
+        return ADAGC_ERR_INVALID_ARG;
+
+    adagc_ctx* c = new (std::nothrow) adagc_ctx;
+    if (!c) return ADAGC_ERR_OOM;
+    int rc = ADAGC_OK;
+    std::vector<uint32_t> chunk_tensor, chunk_index;
+    try {
+        c->chunk_begin.resize((size_t)n_tensors + 1);
+        int64_t n_chunks = 0;
+        rc = adagc_build_segment_table(descs, n_tensors, kChunkElems, c->chunk_begin.data(), nullptr,
+                                       nullptr, 0, &n_chunks);
+        if (rc != ADAGC_OK) { free_ctx(c); return rc; }
+        chunk_tensor.resize((size_t)n_chunks);
+        chunk_index.resize((size_t)n_chunks);
+        rc = adagc_build_segment_table(descs, n_tensors, kChunkElems, c->chunk_begin.data(),
+                                       chunk_tensor.data(), chunk_index.data(), n_chunks, &n_chunks);
+        if (rc != ADAGC_OK) { free_ctx(c); return rc; }
+        c->n_tensors = n_tensors;
+        c->n_chunks = n_chunks;
+        c->cfg = *cfg;
+        c->numel.resize((size_t)n_tensors);
+        for (int64_t i = 0; i < n_tensors; ++i) c->numel[(size_t)i] = descs[i].numel;
+        c->cached_args.assign((size_t)n_tensors, TensorArgs{});
+        c->scratch_args.assign((size_t)n_tensors, TensorArgs{});
+    } catch (const std::bad_alloc&) {
+        free_ctx(c);
+        return ADAGC_ERR_OOM;
+    }
+
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&c->device) != hipSuccess ||
+        hipGetDeviceProperties(&prop, c->device) != hipSuccess) {
+        free_ctx(c);
+        return ADAGC_ERR_HIP;
+    }
+    const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    c->unroll = cfg->unroll ? cfg->unroll : 2;
+    c->nontemporal = cfg->nontemporal ? (cfg->nontemporal == 1) : 0;
+    // Persistent grids: exactly as many workgroups as can be resident at once (so that none waits
+    // for another to finish), never more than there are chunks.
+    const int bf16g = cfg->grad_dtype == ADAGC_GRAD_BF16;
+    int occ_norm = sumsq_blocks_per_cu(bf16g);
+    int occ_update = update_blocks_per_cu(cfg->optimizer, bf16g, cfg->has_bf16_param_copy, c->unroll, c->nontemporal);
+    if (occ_norm <= 0) occ_norm = 4;
+    if (occ_update <= 0) occ_update = 4;
+    const int64_t want_norm = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : (int64_t)cus * occ_norm;
+    const int64_t want_update = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : (int64_t)cus * occ_update;
+    c->grid_norm = (int)(want_norm < c->n_chunks ? want_norm : c->n_chunks);
+    c->grid_update = (int)(want_update < c->n_chunks ? want_update : c->n_chunks);
+
+    // One slab, carved into 256-byte aligned arrays.
+    const size_t nt = (size_t)n_tensors, nc = (size_t)c->n_chunks;
+    size_t off = 0;
+    auto carve = [&off](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t o_chunks = carve(nc * sizeof(ChunkRef));
+    const size_t o_targs = carve(nt * sizeof(TensorArgs));
+    const size_t o_partials = carve(nc * sizeof(double));
+    const size_t o_sumsq = carve(nt * sizeof(double));
+    const size_t o_global = carve(2 * sizeof(double));
+    const size_t o_coef64 = carve(nt * sizeof(double));
+    const size_t o_norm = carve(nt * sizeof(float));
+    const size_t o_coef = carve(nt * sizeof(float));
+    const size_t o_flag = carve(nt);
+    const size_t slab_bytes = off;
+
+    hipError_t e = hipMalloc(&c->slab, slab_bytes);
+    if (e != hipSuccess) { free_ctx(c); return e == hipErrorOutOfMemory ? ADAGC_ERR_OOM : ADAGC_ERR_HIP; }
+    char* base = static_cast<char*>(c->slab);
+    if (hipMemset(c->slab, 0, slab_bytes) != hipSuccess) { free_ctx(c); return ADAGC_ERR_HIP; }
+
+    std::vector<ChunkRef> refs;
+    try {
+        refs.resize(nc);
+    } catch (const std::bad_alloc&) { free_ctx(c); return ADAGC_ERR_OOM; }
+    for (size_t k = 0; k < nc; ++k) refs[k] = ChunkRef{chunk_tensor[k], chunk_index[k]};
+    if (hipMemcpy(base + o_chunks, refs.data(), nc * sizeof(ChunkRef), hipMemcpyHostToDevice) != hipSuccess) {
+        free_ctx(c);
+        return ADAGC_ERR_HIP;
+    }
+    if (hipHostMalloc(reinterpret_cast<void**>(&c->staging), nt * sizeof(TensorArgs), hipHostMallocDefault) !=
+            hipSuccess ||
+        hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming) != hipSuccess) {
+        free_ctx(c);
+        return ADAGC_ERR_HIP;
+    }
+
+    c->d_targs = reinterpret_cast<TensorArgs*>(base + o_targs);
+    DeviceTables& t = c->tables;
+    t.chunks = reinterpret_cast<const ChunkRef*>(base + o_chunks);
+    t.targs = c->d_targs;
+    t.partials = reinterpret_cast<double*>(base + o_partials);
+    t.sumsq = reinterpret_cast<double*>(base + o_sumsq);
+    t.global = reinterpret_cast<double*>(base + o_global);
+    t.coef64 = reinterpret_cast<double*>(base + o_coef64);
+    t.norm = reinterpret_cast<float*>(base + o_norm);
+    t.coef = reinterpret_cast<float*>(base + o_coef);
+    t.flag = reinterpret_cast<uint8_t*>(base + o_flag);
+    t.n_chunks = (uint32_t)c->n_chunks;
+    t.n_tensors = (uint32_t)c->n_tensors;
+
+    *out = c;
+    return ADAGC_OK;
+}
+
+extern "C" void adagc_destroy(adagc_ctx* ctx)
+{
+    if (!ctx) return;
+    DeviceGuard guard(ctx->device);
+    free_ctx(ctx);
+}
+
+extern "C" int64_t adagc_num_tensors(const adagc_ctx* ctx) { return ctx ? ctx->n_tensors : ADAGC_ERR_INVALID_ARG; }
+extern "C" int64_t adagc_num_chunks(const adagc_ctx* ctx) { return ctx ? ctx->n_chunks : ADAGC_ERR_INVALID_ARG; }
+
+extern "C" int adagc_set_param_copies(adagc_ctx* ctx, void* const* params_bf16)
+{
+    if (!ctx || !params_bf16) return ADAGC_ERR_INVALID_ARG;
+    if (!ctx->cfg.has_bf16_param_copy) return ADAGC_ERR_STATE;
+    for (int64_t i = 0; i < ctx->n_tensors; ++i)
+        if (!params_bf16[i]) return ADAGC_ERR_INVALID_ARG;
+    try {
+        ctx->param_copies.assign(params_bf16, params_bf16 + ctx->n_tensors);
+    } catch (const std::bad_alloc&) { return ADAGC_ERR_OOM; }
+    return ADAGC_OK;
+}
+
+extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const* grads,
+                          void* const* exp_avg, void* const* exp_avg_sq, float* ema_norms,
+                          const adagc_hyper* hp, int64_t step, void* stream_v)
+{
+    if (!ctx || !params || !grads || !exp_avg || !ema_norms || !hp || step < 1) return ADAGC_ERR_INVALID_ARG;
+    const bool adamw = ctx->cfg.optimizer == ADAGC_OPT_ADAMW;
+    const bool bf16g = ctx->cfg.grad_dtype == ADAGC_GRAD_BF16;
+    const bool copy = ctx->cfg.has_bf16_param_copy != 0;
+    if (adamw && !exp_avg_sq) return ADAGC_ERR_INVALID_ARG;
+    if (!hyper_ok(*hp, ctx->cfg.optimizer)) return ADAGC_ERR_INVALID_ARG;
+    if (copy && ctx->param_copies.size() != (size_t)ctx->n_tensors) return ADAGC_ERR_STATE;
+
+    // Rebuild the per-tensor records from the caller's pointer arrays.
+    const uintptr_t grad_align = bf16g ? 8 : 16;
+    for (int64_t i = 0; i < ctx->n_tensors; ++i) {
+        TensorArgs& a = ctx->scratch_args[(size_t)i];
+        a.param = params[i];
+        a.grad = grads[i];
+        a.exp_avg = exp_avg[i];
+        a.exp_avg_sq = adamw ? exp_avg_sq[i] : nullptr;
+        a.param_copy = copy ? ctx->param_copies[(size_t)i] : nullptr;
+        if (!a.param || !a.grad || !a.exp_avg || (adamw && !a.exp_avg_sq)) return ADAGC_ERR_INVALID_ARG;
+        a.numel = ctx->numel[(size_t)i];
+        a.chunk_begin = (uint32_t)ctx->chunk_begin[(size_t)i];
+        a.chunk_count = (uint32_t)(ctx->chunk_begin[(size_t)i + 1] - ctx->chunk_begin[(size_t)i]);
+        a.vec_ok = (aligned(a.param, 16) && aligned(a.exp_avg, 16) && aligned(a.grad, grad_align) &&
+                    (!adamw || aligned(a.exp_avg_sq, 16)) && (!copy || aligned(a.param_copy, 8)))
+                       ? 1u : 0u;
+        a.pad = 0;
+    }
+
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const size_t args_bytes = (size_t)ctx->n_tensors * sizeof(TensorArgs);
+
+    if (!ctx->args_uploaded ||
+        std::memcmp(ctx->scratch_args.data(), ctx->cached_args.data(), args_bytes) != 0) {
+        // The pinned staging buffer may still be the source of an earlier asynchronous upload.
+        if (ctx->upload_pending && hipEventSynchronize(ctx->upload_done) != hipSuccess) return ADAGC_ERR_HIP;
+        std::memcpy(ctx->staging, ctx->scratch_args.data(), args_bytes);
+        if (hipMemcpyAsync(ctx->d_targs, ctx->staging, args_bytes, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipEventRecord(ctx->upload_done, stream) != hipSuccess)
+            return ADAGC_ERR_HIP;
+        ctx->upload_pending = true;
+        ctx->cached_args.swap(ctx->scratch_args);
+        ctx->args_uploaded = true;
+    }
+
+    // Scalars of this step, in double from the caller's fp32 values.
+    const double lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, wd = hp->weight_decay;
+    const double t = (double)step;
+    RuleArgs r;
+    r.lambda_rel = (double)hp->lambda_rel;
+    r.ema_beta = (double)hp->ema_beta;
+    r.lambda_abs = (double)hp->lambda_abs;
+    r.first_step = (step == 1) ? 1 : 0;
+    UpdateArgs u;
+    u.beta1 = hp->beta1;
+    u.one_minus_beta1 = (float)(1.0 - b1);
+    u.beta2 = hp->beta2;
+    u.one_minus_beta2 = (float)(1.0 - b2);
+    u.inv_bias2 = (float)(1.0 / (1.0 - std::pow(b2, t)));
+    u.step_size = (float)(lr / (1.0 - std::pow(b1, t)));
+    u.decay = (float)(1.0 - lr * wd);
+    u.eps = hp->eps;
+    u.lr = hp->lr;
+    u.weight_decay = hp->weight_decay;
+    u.beta1_d = b1;
+    u.one_minus_beta1_d = 1.0 - b1;
+
+    const bool warmup = (step - 1) < (int64_t)hp->t_start;   // steps 1..t_start
+    const bool prof = ctx->prof_steps < ctx->prof_capacity;
+    hipEvent_t* ev = prof ? &ctx->prof_events[(size_t)ctx->prof_steps * 4] : nullptr;
+
+    if (prof && hipEventRecord(ev[0], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (launch_sumsq_partials(ctx->tables, bf16g, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (prof && hipEventRecord(ev[1], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    hipError_t e = warmup ? launch_finalize_warmup(ctx->tables, ema_norms, r, stream)
+                          : launch_finalize_adagc(ctx->tables, ema_norms, r, stream);
+    if (e != hipSuccess) return ADAGC_ERR_HIP;
+    if (prof && hipEventRecord(ev[2], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (launch_update(ctx->tables, u, ctx->cfg.optimizer, bf16g, copy, ctx->unroll, ctx->nontemporal,
+                      ctx->grid_update, stream) != hipSuccess)
+        return ADAGC_ERR_HIP;
+    if (prof) {
+        if (hipEventRecord(ev[3], stream) != hipSuccess) return ADAGC_ERR_HIP;
+        ctx->prof_steps++;
+    }
+    return ADAGC_OK;
+}
+
+extern "C" int adagc_get_norms(adagc_ctx* ctx, float* host_norms, float* host_coefs, uint8_t* host_clipped,
+                               int64_t n_tensors, void* stream_v)
+{
+    if (!ctx || n_tensors != ctx->n_tensors) return ADAGC_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const size_t n = (size_t)n_tensors;
+    const DeviceTables& t = ctx->tables;
+    if (host_norms && hipMemcpyAsync(host_norms, t.norm, n * sizeof(float), hipMemcpyDeviceToHost, stream) != hipSuccess)
+        return ADAGC_ERR_HIP;
+    if (host_coefs && hipMemcpyAsync(host_coefs, t.coef, n * sizeof(float), hipMemcpyDeviceToHost, stream) != hipSuccess)
+        return ADAGC_ERR_HIP;
+    if (host_clipped && hipMemcpyAsync(host_clipped, t.flag, n, hipMemcpyDeviceToHost, stream) != hipSuccess)
+        return ADAGC_ERR_HIP;
+    return hipStreamSynchronize(stream) == hipSuccess ? ADAGC_OK : ADAGC_ERR_HIP;
+}
+
+extern "C" int adagc_get_segment_table(adagc_ctx* ctx, int64_t* chunk_begin, uint32_t* chunk_tensor,
+                                       uint32_t* chunk_index)
+{
+    if (!ctx) return ADAGC_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    if (chunk_begin) std::memcpy(chunk_begin, ctx->chunk_begin.data(), ((size_t)ctx->n_tensors + 1) * sizeof(int64_t));
+    if (chunk_tensor || chunk_index) {
+        std::vector<ChunkRef> refs;
+        try {
+            refs.resize((size_t)ctx->n_chunks);
+        } catch (const std::bad_alloc&) { return ADAGC_ERR_OOM; }
+        if (hipMemcpy(refs.data(), ctx->tables.chunks, refs.size() * sizeof(ChunkRef), hipMemcpyDeviceToHost) !=
+            hipSuccess)
+            return ADAGC_ERR_HIP;
+        for (size_t k = 0; k < refs.size(); ++k) {
+            if (chunk_tensor) chunk_tensor[k] = refs[k].tensor;
+            if (chunk_index) chunk_index[k] = refs[k].index;
+        }
+    }
+    return ADAGC_OK;
+}
+
+extern "C" int adagc_profile_begin(adagc_ctx* ctx, int32_t max_steps)
+{
+    if (!ctx || max_steps <= 0 || max_steps > 4096) return ADAGC_ERR_INVALID_ARG;
+    if (!ctx->prof_events.empty()) return ADAGC_ERR_STATE;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    try {
+        ctx->prof_events.reserve((size_t)max_steps * 4);
+    } catch (const std::bad_alloc&) { return ADAGC_ERR_OOM; }
+    for (int32_t k = 0; k < max_steps * 4; ++k) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) {
+            for (hipEvent_t x : ctx->prof_events) (void)hipEventDestroy(x);
+            ctx->prof_events.clear();
+            return ADAGC_ERR_HIP;
+        }
+        ctx->prof_events.push_back(e);
+    }
+    ctx->prof_capacity = max_steps;
+    ctx->prof_steps = 0;
+    return ADAGC_OK;
+}
+
+extern "C" int adagc_profile_end(adagc_ctx* ctx, float* ms, int32_t* n_steps)
+{
+    if (!ctx || !ms || !n_steps) return ADAGC_ERR_INVALID_ARG;
+    if (ctx->prof_events.empty()) return ADAGC_ERR_STATE;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    int rc = ADAGC_OK;
+    const int32_t n = ctx->prof_steps;
+    if (n > 0 && hipEventSynchronize(ctx->prof_events[(size_t)n * 4 - 1]) != hipSuccess) rc = ADAGC_ERR_HIP;
+    for (int32_t s = 0; s < n && rc == ADAGC_OK; ++s)
+        for (int k = 0; k < 3; ++k)
+            if (hipEventElapsedTime(&ms[s * 3 + k], ctx->prof_events[(size_t)s * 4 + k],
+                                    ctx->prof_events[(size_t)s * 4 + k + 1]) != hipSuccess)
+                rc = ADAGC_ERR_HIP;
+    for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+    ctx->prof_events.clear();
+    ctx->prof_capacity = 0;
+    ctx->prof_steps = 0;
+    *n_steps = n;
+    return rc;
+}

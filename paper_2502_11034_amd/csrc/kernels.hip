@@ -1,0 +1,499 @@
+// HIP kernels of libadagc for gfx950 (wave64).
+//
+//   sumsq_partials_kernel   per chunk:   sum of g^2 in fp64                        (Sec. 4.1, Eq. 3)
+//   finalize_adagc_kernel   per tensor:  norm, h_i, clip flag, EMA update          (Eq. 3, Alg. 1)
+//   tensor_sumsq_kernel / global_coef_kernel / finalize_warmup_kernel
+//                           warm-up branch: GlobalGC + running minimum             (Eq. 2, Alg. 1)
+//   update_kernel           per chunk:   clipped gradient into AdamW / Lion        (Alg. 1)
+//
+// Nothing here is a dense contraction, so there is no MFMA: the streaming kernels
+// are bound by HBM and are built around 128-bit coalesced accesses with many
+// independent loads in flight per lane.  Reductions are deterministic: a lane
+// accumulates its elements in index order, lanes are combined with a fixed DPP
+// tree, waves through LDS in wave order, chunks by a second kernel in slot order.
+// No floating-point atomics anywhere.
+
+#include "adagc_internal.h"
+
+namespace adagc {
+namespace {
+
+// Native clang vectors (the nontemporal builtins do not take HIP's struct vector types).
+typedef float    f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------------------------------------
+// wave64 reduction in double: rotate-and-add inside each row of 16 lanes with DPP, then read the
+// four row totals with readlane and add them in row order.
+
+template <int DPP_CTRL>
+__device__ __forceinline__ double dpp_mov(double x)
+{
+    int lo = __double2loint(x);
+    int hi = __double2hiint(x);
+    lo = __builtin_amdgcn_update_dpp(0, lo, DPP_CTRL, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(0, hi, DPP_CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double readlane_f64(double x, int lane)
+{
+    int lo = __builtin_amdgcn_readlane(__double2loint(x), lane);
+    int hi = __builtin_amdgcn_readlane(__double2hiint(x), lane);
+    return __hiloint2double(hi, lo);
+}
+
+// All 64 lanes must be active.  Returns the same value in every lane.
+__device__ __forceinline__ double wave_sum_f64(double x)
+{
+    x += dpp_mov<0x128>(x);  // row_ror:8
+    x += dpp_mov<0x124>(x);  // row_ror:4
+    x += dpp_mov<0x122>(x);  // row_ror:2
+    x += dpp_mov<0x121>(x);  // row_ror:1
+    double r0 = readlane_f64(x, 0);
+    double r1 = readlane_f64(x, 16);
+    double r2 = readlane_f64(x, 32);
+    double r3 = readlane_f64(x, 48);
+    return ((r0 + r1) + r2) + r3;
+}
+
+// ---------------------------------------------------------------------------------------------
+// loads / stores
+
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const T* p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void st(T* p, T v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Four consecutive gradient elements, widened to fp32.  `vec` counts groups of four from `base`.
+template <bool BF16, bool NT>
+__device__ __forceinline__ f32x4 load_grad4(const void* base, int vec)
+{
+    if constexpr (BF16) {
+        u32x2 r = ld<NT>(reinterpret_cast<const u32x2*>(base) + vec);
+        f32x4 o;
+        o.x = __uint_as_float(r.x << 16);
+        o.y = __uint_as_float(r.x & 0xFFFF0000u);
+        o.z = __uint_as_float(r.y << 16);
+        o.w = __uint_as_float(r.y & 0xFFFF0000u);
+        return o;
+    } else {
+        return ld<NT>(reinterpret_cast<const f32x4*>(base) + vec);
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_grad1(const void* base, int j)
+{
+    if constexpr (BF16) return bf16_bits_to_float(reinterpret_cast<const uint16_t*>(base)[j]);
+    else return reinterpret_cast<const float*>(base)[j];
+}
+
+template <bool BF16>
+__device__ __forceinline__ const void* grad_chunk_ptr(const void* grad, int64_t first)
+{
+    if constexpr (BF16) return reinterpret_cast<const uint16_t*>(grad) + first;
+    else return reinterpret_cast<const float*>(grad) + first;
+}
+
+// fp32 -> bf16, round to nearest even (add half an ulp of the kept part, plus the parity bit).
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    uint32_t quiet_nan = (u >> 16) | 0x40u;
+    return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? quiet_nan : rounded;
+}
+
+__device__ __forceinline__ u32x2 pack_bf16x4(f32x4 v)
+{
+    u32x2 o;
+    o.x = float_to_bf16_bits(v.x) | (float_to_bf16_bits(v.y) << 16);
+    o.y = float_to_bf16_bits(v.z) | (float_to_bf16_bits(v.w) << 16);
+    return o;
+}
+
+struct ChunkView {
+    uint32_t tensor;
+    int64_t  first;   // first element of the chunk inside its tensor
+    int      len;     // 1..kChunkElems
+};
+
+__device__ __forceinline__ ChunkView chunk_view(const DeviceTables& t, uint32_t c)
+{
+    ChunkRef ck = t.chunks[c];
+    ChunkView v;
+    v.tensor = ck.tensor;
+    v.first = (int64_t)ck.index * kChunkElems;
+    int64_t rest = t.targs[ck.tensor].numel - v.first;
+    v.len = rest < (int64_t)kChunkElems ? (int)rest : kChunkElems;
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// K1: one fp64 partial sum of squares per chunk.  Persistent grid: workgroup b takes chunks
+// b, b+grid, b+2*grid, ... so that neighbouring workgroups stream neighbouring memory.
+
+__device__ __forceinline__ void acc4(double (&acc)[4], f32x4 g)
+{
+    double x = (double)g.x, y = (double)g.y, z = (double)g.z, w = (double)g.w;
+    acc[0] = fma(x, x, acc[0]);
+    acc[1] = fma(y, y, acc[1]);
+    acc[2] = fma(z, z, acc[2]);
+    acc[3] = fma(w, w, acc[3]);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void sumsq_partials_kernel(DeviceTables t)
+{
+    __shared__ double wave_sums[kWavesPerBlock];
+    const int tid = threadIdx.x;
+
+    for (uint32_t c = blockIdx.x; c < t.n_chunks; c += gridDim.x) {
+        const ChunkView cv = chunk_view(t, c);
+        const TensorArgs& ta = t.targs[cv.tensor];
+        const void* g = grad_chunk_ptr<BF16>(ta.grad, cv.first);
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+
+        if (ta.vec_ok) {
+            if (cv.len == kChunkElems) {
+                f32x4 r[kVecPerLane];
+#pragma unroll
+                for (int u = 0; u < kVecPerLane; ++u) r[u] = load_grad4<BF16, false>(g, u * kBlock + tid);
+#pragma unroll
+                for (int u = 0; u < kVecPerLane; ++u) acc4(acc, r[u]);
+            } else {
+                const int nvec = cv.len >> 2;
+                for (int v = tid; v < nvec; v += kBlock) acc4(acc, load_grad4<BF16, false>(g, v));
+                const int j = (nvec << 2) + tid;
+                if (j < cv.len) {
+                    double x = (double)load_grad1<BF16>(g, j);
+                    acc[0] = fma(x, x, acc[0]);
+                }
+            }
+        } else {
+            for (int j = tid; j < cv.len; j += kBlock) {
+                double x = (double)load_grad1<BF16>(g, j);
+                acc[0] = fma(x, x, acc[0]);
+            }
+        }
+
+        double s = wave_sum_f64((acc[0] + acc[1]) + (acc[2] + acc[3]));
+        if ((tid & 63) == 0) wave_sums[tid >> 6] = s;
+        __syncthreads();
+        if (tid == 0) {
+            double b = wave_sums[0];
+#pragma unroll
+            for (int w = 1; w < kWavesPerBlock; ++w) b += wave_sums[w];
+            t.partials[c] = b;
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K2: per-tensor scalars.  One wave per tensor sums that tensor's partial slots in slot order.
+
+__device__ __forceinline__ double tensor_sumsq(const DeviceTables& t, uint32_t i)
+{
+    const uint32_t begin = t.targs[i].chunk_begin;
+    const uint32_t count = t.targs[i].chunk_count;
+    double acc = 0.0;
+    for (uint32_t k = threadIdx.x; k < count; k += 64) acc += t.partials[begin + k];
+    return wave_sum_f64(acc);
+}
+
+// AdaGC branch of Alg. 1 / Eq. 3, in double, with separately rounded operations.
+__global__ __launch_bounds__(64) void finalize_adagc_kernel(DeviceTables t, float* ema, RuleArgs r)
+{
+    const uint32_t i = blockIdx.x;
+    const double s = tensor_sumsq(t, i);
+    if (threadIdx.x != 0) return;
+
+    const double norm = sqrt(s);
+    const double gamma_prev = (double)ema[i];
+    const double threshold = __dmul_rn(r.lambda_rel, gamma_prev);
+    const bool active = norm > threshold;                 // strict; false if either side is NaN
+    const double h = active ? __ddiv_rn(threshold, norm) : 1.0;
+    const double clipped_norm = active ? threshold : norm;
+    const double gamma_new = __dadd_rn(__dmul_rn(r.ema_beta, gamma_prev),
+                                       __dmul_rn(__dsub_rn(1.0, r.ema_beta), clipped_norm));
+    t.sumsq[i] = s;
+    t.norm[i] = (float)norm;
+    t.coef[i] = (float)h;
+    t.coef64[i] = h;
+    t.flag[i] = active ? 1 : 0;
+    ema[i] = (float)gamma_new;
+}
+
+// Warm-up branch, stage 1: per-tensor sum of squares only.
+__global__ __launch_bounds__(64) void tensor_sumsq_kernel(DeviceTables t)
+{
+    const uint32_t i = blockIdx.x;
+    const double s = tensor_sumsq(t, i);
+    if (threadIdx.x == 0) t.sumsq[i] = s;
+}
+
+// Warm-up branch, stage 2: global norm over all tensors (fixed order) and the coefficient of Eq. 2.
+__global__ __launch_bounds__(kBlock) void global_coef_kernel(DeviceTables t, RuleArgs r)
+{
+    __shared__ double wave_sums[kWavesPerBlock];
+    const int tid = threadIdx.x;
+    double acc = 0.0;
+    for (uint32_t i = tid; i < t.n_tensors; i += kBlock) acc += t.sumsq[i];
+    double s = wave_sum_f64(acc);
+    if ((tid & 63) == 0) wave_sums[tid >> 6] = s;
+    __syncthreads();
+    if (tid == 0) {
+        double total = wave_sums[0];
+#pragma unroll
+        for (int w = 1; w < kWavesPerBlock; ++w) total += wave_sums[w];
+        const double gnorm = sqrt(total);
+        const bool active = gnorm > r.lambda_abs;
+        t.global[0] = total;
+        t.global[1] = active ? __ddiv_rn(r.lambda_abs, gnorm) : 1.0;
+    }
+}
+
+// Warm-up branch, stage 3: gamma_i = min{gamma_i, h*n_i}, or h*n_i on the first step.
+__global__ __launch_bounds__(kBlock) void finalize_warmup_kernel(DeviceTables t, float* ema, RuleArgs r)
+{
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= t.n_tensors) return;
+    const double h = t.global[1];
+    const double norm = sqrt(t.sumsq[i]);
+    const double clipped_norm = __dmul_rn(h, norm);
+    const double gamma_prev = (double)ema[i];
+    double gamma_new = clipped_norm;
+    if (!r.first_step) gamma_new = clipped_norm < gamma_prev ? clipped_norm : gamma_prev;
+    t.norm[i] = (float)norm;
+    t.coef[i] = (float)h;
+    t.coef64[i] = h;
+    t.flag[i] = (h < 1.0) ? 1 : 0;
+    ema[i] = (float)gamma_new;
+}
+
+// ---------------------------------------------------------------------------------------------
+// K3: clipped gradient into the optimizer, elementwise in fp32.
+
+struct ElemState {
+    float p, m, v;
+};
+
+// AdamW statements of Alg. 1 with the bias corrections folded into two host-computed scalars.
+__device__ __forceinline__ void adamw_elem(const UpdateArgs& a, float h, float g, ElemState& s)
+{
+    const float gh = h * g;
+    s.m = fmaf(a.one_minus_beta1, gh, a.beta1 * s.m);
+    s.v = fmaf(a.one_minus_beta2 * gh, gh, a.beta2 * s.v);
+    const float denom = sqrtf(s.v * a.inv_bias2) + a.eps;
+    s.p = fmaf(s.p, a.decay, -((a.step_size * s.m) / denom));
+}
+
+// Lion.  The sign is a discrete decision, so the interpolation c is evaluated in double with
+// separately rounded operations; everything stored is fp32.
+__device__ __forceinline__ void lion_elem(const UpdateArgs& a, float h, double h64, float g, ElemState& s)
+{
+    const double c = __dadd_rn(__dmul_rn(a.beta1_d, (double)s.m),
+                               __dmul_rn(a.one_minus_beta1_d, __dmul_rn(h64, (double)g)));
+    const float sgn = (c > 0.0) ? 1.0f : ((c < 0.0) ? -1.0f : 0.0f);
+    const float gh = h * g;
+    s.p = fmaf(-a.lr, fmaf(a.weight_decay, s.p, sgn), s.p);
+    s.m = fmaf(a.one_minus_beta2, gh, a.beta2 * s.m);
+}
+
+template <int OPT>
+__device__ __forceinline__ void apply_elem(const UpdateArgs& a, float h, double h64, float g, ElemState& s)
+{
+    if constexpr (OPT == ADAGC_OPT_ADAMW) adamw_elem(a, h, g, s);
+    else lion_elem(a, h, h64, g, s);
+}
+
+template <int OPT>
+__device__ __forceinline__ void apply_vec(const UpdateArgs& a, float h, double h64, f32x4 g, f32x4& p,
+                                          f32x4& m, f32x4& v)
+{
+    ElemState s;
+    s = {p.x, m.x, v.x}; apply_elem<OPT>(a, h, h64, g.x, s); p.x = s.p; m.x = s.m; v.x = s.v;
+    s = {p.y, m.y, v.y}; apply_elem<OPT>(a, h, h64, g.y, s); p.y = s.p; m.y = s.m; v.y = s.v;
+    s = {p.z, m.z, v.z}; apply_elem<OPT>(a, h, h64, g.z, s); p.z = s.p; m.z = s.m; v.z = s.v;
+    s = {p.w, m.w, v.w}; apply_elem<OPT>(a, h, h64, g.w, s); p.w = s.p; m.w = s.m; v.w = s.v;
+}
+
+template <int OPT, bool BF16G, bool COPY, int U, bool NT>
+__global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateArgs a)
+{
+    constexpr bool kHasV = (OPT == ADAGC_OPT_ADAMW);
+    const int tid = threadIdx.x;
+
+    for (uint32_t c = blockIdx.x; c < t.n_chunks; c += gridDim.x) {
+        const ChunkView cv = chunk_view(t, c);
+        const TensorArgs& ta = t.targs[cv.tensor];
+        const float h = t.coef[cv.tensor];
+        const double h64 = (OPT == ADAGC_OPT_LION) ? t.coef64[cv.tensor] : 1.0;
+
+        const void* g = grad_chunk_ptr<BF16G>(ta.grad, cv.first);
+        float* p = reinterpret_cast<float*>(ta.param) + cv.first;
+        float* m = reinterpret_cast<float*>(ta.exp_avg) + cv.first;
+        float* v = kHasV ? reinterpret_cast<float*>(ta.exp_avg_sq) + cv.first : nullptr;
+        uint16_t* pc = COPY ? reinterpret_cast<uint16_t*>(ta.param_copy) + cv.first : nullptr;
+
+        if (ta.vec_ok) {
+            f32x4* p4 = reinterpret_cast<f32x4*>(p);
+            f32x4* m4 = reinterpret_cast<f32x4*>(m);
+            f32x4* v4 = reinterpret_cast<f32x4*>(v);
+            u32x2* c4 = reinterpret_cast<u32x2*>(pc);
+            const int nvec = cv.len >> 2;
+
+            if (cv.len == kChunkElems) {
+#pragma unroll 1
+                for (int it = 0; it < kVecPerLane; it += U) {
+                    f32x4 gg[U], pp[U], mm[U], vv[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int idx = (it + u) * kBlock + tid;
+                        gg[u] = load_grad4<BF16G, NT>(g, idx);
+                        pp[u] = ld<NT>(p4 + idx);
+                        mm[u] = ld<NT>(m4 + idx);
+                        if constexpr (kHasV) vv[u] = ld<NT>(v4 + idx);
+                        else vv[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int idx = (it + u) * kBlock + tid;
+                        apply_vec<OPT>(a, h, h64, gg[u], pp[u], mm[u], vv[u]);
+                        st<NT>(p4 + idx, pp[u]);
+                        st<NT>(m4 + idx, mm[u]);
+                        if constexpr (kHasV) st<NT>(v4 + idx, vv[u]);
+                        if constexpr (COPY) st<NT>(c4 + idx, pack_bf16x4(pp[u]));
+                    }
+                }
+            } else {
+                for (int idx = tid; idx < nvec; idx += kBlock) {
+                    f32x4 gg = load_grad4<BF16G, NT>(g, idx);
+                    f32x4 pp = ld<NT>(p4 + idx);
+                    f32x4 mm = ld<NT>(m4 + idx);
+                    f32x4 vv = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if constexpr (kHasV) vv = ld<NT>(v4 + idx);
+                    apply_vec<OPT>(a, h, h64, gg, pp, mm, vv);
+                    st<NT>(p4 + idx, pp);
+                    st<NT>(m4 + idx, mm);
+                    if constexpr (kHasV) st<NT>(v4 + idx, vv);
+                    if constexpr (COPY) st<NT>(c4 + idx, pack_bf16x4(pp));
+                }
+                const int j = (nvec << 2) + tid;
+                if (j < cv.len) {
+                    ElemState s = {p[j], m[j], kHasV ? v[j] : 0.f};
+                    apply_elem<OPT>(a, h, h64, load_grad1<BF16G>(g, j), s);
+                    p[j] = s.p;
+                    m[j] = s.m;
+                    if constexpr (kHasV) v[j] = s.v;
+                    if constexpr (COPY) pc[j] = (uint16_t)float_to_bf16_bits(s.p);
+                }
+            }
+        } else {
+            for (int j = tid; j < cv.len; j += kBlock) {
+                ElemState s = {p[j], m[j], kHasV ? v[j] : 0.f};
+                apply_elem<OPT>(a, h, h64, load_grad1<BF16G>(g, j), s);
+                p[j] = s.p;
+                m[j] = s.m;
+                if constexpr (kHasV) v[j] = s.v;
+                if constexpr (COPY) pc[j] = (uint16_t)float_to_bf16_bits(s.p);
+            }
+        }
+    }
+}
+
+using UpdateFn = void (*)(DeviceTables, UpdateArgs);
+using SumsqFn = void (*)(DeviceTables);
+
+template <int OPT, bool BF16G, bool COPY>
+UpdateFn select_update_variant(int unroll, int nt)
+{
+    if (unroll == 4) return nt ? update_kernel<OPT, BF16G, COPY, 4, true> : update_kernel<OPT, BF16G, COPY, 4, false>;
+    if (unroll == 2) return nt ? update_kernel<OPT, BF16G, COPY, 2, true> : update_kernel<OPT, BF16G, COPY, 2, false>;
+    return nt ? update_kernel<OPT, BF16G, COPY, 1, true> : update_kernel<OPT, BF16G, COPY, 1, false>;
+}
+
+UpdateFn select_update(int optimizer, int grad_bf16, int with_copy, int unroll, int nt)
+{
+    const int key = (optimizer == ADAGC_OPT_LION ? 4 : 0) | (grad_bf16 ? 2 : 0) | (with_copy ? 1 : 0);
+    switch (key) {
+    case 0: return select_update_variant<ADAGC_OPT_ADAMW, false, false>(unroll, nt);
+    case 1: return select_update_variant<ADAGC_OPT_ADAMW, false, true>(unroll, nt);
+    case 2: return select_update_variant<ADAGC_OPT_ADAMW, true, false>(unroll, nt);
+    case 3: return select_update_variant<ADAGC_OPT_ADAMW, true, true>(unroll, nt);
+    case 4: return select_update_variant<ADAGC_OPT_LION, false, false>(unroll, nt);
+    case 5: return select_update_variant<ADAGC_OPT_LION, false, true>(unroll, nt);
+    case 6: return select_update_variant<ADAGC_OPT_LION, true, false>(unroll, nt);
+    default: return select_update_variant<ADAGC_OPT_LION, true, true>(unroll, nt);
+    }
+}
+
+SumsqFn select_sumsq(int grad_bf16)
+{
+    return grad_bf16 ? sumsq_partials_kernel<true> : sumsq_partials_kernel<false>;
+}
+
+}  // namespace
+
+int sumsq_blocks_per_cu(int grad_bf16)
+{
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_sumsq(grad_bf16), kBlock, 0) != hipSuccess) return 0;
+    return n;
+}
+
+int update_blocks_per_cu(int optimizer, int grad_bf16, int with_copy, int unroll, int nt)
+{
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_update(optimizer, grad_bf16, with_copy, unroll, nt),
+                                                     kBlock, 0) != hipSuccess)
+        return 0;
+    return n;
+}
+
+hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int grid, hipStream_t stream)
+{
+    select_sumsq(grad_bf16)<<<dim3(grid), dim3(kBlock), 0, stream>>>(t);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize_adagc(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream)
+{
+    finalize_adagc_kernel<<<dim3(t.n_tensors), dim3(64), 0, stream>>>(t, ema, r);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize_warmup(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream)
+{
+    tensor_sumsq_kernel<<<dim3(t.n_tensors), dim3(64), 0, stream>>>(t);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    global_coef_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(t, r);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const uint32_t blocks = (t.n_tensors + kBlock - 1) / kBlock;
+    finalize_warmup_kernel<<<dim3(blocks), dim3(kBlock), 0, stream>>>(t, ema, r);
+    return hipGetLastError();
+}
+
+hipError_t launch_update(const DeviceTables& t, const UpdateArgs& a, int optimizer, int grad_bf16,
+                         int with_copy, int unroll, int nt, int grid, hipStream_t stream)
+{
+    select_update(optimizer, grad_bf16, with_copy, unroll, nt)<<<dim3(grid), dim3(kBlock), 0, stream>>>(t, a);
+    return hipGetLastError();
+}
+
+}  // namespace adagc

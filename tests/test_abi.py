@@ -1,0 +1,82 @@
+"""The C-ABI library loads, exports every symbol its header declares, and validates arguments
+before touching a device.  No compute calls: runs without a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_11034_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "adagc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adagc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    L = B.lib()
+    names = declared_symbols()
+    assert len(names) >= 13
+    for name in names:
+        assert hasattr(L, name), name
+    assert sorted(B.EXPORTS) == names
+
+
+def test_struct_layouts_match_header():
+    assert ctypes.sizeof(B.adagc_tensor_desc) == 16
+    assert ctypes.sizeof(B.adagc_config) == 24
+    assert ctypes.sizeof(B.adagc_hyper) == 36
+
+
+def test_strerror():
+    assert B.strerror(0) == "ok"
+    assert "invalid" in B.strerror(B.ADAGC_ERR_INVALID_ARG)
+    assert B.strerror(-999) == "unknown error code"
+
+
+def _create(numels, **cfg_kw):
+    L = B.lib()
+    ctx = ctypes.c_void_p(None)
+    fields = dict(optimizer=0, grad_dtype=0, has_bf16_param_copy=0, grid_blocks=0, unroll=0, nontemporal=0)
+    fields.update(cfg_kw)
+    cfg = B.adagc_config(**fields)
+    descs = (B.adagc_tensor_desc * max(1, len(numels)))()
+    for i, n in enumerate(numels):
+        descs[i].numel = n
+    rc = L.adagc_create(ctypes.byref(ctx), ctypes.cast(descs, ctypes.c_void_p), len(numels), ctypes.byref(cfg))
+    return rc, ctx
+
+
+def test_create_validates_before_touching_the_device():
+    L = B.lib()
+    assert _create([])[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4, 0])[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], optimizer=7)[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], grad_dtype=2)[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], has_bf16_param_copy=3)[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], unroll=3)[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], grid_blocks=-1)[0] == B.ADAGC_ERR_INVALID_ARG
+    cfg = B.adagc_config()
+    assert L.adagc_create(None, None, 1, ctypes.byref(cfg)) == B.ADAGC_ERR_INVALID_ARG
+    rc, ctx = _create([4])
+    assert ctx.value is None or rc == B.ADAGC_OK
+    if rc == B.ADAGC_OK:       # a GPU is present
+        L.adagc_destroy(ctx)
+    else:                      # no device: a clean error, not a crash
+        assert rc == B.ADAGC_ERR_HIP
+
+
+def test_null_context_is_rejected_everywhere():
+    L = B.lib()
+    hp = B.make_hyper()
+    assert L.adagc_step(None, None, None, None, None, None, ctypes.byref(hp), 1, None) == B.ADAGC_ERR_INVALID_ARG
+    assert L.adagc_get_norms(None, None, None, None, 1, None) == B.ADAGC_ERR_INVALID_ARG
+    assert L.adagc_set_param_copies(None, None) == B.ADAGC_ERR_INVALID_ARG
+    assert L.adagc_get_segment_table(None, None, None, None) == B.ADAGC_ERR_INVALID_ARG
+    assert L.adagc_profile_begin(None, 4) == B.ADAGC_ERR_INVALID_ARG
+    assert L.adagc_num_chunks(None) < 0 and L.adagc_num_tensors(None) < 0
+    L.adagc_destroy(None)   # no-op

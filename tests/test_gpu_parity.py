@@ -1,0 +1,384 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Sizes here finish in seconds on the oracle and still span many chunks, ragged tails and
+tensors smaller than one lane-vector.  Full-size cases are in test_gpu_fullsize.py."""
+import ctypes
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2502_11034_amd import binding as B
+from paper_2502_11034_amd import workloads as W
+from paper_2502_11034_amd.workloads import to_numpy
+import parity as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def trajectory(run, hp, steps, name, lockstep=False):
+    """Advance device and oracle side by side.  lockstep=True re-seeds the oracle's state from the
+    device before every step (strict one-step comparison)."""
+    clipped_total = 0
+    for step in range(1, steps + 1):
+        grads = run.w.make_grads(step, DEV)
+        grads_np = [to_numpy(g) for g in grads]
+        if lockstep:
+            run.h_params = [to_numpy(t) for t in run.params]
+            run.h_m = [to_numpy(t) for t in run.m]
+            if run.v is not None:
+                run.h_v = [to_numpy(t) for t in run.v]
+            run.h_gamma = to_numpy(run.gamma)
+        m_before = [x.copy() for x in run.h_m] if run.optimizer == B.ADAGC_OPT_LION else None
+        norms, coefs, flags = run.gpu_step(grads, hp, step)
+        ref_norms, ref_coefs, ref_flags, thr = run.oracle_step(grads_np, hp, step)
+        warm = (step - 1) < hp.t_start
+        P.check_scalars("%s step %d" % (name, step), norms, coefs, flags, to_numpy(run.gamma),
+                        ref_norms, ref_coefs, ref_flags, run.h_gamma, None if warm else thr)
+        exempt = None
+        if run.optimizer == B.ADAGC_OPT_LION:
+            exempt = [run.lion_exempt(i, grads_np[i], m_before[i], ref_coefs[i], hp)
+                      for i in range(run.w.n_tensors)]
+        if lockstep or step == steps or step in run.w.spikes:
+            strict = run.compare_state("%s step %d" % (name, step), exempt)
+            say("%s step %d: state ok (%d strict-relative misses), %d clipped"
+                % (name, step, strict, int(ref_flags.sum())))
+        clipped_total += int(ref_flags.sum())
+    return clipped_total
+
+
+# --------------------------------------------------------------------------- segment table on the device
+
+def test_device_segment_table_matches_enumeration():
+    numels = [1, 3, 4, 5, 16383, 16384, 16385, 32768, 50000, 2, 100000]
+    ctx = B.AdaGC(numels)
+    begin, tensor, index = ctx.get_segment_table()
+    ref_chunks, ref_begin = oracle.enumerate_chunks(numels, B.adagc_chunk_elems())
+    assert begin.tolist() == ref_begin
+    assert tensor.tolist() == [c[0] for c in ref_chunks]
+    assert (index.astype(np.int64) * B.adagc_chunk_elems()).tolist() == [c[1] for c in ref_chunks]
+    assert ctx.num_chunks() == len(ref_chunks)
+    ctx.close()
+
+
+# --------------------------------------------------------------------------- the named workloads
+
+def test_config1_tiny_transformer_20_steps():
+    w = W.config1()
+    assert w.n_tensors == 27 and w.total_params == 527872
+    run = P.Run(w)
+    hp = B.make_hyper(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    clipped = trajectory(run, hp, 20, "config1")
+    assert clipped >= 6          # the spiked tensors of steps 7 and 13 at least
+
+
+def test_config2_gpt2_small_10_steps():
+    w = W.config2()
+    assert w.n_tensors == 148 and w.total_params == 124439808
+    run = P.Run(w)
+    hp = B.make_hyper()
+    clipped = trajectory(run, hp, 10, "config2")
+    assert clipped >= 7
+
+
+def test_config3_shape_scaled_adamw_bf16_copy():
+    """Llama-shaped list (GQA, SwiGLU, RMSNorm) at 1/8 width, 2 layers, with the bf16 copy."""
+    specs = W.llama_like_list(2, 512, 8, 2, 1792, 16032)
+    w = W.config3(specs)
+    w.spikes = W.forced_spike_schedule(len(specs), 5, {3}, 3, 50.0)
+    run = P.Run(w)
+    clipped = trajectory(run, B.make_hyper(), 5, "config3-scaled", lockstep=True)
+    assert clipped >= 3
+
+
+def test_config4_shape_scaled_lion_bf16_grads():
+    specs = W.llama_like_list(2, 512, 8, 2, 1792, 16032)
+    w = W.config4(specs)
+    w.spikes = W.forced_spike_schedule(len(specs), 5, {3}, 3, 50.0)
+    run = P.Run(w, optimizer="lion")
+    hp = B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1)
+    clipped = trajectory(run, hp, 5, "config4-scaled", lockstep=True)
+    assert clipped >= 3
+
+
+def test_config4_lion_trajectory_fp32_grads():
+    specs = W.gpt2_like_list(2, 128, 512, 1024, 0)
+    w = W.Workload(specs, spikes=W.forced_spike_schedule(len(specs), 6, {4}, 3, 100.0))
+    run = P.Run(w, optimizer="lion")
+    hp = B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1)
+    trajectory(run, hp, 6, "lion-fp32", lockstep=True)
+
+
+def test_config5_ragged_stress_scaled():
+    """2000 tensors, log-uniform sizes in [1, 2^17], heavy-tailed outliers, plus one larger tensor."""
+    specs = W.ragged_stress_list(2000, 1 << 17, (1000, 4099))
+    w = W.config5(specs)
+    sizes = np.array(w.numels)
+    assert (sizes == 1).any() or sizes.min() <= 3
+    run = P.Run(w)
+    trajectory(run, B.make_hyper(), 4, "config5-scaled")
+
+
+# --------------------------------------------------------------------------- edges
+
+def _single(numels, grads, gamma0, hp, step, params=None, optimizer="adamw"):
+    """One step on hand-made tensors; returns (run, gpu scalars, oracle scalars)."""
+    specs = [W.TensorSpec("t%d" % i, (n,), "matrix") for i, n in enumerate(numels)]
+    w = W.Workload(specs)
+    run = P.Run(w, optimizer=optimizer)
+    run.gamma.copy_(torch.tensor(gamma0, dtype=torch.float32))
+    run.h_gamma[:] = np.asarray(gamma0, dtype=np.float32)
+    g_dev = [torch.tensor(g, dtype=torch.float32, device=DEV) for g in grads]
+    got = run.gpu_step(g_dev, hp, step)
+    ref = run.oracle_step([np.asarray(g, dtype=np.float32) for g in grads], hp, step)
+    return run, got, ref
+
+
+def test_chunk_boundary_sizes_and_tiny_tensors():
+    c = B.adagc_chunk_elems()
+    numels = [1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 1023, 1025, c - 1, c, c + 1, 2 * c - 3, 2 * c, 3 * c + 5]
+    rng = np.random.default_rng(0)
+    grads = [rng.standard_normal(n).astype(np.float32) * 0.01 for n in numels]
+    hp = B.make_hyper(t_start=0)
+    gamma0 = [float(np.linalg.norm(g)) * (0.5 if i % 2 else 2.0) for i, g in enumerate(grads)]
+    run, got, ref = _single(numels, grads, gamma0, hp, 3)
+    P.check_scalars("boundary", *got, to_numpy(run.gamma), ref[0], ref[1], ref[2], run.h_gamma, ref[3])
+    assert ref[2].sum() == len(numels) // 2
+    run.compare_state("boundary")
+
+
+def test_degenerate_zero_gradient_and_zero_gamma():
+    numels = [8, 8, 8, 1]
+    grads = [np.zeros(8), np.full(8, 0.5), np.zeros(8), np.array([2.0])]
+    gamma0 = [1.0, 0.0, 0.0, 0.0]
+    hp = B.make_hyper(t_start=0)
+    run, got, ref = _single(numels, grads, gamma0, hp, 2)
+    norms, coefs, flags = got
+    assert coefs.tolist() == [1.0, 0.0, 1.0, 0.0] and flags.tolist() == [0, 1, 0, 1]
+    assert np.array_equal(coefs.astype(np.float64), ref[1]) and np.array_equal(flags, ref[2])
+    assert to_numpy(run.gamma).tolist() == run.h_gamma.tolist()
+    assert to_numpy(run.gamma)[1] == 0.0 and to_numpy(run.gamma)[3] == 0.0
+    run.compare_state("degenerate")
+
+
+def test_infinite_lambda_rel_is_plain_adamw():
+    """With lambda_rel = +inf (and gamma = 0, where the threshold is NaN) nothing is ever clipped
+    and the step is plain AdamW: checked against the library optimizer on the GPU."""
+    rng = np.random.default_rng(1)
+    numels = [1000, 33, 20000]
+    hp = B.make_hyper(lr=1e-2, lambda_rel=math.inf, t_start=0)
+    specs = [W.TensorSpec("t%d" % i, (n,), "matrix") for i, n in enumerate(numels)]
+    run = P.Run(W.Workload(specs), mirror=False)
+    tp = [p.clone().requires_grad_(True) for p in run.params]
+    opt = torch.optim.AdamW(tp, lr=1e-2, betas=(0.9, 0.95), eps=1e-8, weight_decay=0.1, foreach=False)
+    for step in range(1, 6):
+        grads = [torch.tensor(rng.standard_normal(n), dtype=torch.float32, device=DEV) * 100.0 ** (step % 3 - 1)
+                 for n in numels]
+        norms, coefs, flags = run.gpu_step(grads, hp, step)
+        assert (coefs == 1.0).all() and not flags.any()
+        for p, g in zip(tp, grads):
+            p.grad = g.clone()
+        opt.step()
+    for p, q in zip(run.params, tp):
+        np.testing.assert_allclose(to_numpy(p), to_numpy(q), rtol=2e-5, atol=2e-7)
+
+
+def test_unaligned_pointers_take_the_scalar_path():
+    """Views that start 1 element into a buffer are 4-byte aligned only."""
+    rng = np.random.default_rng(2)
+    numels = [5, 1000, 16384 + 7, 40000]
+    hp = B.make_hyper(t_start=0)
+
+    def off(n, fill=None, dtype=torch.float32):
+        buf = torch.zeros(n + 1, dtype=dtype, device=DEV)
+        view = buf[1:]
+        if fill is not None:
+            view.copy_(torch.as_tensor(fill, dtype=dtype))
+        return view
+
+    params = [off(n, rng.standard_normal(n) * 0.02) for n in numels]
+    grads = [off(n, rng.standard_normal(n) * 0.1) for n in numels]
+    m = [off(n, rng.standard_normal(n) * 0.01) for n in numels]
+    v = [off(n, (rng.standard_normal(n) * 0.01) ** 2) for n in numels]
+    copies = [off(n, dtype=torch.bfloat16) for n in numels]
+    assert all(t.data_ptr() % 16 != 0 for t in params)
+    gamma = torch.tensor([0.01, 10.0, 1.0, 100.0], dtype=torch.float32, device=DEV)
+    h = [[to_numpy(t) for t in lst] for lst in (params, grads, m, v)]
+    h_gamma = to_numpy(gamma)
+    h_copies = [np.zeros(n, np.uint16) for n in numels]
+    ctx = B.AdaGC(numels, has_bf16_param_copy=True)
+    ctx.set_param_copies(copies)
+    ctx.step(params, grads, m, v, gamma, hp, 7)
+    norms, coefs, flags = ctx.get_norms()
+    ohp = P.oracle_hyper(hp, 0, 0)
+    rn, rc, rf = oracle.adagc_step(h[0], h[1], h[2], h[3], h_gamma, ohp, 7, h_copies)
+    P.check_scalars("unaligned", norms, coefs, flags, to_numpy(gamma), rn, rc, rf, h_gamma)
+    assert rf.any() and not rf.all()
+    for i in range(len(numels)):
+        P.assert_close("unaligned theta %d" % i, to_numpy(params[i]), h[0][i])
+        P.assert_close("unaligned m %d" % i, to_numpy(m[i]), h[2][i])
+        P.assert_close("unaligned v %d" % i, to_numpy(v[i]), h[3][i])
+        P.assert_bf16_copy("unaligned copy %d" % i, to_numpy(copies[i]), to_numpy(params[i]), h[0][i])
+    ctx.close()
+
+
+def test_warmup_branch_global_clip_and_running_min():
+    """t_start = 3 with a finite lambda_abs that the global norm exceeds on steps 1 and 3."""
+    specs = W.gpt2_like_list(1, 64, 256, 300, 0)
+    w = W.Workload(specs, sigma_lo=1e-2, sigma_hi=1e-1,
+                   spikes={3: (np.arange(len(specs)), 10.0)})
+    run = P.Run(w)
+    g1 = w.make_grads(1, DEV)
+    total = math.sqrt(sum(float((g.double() ** 2).sum()) for g in g1))
+    hp = B.make_hyper(lambda_abs=0.5 * total, t_start=3)
+    for step in range(1, 6):
+        grads = w.make_grads(step, DEV)
+        norms, coefs, flags = run.gpu_step(grads, hp, step)
+        rn, rc, rf, thr = run.oracle_step([to_numpy(g) for g in grads], hp, step)
+        P.check_scalars("warmup step %d" % step, norms, coefs, flags, to_numpy(run.gamma), rn, rc, rf,
+                        run.h_gamma, None if step <= 3 else thr)
+        if step in (1, 3):
+            assert rf.all() and (rc < 1.0).all() and len(set(rc.tolist())) == 1
+        if step == 2:
+            assert not rf.any()
+    run.compare_state("warmup")
+
+
+# --------------------------------------------------------------------------- determinism, state, errors
+
+def test_run_to_run_and_permutation_determinism():
+    specs = W.ragged_stress_list(300, 1 << 16, None)
+    w = W.Workload(specs)
+    hp = B.make_hyper()
+
+    def run_once(order):
+        ws = W.Workload([specs[i] for i in order])
+        ws.sigma = w.sigma[order]
+        run = P.Run(ws, mirror=False)
+        out = None
+        for step in range(1, 4):
+            grads = [w.make_grad(i, step, DEV) for i in order]     # same bits per original tensor
+            for k, i in enumerate(order):
+                if step == 1:
+                    run.params[k].copy_(w.init_param(i, DEV))
+            out = run.gpu_step(grads, hp, step)
+        state = [(to_numpy(run.params[k]), to_numpy(run.m[k]), to_numpy(run.v[k])) for k in range(len(order))]
+        return out, to_numpy(run.gamma), state
+
+    ident = np.arange(len(specs))
+    a = run_once(ident)
+    b = run_once(ident)
+    perm = np.random.default_rng(5).permutation(len(specs))
+    c = run_once(perm)
+    for x, y in zip(a[0], b[0]):
+        assert np.array_equal(x, y)
+    assert np.array_equal(a[1], b[1])
+    for k, i in enumerate(perm):
+        assert a[0][0][i] == c[0][0][k] and a[0][1][i] == c[0][1][k] and a[1][i] == c[1][k]
+        for x, y in zip(a[2][i], c[2][k]):
+            assert np.array_equal(x, y)
+    for sa, sb in zip(a[2], b[2]):
+        for x, y in zip(sa, sb):
+            assert np.array_equal(x, y)
+
+
+def test_context_holds_no_algorithm_state():
+    """Destroying and re-creating the context mid-run changes nothing: all state is the caller's."""
+    w = W.config1()
+    hp = B.make_hyper()
+    a = P.Run(w, mirror=False)
+    b = P.Run(w, mirror=False)
+    for step in range(1, 7):
+        grads = w.make_grads(step, DEV)
+        a.gpu_step(grads, hp, step)
+        if step == 4:
+            b.ctx.close()
+            b.ctx = B.AdaGC(w.numels)
+        b.gpu_step(grads, hp, step)
+    for x, y in zip(a.params + a.m + a.v + [a.gamma], b.params + b.m + b.v + [b.gamma]):
+        assert torch.equal(x, y)
+
+
+def test_step_errors_leave_state_untouched():
+    numels = [100, 5000]
+    specs = [W.TensorSpec("t%d" % i, (n,), "matrix") for i, n in enumerate(numels)]
+    w = W.Workload(specs, bf16_copy=True)
+    run = P.Run(w, mirror=False)
+    grads = w.make_grads(1, DEV)
+    before = [t.clone() for t in run.params + run.m + run.v + [run.gamma]]
+    hp = B.make_hyper()
+    L = B.lib()
+
+    def code(fn):
+        with pytest.raises(B.AdagcError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, hp, 0)) == B.ADAGC_ERR_INVALID_ARG
+    assert code(lambda: run.ctx.step(run.params, grads, run.m, None, run.gamma, hp, 1)) == B.ADAGC_ERR_INVALID_ARG
+    bad = B.make_hyper(beta1=1.0)
+    assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, bad, 1)) == B.ADAGC_ERR_INVALID_ARG
+    bad = B.make_hyper(lambda_rel=float("nan"))
+    assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, bad, 1)) == B.ADAGC_ERR_INVALID_ARG
+    nullp = (ctypes.c_void_p * 2)(run.params[0].data_ptr(), None)
+    assert code(lambda: run.ctx.step(nullp, grads, run.m, run.v, run.gamma, hp, 1)) == B.ADAGC_ERR_INVALID_ARG
+    # bf16 copies announced but never registered
+    ctx2 = B.AdaGC(numels, has_bf16_param_copy=True)
+    assert code(lambda: ctx2.step(run.params, grads, run.m, run.v, run.gamma, hp, 1)) == B.ADAGC_ERR_STATE
+    ctx2.close()
+    ctx3 = B.AdaGC(numels)
+    assert code(lambda: ctx3.set_param_copies(run.copies)) == B.ADAGC_ERR_STATE
+    ctx3.close()
+    assert L.adagc_get_norms(run.ctx._ctx, None, None, None, 3, None) == B.ADAGC_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    for x, y in zip(before, run.params + run.m + run.v + [run.gamma]):
+        assert torch.equal(x, y)
+    # and the context still works afterwards
+    run.gpu_step(grads, hp, 1)
+    assert not torch.equal(before[0], run.params[0])
+
+
+def test_launch_tuning_knobs_do_not_change_results():
+    """grid size, unroll depth and non-temporal hints are scheduling choices only."""
+    specs = W.llama_like_list(1, 256, 4, 2, 896, 4000)
+    w = W.config3(specs)
+    hp = B.make_hyper()
+    outs = []
+    for kw in (dict(), dict(grid_blocks=7), dict(unroll=1), dict(unroll=4, nontemporal=1),
+               dict(grid_blocks=100000, unroll=2, nontemporal=2)):
+        run = P.Run(w, mirror=False, **kw)
+        for step in range(1, 4):
+            run.gpu_step(w.make_grads(step, DEV), hp, step)
+        outs.append([to_numpy(t) for t in run.params + run.m + run.v + run.copies + [run.gamma]])
+    for other in outs[1:]:
+        for x, y in zip(outs[0], other):
+            assert np.array_equal(x, y)
+
+
+def test_steps_on_a_side_stream_and_profile_events():
+    w = W.config1()
+    run = P.Run(w, mirror=False)
+    ref = P.Run(w, mirror=False)
+    hp = B.make_hyper()
+    side = torch.cuda.Stream()
+    run.ctx.profile_begin(8)
+    grads = [w.make_grads(s, DEV) for s in range(1, 4)]
+    torch.cuda.synchronize()
+    for step in range(1, 4):
+        run.ctx.step(run.params, grads[step - 1], run.m, run.v, run.gamma, hp, step, stream=side.cuda_stream)
+        ref.ctx.step(ref.params, grads[step - 1], ref.m, ref.v, ref.gamma, hp, step)
+    n1 = run.ctx.get_norms(stream=side.cuda_stream)
+    ms = run.ctx.profile_end()
+    n2 = ref.ctx.get_norms()
+    torch.cuda.synchronize()
+    assert ms.shape == (3, 3) and (ms > 0).all() and (ms < 1000).all()
+    for x, y in zip(n1, n2):
+        assert np.array_equal(x, y)
+    for x, y in zip(run.params, ref.params):
+        assert torch.equal(x, y)

@@ -1,0 +1,81 @@
+"""Host segment-table builder of the library vs the oracle's brute-force enumeration: integer
+work, compared bit for bit.  Needs no GPU."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2502_11034_amd import binding as B
+from paper_2502_11034_amd import workloads as W
+
+
+def compare(numels, chunk):
+    begin, tensor, index = B.adagc_build_segment_table(numels, chunk)
+    ref_chunks, ref_begin = oracle.enumerate_chunks(numels, chunk)
+    assert begin.tolist() == ref_begin
+    assert len(tensor) == len(ref_chunks)
+    ref_tensor = np.array([c[0] for c in ref_chunks], dtype=np.int64)
+    ref_first = np.array([c[1] for c in ref_chunks], dtype=np.int64)
+    ref_len = np.array([c[2] for c in ref_chunks], dtype=np.int64)
+    first = index.astype(np.int64) * chunk
+    length = np.minimum(chunk, np.asarray(numels, dtype=np.int64)[tensor.astype(np.int64)] - first)
+    assert np.array_equal(tensor.astype(np.int64), ref_tensor)
+    assert np.array_equal(first, ref_first)
+    assert np.array_equal(length, ref_len)
+    assert int(length.sum()) == int(sum(numels))
+
+
+def test_chunk_constant():
+    assert B.adagc_chunk_elems() == 16384
+
+
+@pytest.mark.parametrize("chunk", [1, 7, 16, 16384])
+def test_small_ragged_lists(chunk):
+    rng = np.random.default_rng(0)
+    numels = [int(x) for x in rng.integers(1, 100, 50)] + [1, chunk, chunk + 1, 2 * chunk, 2 * chunk - 1]
+    compare(numels, chunk)
+
+
+@pytest.mark.parametrize("make", [W.tiny_transformer_list, W.gpt2_small_list, W.llama3_8b_list])
+def test_model_lists(make):
+    numels = [s.numel for s in make()]
+    compare(numels, B.adagc_chunk_elems())
+
+
+def test_llama3_8b_counts():
+    numels = [s.numel for s in W.llama3_8b_list()]
+    assert len(numels) == 291 and sum(numels) == 8030261248
+    begin, tensor, index = B.adagc_build_segment_table(numels)
+    assert begin[-1] == sum(-(-n // 16384) for n in numels)
+
+
+def test_ragged_stress_list():
+    numels = [s.numel for s in W.ragged_stress_list()]
+    assert len(numels) == 20001
+    compare(numels, B.adagc_chunk_elems())
+
+
+def test_permutation_permutes_rows():
+    rng = np.random.default_rng(1)
+    numels = [int(x) for x in rng.integers(1, 70000, 30)]
+    perm = rng.permutation(len(numels))
+    b0, t0, i0 = B.adagc_build_segment_table(numels)
+    b1, t1, i1 = B.adagc_build_segment_table([numels[p] for p in perm])
+    for k, p in enumerate(perm):
+        assert np.array_equal(i1[b1[k]:b1[k + 1]], i0[b0[p]:b0[p + 1]])
+        assert (t1[b1[k]:b1[k + 1]] == k).all()
+
+
+def test_builder_rejects_bad_input():
+    with pytest.raises(B.AdagcError) as e:
+        B.adagc_build_segment_table([4, 0, 3])
+    assert e.value.code == B.ADAGC_ERR_INVALID_ARG
+    with pytest.raises(B.AdagcError):
+        B.adagc_build_segment_table([4, -1])
+    with pytest.raises(B.AdagcError):
+        B.adagc_build_segment_table([4], 0)
+    with pytest.raises(B.AdagcError):
+        B.adagc_build_segment_table([])
+    # more than 2^32-1 chunks
+    with pytest.raises(B.AdagcError) as e:
+        B.adagc_build_segment_table([2 ** 40], 1)
+    assert e.value.code == B.ADAGC_ERR_TOO_LARGE

@@ -1,0 +1,209 @@
+"""Benchmark of the fused AdaGC + AdamW step on Llama-3-8B-shaped synthetic tensors, one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config3|config4|config2|config5]
+
+A "step" is one pass of the whole hot path (segmented norms, per-tensor clip rule + EMA, fused
+clip + optimizer update) over the full parameter list, inputs resident in HBM.  Prints ONE JSON
+line: throughput as effective GB/s under the two-pass algorithmic byte count, ms per step, the
+roofline record of the dominant kernel (measured with HIP events on the step's stream), and the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(workload_name):
+    """Bytes per parameter that the method itself must move:
+    norm pass reads g once; update pass reads g, theta, m(, v) and writes theta, m(, v)(, bf16 copy)."""
+    table = {
+        # name: (norm read, update read, update write)
+        "config2": (4, 16, 12),     # fp32 everything, no copy
+        "config3": (4, 16, 14),     # + bf16 copy
+        "config4": (2, 10, 10),     # Lion: bf16 g; theta, m fp32; + bf16 copy
+        "config5": (4, 16, 12),
+    }
+    return table[workload_name]
+
+
+def kernel_source_hash():
+    h = hashlib.sha256()
+    for name in ("kernels.hip", "adagc_internal.h"):
+        with open(os.path.join(ROOT, "paper_2502_11034_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload_name, kernel):
+    """HBM bytes per launch from stored rocprofv3 --pmc runs, or None if the kernel source has
+    changed since they were taken (profiles/hbm_traffic.json is written by hand from those runs)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        rec = json.load(f)
+    if rec.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return rec.get(workload_name, {}).get(kernel)
+
+
+def cpu_baseline(workload_name, target_seconds=15.0):
+    """Time the CPU oracle (as it stands, one thread) on a bounded sample of the same workload:
+    the tensors of one transformer layer, several steps."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2502_11034_amd import workloads as W
+
+    if workload_name in ("config3", "config4"):
+        specs = [s for s in W.llama3_8b_list() if s.name.startswith("l0.")]
+        sample = "layer 0 of the Llama-3-8B-shaped list (9 tensors, %d params)"
+    elif workload_name == "config2":
+        specs = W.gpt2_small_list()
+        sample = "the whole GPT-2-small-shaped list (148 tensors, %d params)"
+    else:
+        specs = W.ragged_stress_list(400, 4194304, None)
+        sample = "400 tensors of the ragged list (%d params)"
+    lion = workload_name == "config4"
+    numels = [s.numel for s in specs]
+    n = sum(numels)
+    gen = torch.Generator().manual_seed(1234)
+    theta = [(torch.randn(k, generator=gen) * 0.02).numpy() for k in numels]
+    m = [np.zeros(k, np.float32) for k in numels]
+    v = None if lion else [np.zeros(k, np.float32) for k in numels]
+    copies = [np.zeros(k, np.uint16) for k in numels] if workload_name in ("config3", "config4") else None
+    if lion:
+        grads = [(torch.randn(k, generator=gen) * 1e-2).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+                 for k in numels]
+        hp = oracle.Hyper(lr=1e-4, beta1=0.9, beta2=0.99, optimizer=oracle.LION, grad_dtype=oracle.GRAD_BF16)
+    else:
+        grads = [(torch.randn(k, generator=gen) * 1e-2).numpy() for k in numels]
+        hp = oracle.Hyper()
+    gamma = np.zeros(len(numels), np.float32)
+    oracle.lib()
+    rd, ur, uw = algorithmic_bytes(workload_name)
+    steps, elapsed = 0, 0.0
+    while elapsed < target_seconds and steps < 64:
+        t0 = time.perf_counter()
+        oracle.adagc_step(theta, grads, m, v, gamma, hp, steps + 1, copies)
+        elapsed += time.perf_counter() - t0
+        steps += 1
+    gbps = (rd + ur + uw) * n * steps / elapsed / 1e9
+    return {"value": round(gbps, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": (sample % n) + ", %d steps, %.1f s, %.2f ns/param/step" % (steps, elapsed, elapsed / steps / n * 1e9)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5"])
+    ap.add_argument("--grid-blocks", type=int, default=0, help="launch tuning: workgroups of the persistent grids")
+    ap.add_argument("--unroll", type=int, default=0, help="launch tuning: vectors in flight per lane per stream")
+    ap.add_argument("--nontemporal", type=int, default=0, help="launch tuning: 1 on, 2 off")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    from paper_2502_11034_amd import binding as B
+    from paper_2502_11034_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    w = {"config2": W.config2, "config3": W.config3, "config4": W.config4, "config5": W.config5}[args.workload]()
+    lion = args.workload == "config4"
+    optimizer = B.ADAGC_OPT_LION if lion else B.ADAGC_OPT_ADAMW
+    grad_dtype = B.ADAGC_GRAD_BF16 if w.grad_dtype == torch.bfloat16 else B.ADAGC_GRAD_F32
+    hp = (B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1) if lion else B.make_hyper())
+
+    params, m, v, copies = w.make_state(dev, "lion" if lion else "adamw")
+    grads = w.make_grads(2, dev)                   # one batch of synthetic gradients, resident
+    gamma = torch.zeros(w.n_tensors, dtype=torch.float32, device=dev)
+    ctx = B.AdaGC(w.numels, optimizer, grad_dtype, w.bf16_copy, grid_blocks=args.grid_blocks,
+                  unroll=args.unroll, nontemporal=args.nontemporal)
+    if copies is not None:
+        ctx.set_param_copies(copies)
+    ptrs = tuple(B.ptr_array(x) if x is not None else None for x in (params, grads, m, v))
+    stream = torch.cuda.current_stream().cuda_stream
+
+    step = 0
+    for _ in range(args.warmup):
+        step += 1
+        ctx.step(ptrs[0], ptrs[1], ptrs[2], ptrs[3], gamma, hp, step, stream=stream)
+    torch.cuda.synchronize()
+
+    ctx.profile_begin(args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step += 1
+        ctx.step(ptrs[0], ptrs[1], ptrs[2], ptrs[3], gamma, hp, step, stream=stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per_kernel = ctx.profile_end()                 # [steps, 3] ms: norm, finalize, update
+    norms, coefs, flags = ctx.get_norms()
+
+    n = w.total_params
+    rd, ur, uw = algorithmic_bytes(args.workload)
+    ms_per_step = (t1 - t0) / args.steps * 1e3
+    bytes_two_pass = (rd + ur + uw) * n
+    bytes_once = (ur + uw) * n
+    value = bytes_two_pass / (ms_per_step * 1e-3) / 1e9
+    k_norm, k_fin, k_upd = (float(per_kernel[:, j].mean()) for j in range(3))
+    upd_bytes = (ur + uw) * n
+    upd_gbps = upd_bytes / (k_upd * 1e-3) / 1e9
+    norm_gbps = rd * n / (k_norm * 1e-3) / 1e9
+
+    out = {
+        "metric": "fused AdaGC+%s step: effective GB/s (two-pass algorithmic bytes), %s" % (
+            "Lion" if lion else "AdamW",
+            {"config2": "GPT-2-small shapes", "config3": "Llama-3-8B shapes", "config4": "Llama-3-8B shapes",
+             "config5": "ragged stress list"}[args.workload]),
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d tensors, %d params, %s grads, %s%s" % (
+            args.workload, w.n_tensors, n, "bf16" if grad_dtype else "fp32",
+            "Lion fp32 theta/m" if lion else "AdamW fp32 theta/m/v", ", bf16 param copy" if w.bf16_copy else ""),
+            "bytes_per_param_two_pass": rd + ur + uw, "bytes_per_param_each_array_once": ur + uw},
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "effective_gbps_each_array_once": round(bytes_once / (ms_per_step * 1e-3) / 1e9, 1),
+        "kernels_ms": {"sumsq_partials": round(k_norm, 4), "finalize": round(k_fin, 4), "update": round(k_upd, 4)},
+        "norm_kernel_gbps": round(norm_gbps, 1),
+        "tensors_clipped_last_step": int(flags.sum()),
+        "roofline": {"kernel": "update_kernel", "bound": "hbm", "achieved": round(upd_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(upd_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic(args.workload, "update_kernel")},
+    }
+    ctx.close()
+    del params, m, v, copies, grads
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -126,6 +126,7 @@ def forced_spike_schedule(n_tensors, steps, spike_steps, n_spiked, factor, seed=
 
 def _mix(seed, a, b):
     """Integer-only stream id for (seed, tensor, step)."""
+    seed, a, b = int(seed), int(a), int(b)
     x = (seed * 0x9E3779B97F4A7C15 + a * 0xBF58476D1CE4E5B9 + b * 0x94D049BB133111EB + 0x2545F491)
     x &= (1 << 63) - 1
     return x

@@ -1,6 +1,6 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
 inputs.  Sizes here finish in seconds on the oracle and still span many chunks, ragged tails and
-tensors smaller than one lane-vector.  Full-size cases are in test_gpu_fullsize.py."""
+tensors smaller than one lane-vector.  Full-size cases are in test_gpu_parity_fullsize.py."""
 import ctypes
 import math
 
@@ -46,7 +46,7 @@ def trajectory(run, hp, steps, name, lockstep=False):
             exempt = [run.lion_exempt(i, grads_np[i], m_before[i], ref_coefs[i], hp)
                       for i in range(run.w.n_tensors)]
         if lockstep or step == steps or step in run.w.spikes:
-            strict = run.compare_state("%s step %d" % (name, step), exempt)
+            strict = run.compare_state("%s step %d" % (name, step), exempt, grads_np, ref_coefs, hp.lr)
             say("%s step %d: state ok (%d strict-relative misses), %d clipped"
                 % (name, step, strict, int(ref_flags.sum())))
         clipped_total += int(ref_flags.sum())
@@ -229,14 +229,14 @@ def test_unaligned_pointers_take_the_scalar_path():
 
 
 def test_warmup_branch_global_clip_and_running_min():
-    """t_start = 3 with a finite lambda_abs that the global norm exceeds on steps 1 and 3."""
+    """t_start = 3 with a finite lambda_abs that the global norm exceeds on steps 1 and 3 only."""
     specs = W.gpt2_like_list(1, 64, 256, 300, 0)
     w = W.Workload(specs, sigma_lo=1e-2, sigma_hi=1e-1,
-                   spikes={3: (np.arange(len(specs)), 10.0)})
+                   spikes={1: (np.arange(len(specs)), 10.0), 3: (np.arange(len(specs)), 10.0)})
     run = P.Run(w)
-    g1 = w.make_grads(1, DEV)
-    total = math.sqrt(sum(float((g.double() ** 2).sum()) for g in g1))
-    hp = B.make_hyper(lambda_abs=0.5 * total, t_start=3)
+    g2 = w.make_grads(2, DEV)
+    total = math.sqrt(sum(float((g.double() ** 2).sum()) for g in g2))    # an unspiked step
+    hp = B.make_hyper(lambda_abs=3.0 * total, t_start=3)
     for step in range(1, 6):
         grads = w.make_grads(step, DEV)
         norms, coefs, flags = run.gpu_step(grads, hp, step)

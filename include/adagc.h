@@ -66,9 +66,14 @@ typedef struct {
     int32_t has_bf16_param_copy;  /* 1: every step also writes round-to-nearest-even bf16 copies of the
                                      updated params to the buffers given to adagc_set_param_copies */
     /* Launch tuning of the streaming kernels; 0 = library default for each. */
-    int32_t grid_blocks;          /* workgroups of the persistent grids */
-    int32_t unroll;               /* 128-bit vectors per lane per stream kept in flight: 1, 2 or 4 */
-    int32_t nontemporal;          /* 1 = streaming (non-temporal) loads/stores in the update kernel, 2 = off */
+    int32_t grid_blocks;          /* > 0: persistent grid of that many workgroups, each walking chunks
+                                     b, b+grid, ...; default: one chunk per workgroup */
+    int32_t unroll;               /* 128-bit vectors per lane per stream kept in flight: 1, 2 or 4 (default 2) */
+    int32_t nontemporal;          /* streaming (non-temporal) loads/stores in the update kernel:
+                                     1 = on (default), 2 = off */
+    int32_t schedule;             /* order in which workgroups visit chunks: 1 = list order; w >= 2 = the list is
+                                     cut into w contiguous parts and workgroup b walks part b mod w
+                                     (default 8 = the number of XCDs workgroups are dealt to in turn) */
 } adagc_config;
 
 /* Hyper-parameters of Alg. 1, passed by the caller on every step (the learning

@@ -37,7 +37,7 @@ class adagc_tensor_desc(ctypes.Structure):
 class adagc_config(ctypes.Structure):
     _fields_ = [("optimizer", ctypes.c_int32), ("grad_dtype", ctypes.c_int32),
                 ("has_bf16_param_copy", ctypes.c_int32), ("grid_blocks", ctypes.c_int32),
-                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32)]
+                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32), ("schedule", ctypes.c_int32)]
 
 
 class adagc_hyper(ctypes.Structure):
@@ -152,13 +152,13 @@ class AdaGC:
     """Owner of one adagc_ctx.  Methods mirror the C entry points one to one."""
 
     def __init__(self, numels, optimizer=ADAGC_OPT_ADAMW, grad_dtype=ADAGC_GRAD_F32,
-                 has_bf16_param_copy=False, grid_blocks=0, unroll=0, nontemporal=0):
+                 has_bf16_param_copy=False, grid_blocks=0, unroll=0, nontemporal=0, schedule=0):
         L = lib()
         self._ctx = ctypes.c_void_p(None)
         self.n_tensors = len(numels)
         self.numels = [int(n) for n in numels]
         cfg = adagc_config(int(optimizer), int(grad_dtype), int(bool(has_bf16_param_copy)),
-                           int(grid_blocks), int(unroll), int(nontemporal))
+                           int(grid_blocks), int(unroll), int(nontemporal), int(schedule))
         descs = _descs(self.numels)
         _check(L.adagc_create(ctypes.byref(self._ctx), ctypes.cast(descs, ctypes.c_void_p), self.n_tensors,
                               ctypes.byref(cfg)), "adagc_create")

@@ -61,7 +61,8 @@ struct UpdateArgs {
 };
 
 struct DeviceTables {
-    const ChunkRef*   chunks;
+    const ChunkRef*   chunks;     // canonical order: tensor by tensor; slot c of `partials` belongs to chunk c
+    const uint32_t*   schedule;   // order in which the streaming kernels visit the chunks
     const TensorArgs* targs;
     double*           partials;   // one per chunk
     double*           sumsq;      // one per tensor
@@ -73,10 +74,6 @@ struct DeviceTables {
     uint32_t          n_chunks;
     uint32_t          n_tensors;
 };
-
-// Resident workgroups per compute unit of the selected kernel variant (0 if the query fails).
-int sumsq_blocks_per_cu(int grad_bf16);
-int update_blocks_per_cu(int optimizer, int grad_bf16, int with_copy, int unroll, int nt);
 
 // Launchers (kernels.hip).  Each only enqueues on `stream`.
 hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int grid, hipStream_t stream);

@@ -106,9 +106,9 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     if (cfg->optimizer != ADAGC_OPT_ADAMW && cfg->optimizer != ADAGC_OPT_LION) return ADAGC_ERR_INVALID_ARG;
     if (cfg->grad_dtype != ADAGC_GRAD_F32 && cfg->grad_dtype != ADAGC_GRAD_BF16) return ADAGC_ERR_INVALID_ARG;
     if (cfg->has_bf16_param_copy != 0 && cfg->has_bf16_param_copy != 1) return ADAGC_ERR_INVALID_ARG;
-    if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 2) return ADAGC_ERR_INVALID_ARG;
-    if (cfg->unroll != 0 && cfg->unroll != 1 && cfg->unroll != 2 && cfg->unroll != 4)
+    if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 2 || cfg->schedule < 0)
         return ADAGC_ERR_INVALID_ARG;
+    if (cfg->unroll != 0 && cfg->unroll != 1 && cfg->unroll != 2 && cfg->unroll != 4) return ADAGC_ERR_INVALID_ARG;
 
     adagc_ctx* c = new (std::nothrow) adagc_ctx;
     if (!c) return ADAGC_ERR_OOM;
@@ -137,32 +137,30 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
         return ADAGC_ERR_OOM;
     }
 
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&c->device) != hipSuccess ||
-        hipGetDeviceProperties(&prop, c->device) != hipSuccess) {
+    if (hipGetDevice(&c->device) != hipSuccess) {
         free_ctx(c);
         return ADAGC_ERR_HIP;
     }
-    const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    // Launch defaults, each chosen by measurement on Llama-3-8B shapes (see the profiles):
+    //  - one chunk per workgroup, dispatched by the hardware, beat a static persistent grid by
+    //    1.5-2 % (a CU that falls behind simply receives fewer chunks); grid_blocks > 0 selects
+    //    a persistent grid of that many workgroups, each walking chunks b, b+grid, ...
+    //  - non-temporal loads/stores in the update kernel: +4.5 %
+    //  - visiting order cut into 8 parts, so that the workgroups that land on one XCD
+    //    (workgroup b goes to XCD b mod 8) stream one contiguous eighth of the list: +0.5-1.3 %,
+    //    +5 % on the norm kernel.
     c->unroll = cfg->unroll ? cfg->unroll : 2;
-    c->nontemporal = cfg->nontemporal ? (cfg->nontemporal == 1) : 0;
-    // Persistent grids: exactly as many workgroups as can be resident at once (so that none waits
-    // for another to finish), never more than there are chunks.
-    const int bf16g = cfg->grad_dtype == ADAGC_GRAD_BF16;
-    int occ_norm = sumsq_blocks_per_cu(bf16g);
-    int occ_update = update_blocks_per_cu(cfg->optimizer, bf16g, cfg->has_bf16_param_copy, c->unroll, c->nontemporal);
-    if (occ_norm <= 0) occ_norm = 4;
-    if (occ_update <= 0) occ_update = 4;
-    const int64_t want_norm = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : (int64_t)cus * occ_norm;
-    const int64_t want_update = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : (int64_t)cus * occ_update;
-    c->grid_norm = (int)(want_norm < c->n_chunks ? want_norm : c->n_chunks);
-    c->grid_update = (int)(want_update < c->n_chunks ? want_update : c->n_chunks);
+    c->nontemporal = cfg->nontemporal ? (cfg->nontemporal == 1) : 1;
+    const int64_t want = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : c->n_chunks;
+    c->grid_norm = (int)(want < c->n_chunks ? want : c->n_chunks);
+    c->grid_update = c->grid_norm;
 
     // One slab, carved into 256-byte aligned arrays.
     const size_t nt = (size_t)n_tensors, nc = (size_t)c->n_chunks;
     size_t off = 0;
     auto carve = [&off](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     const size_t o_chunks = carve(nc * sizeof(ChunkRef));
+    const size_t o_schedule = carve(nc * sizeof(uint32_t));
     const size_t o_targs = carve(nt * sizeof(TensorArgs));
     const size_t o_partials = carve(nc * sizeof(double));
     const size_t o_sumsq = carve(nt * sizeof(double));
@@ -187,6 +185,32 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
         free_ctx(c);
         return ADAGC_ERR_HIP;
     }
+    // Visiting order.  With w parts, position k goes to part k mod w, at offset k / w inside it
+    // (parts differ in length by at most one chunk); w = 1 is the list order.
+    {
+        const size_t wparts = cfg->schedule == 0 ? 8 : (size_t)cfg->schedule;
+        std::vector<uint32_t> order;
+        try {
+            order.resize(nc);
+        } catch (const std::bad_alloc&) { free_ctx(c); return ADAGC_ERR_OOM; }
+        if (wparts <= 1 || wparts > nc) {
+            for (size_t k = 0; k < nc; ++k) order[k] = (uint32_t)k;
+        } else {
+            const size_t base_len = nc / wparts, extra = nc % wparts;   // first `extra` parts are one longer
+            size_t k = 0;
+            for (size_t row = 0; row <= base_len; ++row)
+                for (size_t part = 0; part < wparts; ++part) {
+                    const size_t len = base_len + (part < extra ? 1 : 0);
+                    if (row >= len) continue;
+                    const size_t start = part * base_len + (part < extra ? part : extra);
+                    order[k++] = (uint32_t)(start + row);
+                }
+        }
+        if (hipMemcpy(base + o_schedule, order.data(), nc * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) {
+            free_ctx(c);
+            return ADAGC_ERR_HIP;
+        }
+    }
     if (hipHostMalloc(reinterpret_cast<void**>(&c->staging), nt * sizeof(TensorArgs), hipHostMallocDefault) !=
             hipSuccess ||
         hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming) != hipSuccess) {
@@ -197,6 +221,7 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     c->d_targs = reinterpret_cast<TensorArgs*>(base + o_targs);
     DeviceTables& t = c->tables;
     t.chunks = reinterpret_cast<const ChunkRef*>(base + o_chunks);
+    t.schedule = reinterpret_cast<const uint32_t*>(base + o_schedule);
     t.targs = c->d_targs;
     t.partials = reinterpret_cast<double*>(base + o_partials);
     t.sumsq = reinterpret_cast<double*>(base + o_sumsq);

@@ -160,7 +160,8 @@ __global__ __launch_bounds__(kBlock) void sumsq_partials_kernel(DeviceTables t)
     __shared__ double wave_sums[kWavesPerBlock];
     const int tid = threadIdx.x;
 
-    for (uint32_t c = blockIdx.x; c < t.n_chunks; c += gridDim.x) {
+    for (uint32_t k = blockIdx.x; k < t.n_chunks; k += gridDim.x) {
+        const uint32_t c = t.schedule[k];
         const ChunkView cv = chunk_view(t, c);
         const TensorArgs& ta = t.targs[cv.tensor];
         const void* g = grad_chunk_ptr<BF16>(ta.grad, cv.first);
@@ -203,22 +204,40 @@ __global__ __launch_bounds__(kBlock) void sumsq_partials_kernel(DeviceTables t)
 }
 
 // ---------------------------------------------------------------------------------------------
-// K2: per-tensor scalars.  One wave per tensor sums that tensor's partial slots in slot order.
+// K2: per-tensor scalars.  One workgroup per tensor sums that tensor's partial slots in a fixed
+// order that depends only on the slot count: lane l owns slots l, l+256, l+512, ... and keeps four
+// accumulators (slot row mod 4) so that four loads are in flight; lanes are combined by the
+// wave tree, waves through LDS in wave order.
 
-__device__ __forceinline__ double tensor_sumsq(const DeviceTables& t, uint32_t i)
+__device__ __forceinline__ double tensor_sumsq(const DeviceTables& t, uint32_t i, double* wave_sums)
 {
     const uint32_t begin = t.targs[i].chunk_begin;
     const uint32_t count = t.targs[i].chunk_count;
-    double acc = 0.0;
-    for (uint32_t k = threadIdx.x; k < count; k += 64) acc += t.partials[begin + k];
-    return wave_sum_f64(acc);
+    const double* p = t.partials + begin;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    uint32_t k = threadIdx.x;
+    for (; k + 3 * kBlock < count; k += 4 * kBlock) {
+        const double x0 = p[k], x1 = p[k + kBlock], x2 = p[k + 2 * kBlock], x3 = p[k + 3 * kBlock];
+        a0 += x0; a1 += x1; a2 += x2; a3 += x3;
+    }
+    if (k < count) a0 += p[k];
+    if (k + kBlock < count) a1 += p[k + kBlock];
+    if (k + 2 * kBlock < count) a2 += p[k + 2 * kBlock];
+    const double s = wave_sum_f64((a0 + a1) + (a2 + a3));
+    if ((threadIdx.x & 63) == 0) wave_sums[threadIdx.x >> 6] = s;
+    __syncthreads();
+    double total = wave_sums[0];
+#pragma unroll
+    for (int w = 1; w < kWavesPerBlock; ++w) total += wave_sums[w];
+    return total;
 }
 
 // AdaGC branch of Alg. 1 / Eq. 3, in double, with separately rounded operations.
-__global__ __launch_bounds__(64) void finalize_adagc_kernel(DeviceTables t, float* ema, RuleArgs r)
+__global__ __launch_bounds__(kBlock) void finalize_adagc_kernel(DeviceTables t, float* ema, RuleArgs r)
 {
+    __shared__ double wave_sums[kWavesPerBlock];
     const uint32_t i = blockIdx.x;
-    const double s = tensor_sumsq(t, i);
+    const double s = tensor_sumsq(t, i, wave_sums);
     if (threadIdx.x != 0) return;
 
     const double norm = sqrt(s);
@@ -238,10 +257,11 @@ __global__ __launch_bounds__(64) void finalize_adagc_kernel(DeviceTables t, floa
 }
 
 // Warm-up branch, stage 1: per-tensor sum of squares only.
-__global__ __launch_bounds__(64) void tensor_sumsq_kernel(DeviceTables t)
+__global__ __launch_bounds__(kBlock) void tensor_sumsq_kernel(DeviceTables t)
 {
+    __shared__ double wave_sums[kWavesPerBlock];
     const uint32_t i = blockIdx.x;
-    const double s = tensor_sumsq(t, i);
+    const double s = tensor_sumsq(t, i, wave_sums);
     if (threadIdx.x == 0) t.sumsq[i] = s;
 }
 
@@ -337,7 +357,8 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
     constexpr bool kHasV = (OPT == ADAGC_OPT_ADAMW);
     const int tid = threadIdx.x;
 
-    for (uint32_t c = blockIdx.x; c < t.n_chunks; c += gridDim.x) {
+    for (uint32_t k = blockIdx.x; k < t.n_chunks; k += gridDim.x) {
+        const uint32_t c = t.schedule[k];
         const ChunkView cv = chunk_view(t, c);
         const TensorArgs& ta = t.targs[cv.tensor];
         const float h = t.coef[cv.tensor];
@@ -448,22 +469,6 @@ SumsqFn select_sumsq(int grad_bf16)
 
 }  // namespace
 
-int sumsq_blocks_per_cu(int grad_bf16)
-{
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_sumsq(grad_bf16), kBlock, 0) != hipSuccess) return 0;
-    return n;
-}
-
-int update_blocks_per_cu(int optimizer, int grad_bf16, int with_copy, int unroll, int nt)
-{
-    int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, select_update(optimizer, grad_bf16, with_copy, unroll, nt),
-                                                     kBlock, 0) != hipSuccess)
-        return 0;
-    return n;
-}
-
 hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int grid, hipStream_t stream)
 {
     select_sumsq(grad_bf16)<<<dim3(grid), dim3(kBlock), 0, stream>>>(t);
@@ -472,13 +477,13 @@ hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int grid,
 
 hipError_t launch_finalize_adagc(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream)
 {
-    finalize_adagc_kernel<<<dim3(t.n_tensors), dim3(64), 0, stream>>>(t, ema, r);
+    finalize_adagc_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t, ema, r);
     return hipGetLastError();
 }
 
 hipError_t launch_finalize_warmup(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream)
 {
-    tensor_sumsq_kernel<<<dim3(t.n_tensors), dim3(64), 0, stream>>>(t);
+    tensor_sumsq_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     global_coef_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(t, r);

@@ -28,7 +28,7 @@ def test_header_symbols_are_exported():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.adagc_tensor_desc) == 16
-    assert ctypes.sizeof(B.adagc_config) == 24
+    assert ctypes.sizeof(B.adagc_config) == 28
     assert ctypes.sizeof(B.adagc_hyper) == 36
 
 
@@ -41,7 +41,7 @@ def test_strerror():
 def _create(numels, **cfg_kw):
     L = B.lib()
     ctx = ctypes.c_void_p(None)
-    fields = dict(optimizer=0, grad_dtype=0, has_bf16_param_copy=0, grid_blocks=0, unroll=0, nontemporal=0)
+    fields = dict(optimizer=0, grad_dtype=0, has_bf16_param_copy=0, grid_blocks=0, unroll=0, nontemporal=0, schedule=0)
     fields.update(cfg_kw)
     cfg = B.adagc_config(**fields)
     descs = (B.adagc_tensor_desc * max(1, len(numels)))()

@@ -351,7 +351,8 @@ def test_launch_tuning_knobs_do_not_change_results():
     hp = B.make_hyper()
     outs = []
     for kw in (dict(), dict(grid_blocks=7), dict(unroll=1), dict(unroll=4, nontemporal=1),
-               dict(grid_blocks=100000, unroll=2, nontemporal=2)):
+               dict(grid_blocks=100000, unroll=2, nontemporal=2), dict(schedule=1), dict(schedule=7, grid_blocks=50),
+               dict(schedule=1000000), dict(grid_blocks=1024, schedule=2, unroll=1, nontemporal=2)):
         run = P.Run(w, mirror=False, **kw)
         for step in range(1, 4):
             run.gpu_step(w.make_grads(step, DEV), hp, step)

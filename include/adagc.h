@@ -69,8 +69,8 @@ typedef struct {
     int32_t grid_blocks;          /* > 0: persistent grid of that many workgroups, each walking chunks
                                      b, b+grid, ...; default: one chunk per workgroup */
     int32_t unroll;               /* 128-bit vectors per lane per stream kept in flight: 1, 2 or 4 (default 2) */
-    int32_t nontemporal;          /* streaming (non-temporal) loads/stores in the update kernel:
-                                     1 = on (default), 2 = off */
+    int32_t nontemporal;          /* streaming (non-temporal) memory hints: 1 = loads and stores (default),
+                                     2 = off, 3 = loads only, 4 = stores only */
     int32_t schedule;             /* order in which workgroups visit chunks: 1 = list order; w >= 2 = the list is
                                      cut into w contiguous parts and workgroup b walks part b mod w
                                      (default 8 = the number of XCDs workgroups are dealt to in turn) */

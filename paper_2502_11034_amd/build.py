@@ -25,16 +25,19 @@ def is_stale():
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force=True, verbose=False):
-    """Compile every source for gfx950 and link the shared library.  Cross-compiles without a GPU."""
-    if not force and not is_stale():
+def build(force=True, verbose=False, extra_flags=(), out=None):
+    """Compile every source for gfx950 and link the shared library.  Cross-compiles without a GPU.
+    extra_flags/out build a variant (e.g. another chunk size) somewhere else, for measurements."""
+    out = out or LIB
+    if out == LIB and not force and not is_stale():
         return LIB
-    tmp = LIB + ".tmp.%d" % os.getpid()
+    tmp = out + ".tmp.%d" % os.getpid()
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            # packed-fp32 code generation is switched off on purpose (known-bad forms on this part)
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wextra", "-Wno-unused-parameter",
            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-x", "hip"]
+    cmd += list(extra_flags)
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     cmd += ["-o", tmp]
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -44,8 +47,8 @@ def build(force=True, verbose=False):
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

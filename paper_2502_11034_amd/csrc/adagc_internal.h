@@ -12,7 +12,10 @@ namespace adagc {
 // own first element, so a tensor's reduction tree depends only on its own size.
 // 16384 fp32 = 64 KiB per stream per chunk: one workgroup of 256 lanes covers a
 // full chunk with 16 independent 128-bit loads per lane per stream.
-constexpr int kChunkElems = 16384;
+#ifndef ADAGC_CHUNK_ELEMS
+#define ADAGC_CHUNK_ELEMS 16384
+#endif
+constexpr int kChunkElems = ADAGC_CHUNK_ELEMS;
 constexpr int kBlock = 256;              // lanes per workgroup (4 wave64)
 constexpr int kWavesPerBlock = kBlock / 64;
 constexpr int kVecPerLane = kChunkElems / 4 / kBlock;   // 128-bit vectors per lane in a full chunk
@@ -76,7 +79,8 @@ struct DeviceTables {
 };
 
 // Launchers (kernels.hip).  Each only enqueues on `stream`.
-hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int grid, hipStream_t stream);
+// nt: bit 0 = non-temporal loads, bit 1 = non-temporal stores
+hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int nt, int grid, hipStream_t stream);
 hipError_t launch_finalize_adagc(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
 hipError_t launch_finalize_warmup(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
 hipError_t launch_update(const DeviceTables& t, const UpdateArgs& u, int optimizer, int grad_bf16,

@@ -106,7 +106,7 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     if (cfg->optimizer != ADAGC_OPT_ADAMW && cfg->optimizer != ADAGC_OPT_LION) return ADAGC_ERR_INVALID_ARG;
     if (cfg->grad_dtype != ADAGC_GRAD_F32 && cfg->grad_dtype != ADAGC_GRAD_BF16) return ADAGC_ERR_INVALID_ARG;
     if (cfg->has_bf16_param_copy != 0 && cfg->has_bf16_param_copy != 1) return ADAGC_ERR_INVALID_ARG;
-    if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 2 || cfg->schedule < 0)
+    if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 4 || cfg->schedule < 0)
         return ADAGC_ERR_INVALID_ARG;
     if (cfg->unroll != 0 && cfg->unroll != 1 && cfg->unroll != 2 && cfg->unroll != 4) return ADAGC_ERR_INVALID_ARG;
 
@@ -150,7 +150,10 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     //    (workgroup b goes to XCD b mod 8) stream one contiguous eighth of the list: +0.5-1.3 %,
     //    +5 % on the norm kernel.
     c->unroll = cfg->unroll ? cfg->unroll : 2;
-    c->nontemporal = cfg->nontemporal ? (cfg->nontemporal == 1) : 1;
+    {   // knob -> bit mask: bit 0 loads, bit 1 stores
+        static const int mask_of[5] = {3, 3, 0, 1, 2};
+        c->nontemporal = mask_of[cfg->nontemporal];
+    }
     const int64_t want = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : c->n_chunks;
     c->grid_norm = (int)(want < c->n_chunks ? want : c->n_chunks);
     c->grid_update = c->grid_norm;
@@ -335,7 +338,7 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
     hipEvent_t* ev = prof ? &ctx->prof_events[(size_t)ctx->prof_steps * 4] : nullptr;
 
     if (prof && hipEventRecord(ev[0], stream) != hipSuccess) return ADAGC_ERR_HIP;
-    if (launch_sumsq_partials(ctx->tables, bf16g, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (launch_sumsq_partials(ctx->tables, bf16g, ctx->nontemporal, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
     if (prof && hipEventRecord(ev[1], stream) != hipSuccess) return ADAGC_ERR_HIP;
     hipError_t e = warmup ? launch_finalize_warmup(ctx->tables, ema_norms, r, stream)
                           : launch_finalize_adagc(ctx->tables, ema_norms, r, stream);

@@ -154,7 +154,7 @@ __device__ __forceinline__ void acc4(double (&acc)[4], f32x4 g)
     acc[3] = fma(w, w, acc[3]);
 }
 
-template <bool BF16>
+template <bool BF16, bool NTL>
 __global__ __launch_bounds__(kBlock) void sumsq_partials_kernel(DeviceTables t)
 {
     __shared__ double wave_sums[kWavesPerBlock];
@@ -171,12 +171,12 @@ __global__ __launch_bounds__(kBlock) void sumsq_partials_kernel(DeviceTables t)
             if (cv.len == kChunkElems) {
                 f32x4 r[kVecPerLane];
 #pragma unroll
-                for (int u = 0; u < kVecPerLane; ++u) r[u] = load_grad4<BF16, false>(g, u * kBlock + tid);
+                for (int u = 0; u < kVecPerLane; ++u) r[u] = load_grad4<BF16, NTL>(g, u * kBlock + tid);
 #pragma unroll
                 for (int u = 0; u < kVecPerLane; ++u) acc4(acc, r[u]);
             } else {
                 const int nvec = cv.len >> 2;
-                for (int v = tid; v < nvec; v += kBlock) acc4(acc, load_grad4<BF16, false>(g, v));
+                for (int v = tid; v < nvec; v += kBlock) acc4(acc, load_grad4<BF16, NTL>(g, v));
                 const int j = (nvec << 2) + tid;
                 if (j < cv.len) {
                     double x = (double)load_grad1<BF16>(g, j);
@@ -317,8 +317,13 @@ __device__ __forceinline__ void adamw_elem(const UpdateArgs& a, float h, float g
     const float gh = h * g;
     s.m = fmaf(a.one_minus_beta1, gh, a.beta1 * s.m);
     s.v = fmaf(a.one_minus_beta2 * gh, gh, a.beta2 * s.v);
+#ifdef ADAGC_FAST_MATH
+    const float denom = __builtin_amdgcn_sqrtf(s.v * a.inv_bias2) + a.eps;
+    s.p = fmaf(s.p, a.decay, -((a.step_size * s.m) * __builtin_amdgcn_rcpf(denom)));
+#else
     const float denom = sqrtf(s.v * a.inv_bias2) + a.eps;
     s.p = fmaf(s.p, a.decay, -((a.step_size * s.m) / denom));
+#endif
 }
 
 // Lion.  The sign is a discrete decision, so the interpolation c is evaluated in double with
@@ -351,9 +356,11 @@ __device__ __forceinline__ void apply_vec(const UpdateArgs& a, float h, double h
     s = {p.w, m.w, v.w}; apply_elem<OPT>(a, h, h64, g.w, s); p.w = s.p; m.w = s.m; v.w = s.v;
 }
 
-template <int OPT, bool BF16G, bool COPY, int U, bool NT>
+template <int OPT, bool BF16G, bool COPY, int U, int NT>
 __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateArgs a)
 {
+    constexpr bool NTL = (NT & 1) != 0;   // non-temporal loads
+    constexpr bool NTS = (NT & 2) != 0;   // non-temporal stores
     constexpr bool kHasV = (OPT == ADAGC_OPT_ADAMW);
     const int tid = threadIdx.x;
 
@@ -384,34 +391,34 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const int idx = (it + u) * kBlock + tid;
-                        gg[u] = load_grad4<BF16G, NT>(g, idx);
-                        pp[u] = ld<NT>(p4 + idx);
-                        mm[u] = ld<NT>(m4 + idx);
-                        if constexpr (kHasV) vv[u] = ld<NT>(v4 + idx);
+                        gg[u] = load_grad4<BF16G, NTL>(g, idx);
+                        pp[u] = ld<NTL>(p4 + idx);
+                        mm[u] = ld<NTL>(m4 + idx);
+                        if constexpr (kHasV) vv[u] = ld<NTL>(v4 + idx);
                         else vv[u] = f32x4{0.f, 0.f, 0.f, 0.f};
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const int idx = (it + u) * kBlock + tid;
                         apply_vec<OPT>(a, h, h64, gg[u], pp[u], mm[u], vv[u]);
-                        st<NT>(p4 + idx, pp[u]);
-                        st<NT>(m4 + idx, mm[u]);
-                        if constexpr (kHasV) st<NT>(v4 + idx, vv[u]);
-                        if constexpr (COPY) st<NT>(c4 + idx, pack_bf16x4(pp[u]));
+                        st<NTS>(p4 + idx, pp[u]);
+                        st<NTS>(m4 + idx, mm[u]);
+                        if constexpr (kHasV) st<NTS>(v4 + idx, vv[u]);
+                        if constexpr (COPY) st<NTS>(c4 + idx, pack_bf16x4(pp[u]));
                     }
                 }
             } else {
                 for (int idx = tid; idx < nvec; idx += kBlock) {
-                    f32x4 gg = load_grad4<BF16G, NT>(g, idx);
-                    f32x4 pp = ld<NT>(p4 + idx);
-                    f32x4 mm = ld<NT>(m4 + idx);
+                    f32x4 gg = load_grad4<BF16G, NTL>(g, idx);
+                    f32x4 pp = ld<NTL>(p4 + idx);
+                    f32x4 mm = ld<NTL>(m4 + idx);
                     f32x4 vv = f32x4{0.f, 0.f, 0.f, 0.f};
-                    if constexpr (kHasV) vv = ld<NT>(v4 + idx);
+                    if constexpr (kHasV) vv = ld<NTL>(v4 + idx);
                     apply_vec<OPT>(a, h, h64, gg, pp, mm, vv);
-                    st<NT>(p4 + idx, pp);
-                    st<NT>(m4 + idx, mm);
-                    if constexpr (kHasV) st<NT>(v4 + idx, vv);
-                    if constexpr (COPY) st<NT>(c4 + idx, pack_bf16x4(pp));
+                    st<NTS>(p4 + idx, pp);
+                    st<NTS>(m4 + idx, mm);
+                    if constexpr (kHasV) st<NTS>(v4 + idx, vv);
+                    if constexpr (COPY) st<NTS>(c4 + idx, pack_bf16x4(pp));
                 }
                 const int j = (nvec << 2) + tid;
                 if (j < cv.len) {
@@ -439,12 +446,23 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
 using UpdateFn = void (*)(DeviceTables, UpdateArgs);
 using SumsqFn = void (*)(DeviceTables);
 
+template <int OPT, bool BF16G, bool COPY, int U>
+UpdateFn select_update_nt(int nt)
+{
+    switch (nt & 3) {
+    case 0: return update_kernel<OPT, BF16G, COPY, U, 0>;
+    case 1: return update_kernel<OPT, BF16G, COPY, U, 1>;
+    case 2: return update_kernel<OPT, BF16G, COPY, U, 2>;
+    default: return update_kernel<OPT, BF16G, COPY, U, 3>;
+    }
+}
+
 template <int OPT, bool BF16G, bool COPY>
 UpdateFn select_update_variant(int unroll, int nt)
 {
-    if (unroll == 4) return nt ? update_kernel<OPT, BF16G, COPY, 4, true> : update_kernel<OPT, BF16G, COPY, 4, false>;
-    if (unroll == 2) return nt ? update_kernel<OPT, BF16G, COPY, 2, true> : update_kernel<OPT, BF16G, COPY, 2, false>;
-    return nt ? update_kernel<OPT, BF16G, COPY, 1, true> : update_kernel<OPT, BF16G, COPY, 1, false>;
+    if (unroll == 4) return select_update_nt<OPT, BF16G, COPY, 4>(nt);
+    if (unroll == 2) return select_update_nt<OPT, BF16G, COPY, 2>(nt);
+    return select_update_nt<OPT, BF16G, COPY, 1>(nt);
 }
 
 UpdateFn select_update(int optimizer, int grad_bf16, int with_copy, int unroll, int nt)
@@ -462,16 +480,17 @@ UpdateFn select_update(int optimizer, int grad_bf16, int with_copy, int unroll, 
     }
 }
 
-SumsqFn select_sumsq(int grad_bf16)
+SumsqFn select_sumsq(int grad_bf16, int nt)
 {
-    return grad_bf16 ? sumsq_partials_kernel<true> : sumsq_partials_kernel<false>;
+    if (nt & 1) return grad_bf16 ? sumsq_partials_kernel<true, true> : sumsq_partials_kernel<false, true>;
+    return grad_bf16 ? sumsq_partials_kernel<true, false> : sumsq_partials_kernel<false, false>;
 }
 
 }  // namespace
 
-hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int grid, hipStream_t stream)
+hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int nt, int grid, hipStream_t stream)
 {
-    select_sumsq(grad_bf16)<<<dim3(grid), dim3(kBlock), 0, stream>>>(t);
+    select_sumsq(grad_bf16, nt)<<<dim3(grid), dim3(kBlock), 0, stream>>>(t);
     return hipGetLastError();
 }
 

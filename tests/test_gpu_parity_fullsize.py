@@ -29,12 +29,16 @@ def f32(x):
     return float(np.float32(x))
 
 
-def run_fullsize(w, optimizer, hp, steps, subset, scalar_step, name):
+def run_fullsize(w, optimizer, hp, steps, subset, scalar_step, name, early_subset=None):
+    """early_subset: the (smaller) subset checked on the steps before scalar_step; the full subset,
+    which holds the largest tensor, is replayed by the oracle on scalar_step only (time)."""
     lion = optimizer == "lion"
     run = P.Run(w, optimizer=optimizer, mirror=False)
     ohp = P.oracle_hyper(hp, run.optimizer, run.grad_dtype)
     say("%s: %d tensors, %d params resident" % (name, w.n_tensors, w.total_params))
+    full_subset = subset
     for step in range(1, steps + 1):
+        subset = full_subset if (step == scalar_step or early_subset is None) else early_subset
         pre = {}
         for i in subset:
             pre[i] = (to_numpy(run.params[i]), to_numpy(run.m[i]),
@@ -94,25 +98,27 @@ def run_fullsize(w, optimizer, hp, steps, subset, scalar_step, name):
     torch.cuda.empty_cache()
 
 
-def llama_subset(w, spike_step):
+def llama_subsets(w, spike_step):
     names = {s.name: i for i, s in enumerate(w.specs)}
-    subset = [names["embed"], names["l0.attn_norm"], names["l0.k"], names["l7.q"], names["l31.down"],
-              names["final_norm"]]
+    early = [names["l0.attn_norm"], names["l0.k"], names["final_norm"]]
+    subset = early + [names["embed"], names["l7.q"], names["l31.down"]]
     spiked = [int(i) for i in w.spikes[spike_step][0]]
     small_spiked = sorted(spiked, key=lambda i: w.numels[i])[:2]
-    return sorted(set(subset + small_spiked))
+    return sorted(set(subset + small_spiked)), sorted(set(early + small_spiked))
 
 
 def test_config3_full_size_llama3_8b_adamw():
     w = W.config3()
     assert w.n_tensors == 291 and w.total_params == 8030261248
-    run_fullsize(w, "adamw", B.make_hyper(), 3, llama_subset(w, 3), 3, "config3-full")
+    full, early = llama_subsets(w, 3)
+    run_fullsize(w, "adamw", B.make_hyper(), 3, full, 3, "config3-full", early)
 
 
 def test_config4_full_size_llama3_8b_lion_bf16_grads():
     w = W.config4()
     hp = B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1)
-    run_fullsize(w, "lion", hp, 3, llama_subset(w, 3), 3, "config4-full")
+    full, early = llama_subsets(w, 3)
+    run_fullsize(w, "lion", hp, 3, full, 3, "config4-full", early)
 
 
 def test_config5_full_size_ragged_stress():
@@ -124,4 +130,5 @@ def test_config5_full_size_ragged_stress():
     subset = sorted(set([int(order[0]), int(order[1]), int(order[-2])] +          # smallest two, largest ragged
                         [int(i) for i in rng.choice(20000, 150, replace=False)] +
                         [20000]))                                                  # the 128256x4096 tensor
-    run_fullsize(w, "adamw", B.make_hyper(), 2, subset, 2, "config5-full")
+    early = [i for i in subset if w.numels[i] <= (1 << 20)]
+    run_fullsize(w, "adamw", B.make_hyper(), 2, subset, 2, "config5-full", early)

@@ -21,6 +21,9 @@ ADAMW = 0
 LION = 1
 GRAD_F32 = 0
 GRAD_BF16 = 1
+MODE_ADAGC = 0          # Alg. 1
+MODE_GLOBALGC = 1       # Eq. 2 on every step
+MODE_GLOBAL_ADAGC = 2   # one adaptive threshold for the whole model (ablation of Sec. 5.4)
 
 
 class _OptHyper(ctypes.Structure):
@@ -33,7 +36,8 @@ class _StepHyper(ctypes.Structure):
                 ("eps", ctypes.c_double), ("weight_decay", ctypes.c_double),
                 ("lambda_rel", ctypes.c_double), ("ema_beta", ctypes.c_double),
                 ("lambda_abs", ctypes.c_double), ("t_start", ctypes.c_int64),
-                ("optimizer", ctypes.c_int32), ("grad_dtype", ctypes.c_int32)]
+                ("optimizer", ctypes.c_int32), ("grad_dtype", ctypes.c_int32),
+                ("clip_mode", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 def _f32(x):
@@ -57,6 +61,7 @@ class Hyper:
     t_start: int = 1
     optimizer: int = ADAMW
     grad_dtype: int = GRAD_F32
+    clip_mode: int = MODE_ADAGC
 
     def _opt(self):
         return _OptHyper(_f32(self.lr), _f32(self.beta1), _f32(self.beta2), _f32(self.eps),
@@ -66,7 +71,7 @@ class Hyper:
         return _StepHyper(_f32(self.lr), _f32(self.beta1), _f32(self.beta2), _f32(self.eps),
                           _f32(self.weight_decay), _f32(self.lambda_rel), _f32(self.ema_beta),
                           _f32(self.lambda_abs), int(self.t_start), int(self.optimizer),
-                          int(self.grad_dtype))
+                          int(self.grad_dtype), int(self.clip_mode), 0)
 
 
 def lib():

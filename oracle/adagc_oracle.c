@@ -10,6 +10,10 @@
  *   - l2 norm of one gradient tensor ............ Sec. 4.1 (notation), Eq. 3
  *   - AdaGC coefficient h_{t,i} and EMA gamma .... Eq. 3, Alg. 1 (AdaGC branch)
  *   - warm-up: GlobalGC + running minimum ........ Eq. 2, Alg. 1 (warm-up branch)
+ *   - GlobalGC on every step (the baseline) ...... Eq. 2
+ *   - "Global AdaGC" (one adaptive threshold for the whole model; ablation
+ *     "Adaptivity Efficacy and Locality Granularity", Sec. 5.4): Eq. 3 and the
+ *     warm-up branch applied to the global norm with a single gamma
  *   - AdamW moments, bias correction, update ..... Alg. 1 (last four statements)
  * What the paper does not print and is taken from its citation:
  *   - Lion update rule (Chen et al., "Symbolic discovery of optimization
@@ -185,6 +189,9 @@ typedef struct {
     int64_t t_start;                            /* number of warm-up steps                  */
     int32_t optimizer;                          /* 0 = AdamW, 1 = Lion                      */
     int32_t grad_dtype;                         /* 0 = float32, 1 = bf16                    */
+    int32_t clip_mode;                          /* 0 = AdaGC (Alg. 1), 1 = GlobalGC on every step (Eq. 2),
+                                                   2 = Global AdaGC (single gamma, kept in gamma[0]) */
+    int32_t reserved;
 } oracle_step_hyper;
 
 /* Arrays of per-tensor pointers; state is updated in place.  v may be NULL for
@@ -204,29 +211,53 @@ int oracle_adagc_step(int64_t n_tensors, const int64_t *numel, float *const *the
     oracle_opt_hyper oh = { hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay };
     int warmup = (step - 1) < hp->t_start; /* steps 1..T_start */
 
+    const int mode = hp->clip_mode;
+    if (mode < 0 || mode > 2)
+        return -1;
+
+    /* ||g_t|| over the whole model: tensors in list order, elements in index order */
     double h_global = 1.0;
-    if (warmup) {
-        /* ||g_t|| over the whole model: tensors in list order, elements in index order */
+    int clipped_global = 0;
+    if (warmup || mode != 0) {
         double s = 0.0;
         for (int64_t i = 0; i < n_tensors; ++i)
             s += oracle_sum_squares(grad[i], numel[i], hp->grad_dtype);
-        h_global = oracle_globalgc_coef(sqrt(s), hp->lambda_abs);
+        double global_norm = sqrt(s);
+        if (mode == 2 && !warmup) {
+            /* Eq. 3 with the model as the single "tensor" */
+            double gamma_new;
+            oracle_adagc_rule(global_norm, (double)gamma[0], hp->lambda_rel, hp->ema_beta, &h_global,
+                              &gamma_new, &clipped_global);
+            gamma[0] = (float)gamma_new;
+        } else {
+            h_global = oracle_globalgc_coef(global_norm, hp->lambda_abs);
+            clipped_global = (h_global < 1.0);
+            if (mode == 2)
+                gamma[0] = (float)oracle_warmup_gamma((double)gamma[0], h_global * global_norm, step == 1);
+        }
     }
 
     for (int64_t i = 0; i < n_tensors; ++i) {
         double norm = oracle_l2_norm(grad[i], numel[i], hp->grad_dtype);
-        double gamma_prev = (double)gamma[i];
-        double h, gamma_new;
+        double h;
         int clipped;
-        if (warmup) {
+        if (mode != 0) {
+            /* one coefficient for every tensor; no per-tensor state */
             h = h_global;
-            clipped = (h_global < 1.0);
-            gamma_new = oracle_warmup_gamma(gamma_prev, h * norm, step == 1);
+            clipped = clipped_global;
         } else {
-            oracle_adagc_rule(norm, gamma_prev, hp->lambda_rel, hp->ema_beta, &h, &gamma_new,
-                              &clipped);
+            double gamma_prev = (double)gamma[i];
+            double gamma_new;
+            if (warmup) {
+                h = h_global;
+                clipped = clipped_global;
+                gamma_new = oracle_warmup_gamma(gamma_prev, h * norm, step == 1);
+            } else {
+                oracle_adagc_rule(norm, gamma_prev, hp->lambda_rel, hp->ema_beta, &h, &gamma_new,
+                                  &clipped);
+            }
+            gamma[i] = (float)gamma_new;
         }
-        gamma[i] = (float)gamma_new;
         if (out_norm) out_norm[i] = norm;
         if (out_coef) out_coef[i] = h;
         if (out_clipped) out_clipped[i] = (uint8_t)clipped;

@@ -501,3 +501,104 @@ def test_enumerate_chunks_covers_every_element_once():
         for i in range(len(numels)):
             own = chunks[begin[i]:begin[i + 1]]
             assert all(c[0] == i for c in own) and len(own) == -(-numels[i] // chunk)
+
+
+# ------------------------------------------------------------------ global-statistic modes (Eq. 2; Sec. 5.4 ablation)
+
+def test_globalgc_mode_hand_worked_and_equals_endless_warmup():
+    """Mode GlobalGC applies Eq. 2 on every step and keeps no per-tensor state.  Tensors [3,4] and
+    [12]: global norm 13, lambda_abs 6.5 -> h = 1/2.  The same numbers come out of Alg. 1's warm-up
+    branch when T_start never ends."""
+    def fresh():
+        return (_lists([[1, 1], [1]]), _lists([[0, 0], [0]]), _lists([[0, 0], [0]]))
+    g = _lists([[3, 4], [12]])
+    th_a, m_a, v_a = fresh()
+    gam_a = np.array([7.0, 9.0], np.float32)
+    hp_a = Hyper(lr=0.25, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.0, lambda_abs=6.5, t_start=0,
+                 clip_mode=oracle.MODE_GLOBALGC)
+    norms, coefs, clipped = oracle.adagc_step(th_a, g, m_a, v_a, gam_a, hp_a, 5)
+    assert list(norms) == [5.0, 12.0] and list(coefs) == [0.5, 0.5] and list(clipped) == [1, 1]
+    assert list(gam_a) == [7.0, 9.0]                      # untouched
+    th_b, m_b, v_b = fresh()
+    gam_b = np.array([7.0, 9.0], np.float32)
+    hp_b = Hyper(lr=0.25, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.0, lambda_abs=6.5, t_start=1000)
+    oracle.adagc_step(th_b, g, m_b, v_b, gam_b, hp_b, 5)
+    for x, y in zip(th_a + m_a + v_a, th_b + m_b + v_b):
+        assert np.array_equal(x, y)
+    assert list(m_a[0]) == [0.75, 1.0] and list(m_a[1]) == [3.0]
+    # below the threshold nothing is clipped
+    hp_a.lambda_abs = 13.0
+    norms, coefs, clipped = oracle.adagc_step(th_a, g, m_a, v_a, gam_a, hp_a, 6)
+    assert list(coefs) == [1.0, 1.0] and list(clipped) == [0, 0]
+
+
+def test_global_adagc_on_one_tensor_is_adagc():
+    """With a single tensor the model's norm is the tensor's norm: both modes must agree bit for bit,
+    through the warm-up and after it."""
+    rng = np.random.default_rng(20)
+    n = 50
+    def run(mode):
+        r = np.random.default_rng(21)
+        theta = [r.standard_normal(n).astype(np.float32)]
+        m, v = [np.zeros(n, np.float32)], [np.zeros(n, np.float32)]
+        gamma = np.zeros(1, np.float32)
+        hp = Hyper(lambda_abs=0.9, t_start=3, clip_mode=mode)
+        out = []
+        for step in range(1, 12):
+            scale = 10.0 if step in (2, 7) else (0.3 if step == 9 else 1.0)
+            g = [(r.standard_normal(n) * 0.1 * scale).astype(np.float32)]
+            out.append(oracle.adagc_step(theta, g, m, v, gamma, hp, step) + (gamma.copy(),))
+        return theta, m, v, out
+    a, b = run(oracle.MODE_ADAGC), run(oracle.MODE_GLOBAL_ADAGC)
+    for x, y in zip(a[0] + a[1] + a[2], b[0] + b[1] + b[2]):
+        assert np.array_equal(x, y)
+    flags = []
+    for (na, ca, fa, ga), (nb, cb, fb, gb) in zip(a[3], b[3]):
+        assert na[0] == nb[0] and ca[0] == cb[0] and fa[0] == fb[0] and ga[0] == gb[0]
+        flags.append(int(fa[0]))
+    assert 0 < sum(flags) < len(flags)
+
+
+def test_global_adagc_on_a_list_is_adagc_on_the_concatenation():
+    rng = np.random.default_rng(22)
+    sizes = [3, 17, 1, 40]
+    hp_g = Hyper(t_start=0, clip_mode=oracle.MODE_GLOBAL_ADAGC)
+    hp_t = Hyper(t_start=0)
+    theta = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    m = [rng.standard_normal(n).astype(np.float32) * 0.01 for n in sizes]
+    v = [(rng.standard_normal(n).astype(np.float32) * 0.01) ** 2 for n in sizes]
+    g = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    cat = lambda xs: [np.concatenate(xs)]
+    th_c, m_c, v_c, g_c = cat(theta), cat(m), cat(v), cat(g)
+    gamma_g = np.array([0.5, 123.0, 456.0, 789.0], np.float32)      # only element 0 is the model's gamma
+    gamma_c = np.array([0.5], np.float32)
+    n_g, c_g, f_g = oracle.adagc_step(theta, g, m, v, gamma_g, hp_g, 4)
+    n_c, c_c, f_c = oracle.adagc_step(th_c, g_c, m_c, v_c, gamma_c, hp_t, 4)
+    assert f_c[0] == 1 and f_g.all()
+    assert len(set(c_g.tolist())) == 1 and c_g[0] == pytest.approx(c_c[0], rel=1e-14)
+    assert gamma_g[0] == gamma_c[0] and list(gamma_g[1:]) == [123.0, 456.0, 789.0]
+    np.testing.assert_allclose(np.concatenate(theta), th_c[0], rtol=1e-6, atol=1e-9)
+    np.testing.assert_allclose(np.concatenate(m), m_c[0], rtol=1e-6, atol=1e-9)
+    # the model's clipped norm equals lambda_rel * gamma
+    total = math.sqrt(sum(oracle.sum_squares(x) for x in g))
+    assert c_g[0] * total == pytest.approx(f32(1.04) * 0.5, rel=1e-12)
+
+
+def test_global_adagc_warmup_sets_then_minimises_the_single_gamma():
+    theta, m, v = _lists([[0, 0], [0]]), _lists([[0, 0], [0]]), _lists([[0, 0], [0]])
+    gamma = np.array([99.0, 55.0], np.float32)
+    hp = Hyper(lr=0.0, lambda_abs=6.5, t_start=2, lambda_rel=2.0, ema_beta=0.5, clip_mode=oracle.MODE_GLOBAL_ADAGC)
+    n, c, f = oracle.adagc_step(theta, _lists([[3, 4], [12]]), m, v, gamma, hp, 1)      # ||g|| = 13 -> h = 1/2
+    assert list(c) == [0.5, 0.5] and list(gamma) == [6.5, 55.0]
+    n, c, f = oracle.adagc_step(theta, _lists([[0, 3], [4]]), m, v, gamma, hp, 2)       # ||g|| = 5, no clip
+    assert list(c) == [1.0, 1.0] and list(gamma) == [5.0, 55.0]
+    n, c, f = oracle.adagc_step(theta, _lists([[6, 8], [0]]), m, v, gamma, hp, 3)       # Eq. 3: 10 = 2*5, tie
+    assert list(c) == [1.0, 1.0] and list(f) == [0, 0] and gamma[0] == 7.5
+    n, c, f = oracle.adagc_step(theta, _lists([[18, 24], [0]]), m, v, gamma, hp, 4)     # 30 > 15 -> h = 1/2
+    assert list(c) == [0.5, 0.5] and list(f) == [1, 1] and gamma[0] == 0.5 * 7.5 + 0.5 * 15.0
+
+
+def test_step_rejects_unknown_mode():
+    theta, m, v = _lists([[1]]), _lists([[0]]), _lists([[0]])
+    with pytest.raises(ValueError):
+        oracle.adagc_step(theta, _lists([[1]]), m, v, np.zeros(1, np.float32), Hyper(clip_mode=3), 1)

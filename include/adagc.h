@@ -50,6 +50,13 @@ extern "C" {
 #define ADAGC_GRAD_F32  0
 #define ADAGC_GRAD_BF16 1
 
+/* Which clipping rule adagc_step applies (adagc_hyper.clip_mode). */
+#define ADAGC_MODE_ADAGC         0  /* Alg. 1: GlobalGC warm-up for t_start steps, then per-tensor Eq. 3 */
+#define ADAGC_MODE_GLOBALGC      1  /* Eq. 2 on every step (the paper's baseline); keeps no state */
+#define ADAGC_MODE_GLOBAL_ADAGC  2  /* one adaptive threshold for the whole model (ablation "adaptive but
+                                       non-local", Sec. 5.4): Eq. 3 and the warm-up branch applied to the
+                                       model's norm; its single gamma lives in ema_norms[0] */
+
 typedef struct adagc_ctx adagc_ctx; /* opaque; created by adagc_create, freed by adagc_destroy */
 
 /* One parameter tensor = one clipping unit (Sec. 4.2: "each parameter tensor";
@@ -89,6 +96,7 @@ typedef struct {
     float   lambda_abs;    /* GlobalGC threshold of the warm-up (Eq. 2); +inf disables it */
     int32_t t_start;       /* number of warm-up steps: steps 1..t_start take the warm-up branch.
                               0 = never (ema_norms must then be pre-filled by the caller) */
+    int32_t clip_mode;     /* ADAGC_MODE_*; 0 = the paper's method */
 } adagc_hyper;
 
 /* Elements per chunk of the segment table (a compile-time constant of the library). */
@@ -140,7 +148,8 @@ int adagc_set_param_copies(adagc_ctx* ctx, void* const* params_bf16);
  *   grads       HOST array of n_tensors DEVICE pointers, fp32 or bf16 per cfg, read only   (g_t)
  *   exp_avg     HOST array of n_tensors DEVICE pointers, fp32, updated in place      (m)
  *   exp_avg_sq  HOST array of n_tensors DEVICE pointers, fp32, updated in place      (v); NULL for Lion
- *   ema_norms   DEVICE fp32[n_tensors], updated in place                              (gamma_i)
+ *   ema_norms   DEVICE fp32[n_tensors], updated in place                              (gamma_i);
+ *               ADAGC_MODE_GLOBAL_ADAGC uses element 0 only, ADAGC_MODE_GLOBALGC none
  *   hp          HOST hyper-parameters of this step
  *   step        1-based t of Alg. 1: drives the bias correction and the warm-up test
  *   stream      hipStream_t (NULL = the default stream)

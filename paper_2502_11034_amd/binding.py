@@ -21,6 +21,7 @@ ADAGC_ERR_STATE = -5
 
 ADAGC_OPT_ADAMW, ADAGC_OPT_LION = 0, 1
 ADAGC_GRAD_F32, ADAGC_GRAD_BF16 = 0, 1
+ADAGC_MODE_ADAGC, ADAGC_MODE_GLOBALGC, ADAGC_MODE_GLOBAL_ADAGC = 0, 1, 2
 
 EXPORTS = [
     "adagc_chunk_elems", "adagc_build_segment_table", "adagc_create", "adagc_destroy",
@@ -44,7 +45,7 @@ class adagc_hyper(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
                 ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
                 ("lambda_rel", ctypes.c_float), ("ema_beta", ctypes.c_float),
-                ("lambda_abs", ctypes.c_float), ("t_start", ctypes.c_int32)]
+                ("lambda_abs", ctypes.c_float), ("t_start", ctypes.c_int32), ("clip_mode", ctypes.c_int32)]
 
 
 class AdagcError(RuntimeError):
@@ -222,5 +223,6 @@ class AdaGC:
 
 
 def make_hyper(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, lambda_rel=1.04,
-               ema_beta=0.99, lambda_abs=float("inf"), t_start=1):
-    return adagc_hyper(lr, beta1, beta2, eps, weight_decay, lambda_rel, ema_beta, lambda_abs, int(t_start))
+               ema_beta=0.99, lambda_abs=float("inf"), t_start=1, clip_mode=ADAGC_MODE_ADAGC):
+    return adagc_hyper(lr, beta1, beta2, eps, weight_decay, lambda_rel, ema_beta, lambda_abs, int(t_start),
+                       int(clip_mode))

@@ -48,6 +48,8 @@ struct RuleArgs {
     double ema_beta;
     double lambda_abs;
     int    first_step;   // step == 1: gamma is set, not min-ed
+    int    warmup;       // step <= t_start
+    int    mode;         // ADAGC_MODE_*
 };
 
 // Scalars of the elementwise update, precomputed on the host in double.
@@ -69,7 +71,7 @@ struct DeviceTables {
     const TensorArgs* targs;
     double*           partials;   // one per chunk
     double*           sumsq;      // one per tensor
-    double*           global;     // [0] = global sum of squares, [1] = global coefficient
+    double*           global;     // [0] = model's sum of squares, [1] = its coefficient, [2] = 1 if clipped
     float*            norm;       // per tensor, pre-clip
     float*            coef;       // per tensor, fp32
     double*           coef64;     // per tensor, as computed
@@ -82,7 +84,7 @@ struct DeviceTables {
 // nt: bit 0 = non-temporal loads, bit 1 = non-temporal stores
 hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int nt, int grid, hipStream_t stream);
 hipError_t launch_finalize_adagc(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
-hipError_t launch_finalize_warmup(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
+hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
 hipError_t launch_update(const DeviceTables& t, const UpdateArgs& u, int optimizer, int grad_bf16,
                          int with_copy, int unroll, int nt, int grid, hipStream_t stream);
 

@@ -69,6 +69,7 @@ bool hyper_ok(const adagc_hyper& h, int optimizer)
     if (!(h.lambda_rel >= 0.0f)) return false;    // +inf allowed, NaN not
     if (!(h.lambda_abs > 0.0f)) return false;     // +inf allowed, NaN not
     if (h.t_start < 0) return false;
+    if (h.clip_mode < ADAGC_MODE_ADAGC || h.clip_mode > ADAGC_MODE_GLOBAL_ADAGC) return false;
     return true;
 }
 
@@ -167,7 +168,7 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     const size_t o_targs = carve(nt * sizeof(TensorArgs));
     const size_t o_partials = carve(nc * sizeof(double));
     const size_t o_sumsq = carve(nt * sizeof(double));
-    const size_t o_global = carve(2 * sizeof(double));
+    const size_t o_global = carve(4 * sizeof(double));
     const size_t o_coef64 = carve(nt * sizeof(double));
     const size_t o_norm = carve(nt * sizeof(float));
     const size_t o_coef = carve(nt * sizeof(float));
@@ -319,6 +320,7 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
     r.ema_beta = (double)hp->ema_beta;
     r.lambda_abs = (double)hp->lambda_abs;
     r.first_step = (step == 1) ? 1 : 0;
+    r.mode = hp->clip_mode;
     UpdateArgs u;
     u.beta1 = hp->beta1;
     u.one_minus_beta1 = (float)(1.0 - b1);
@@ -334,14 +336,16 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
     u.one_minus_beta1_d = 1.0 - b1;
 
     const bool warmup = (step - 1) < (int64_t)hp->t_start;   // steps 1..t_start
+    r.warmup = warmup ? 1 : 0;
+    const bool global_rule = warmup || hp->clip_mode != ADAGC_MODE_ADAGC;
     const bool prof = ctx->prof_steps < ctx->prof_capacity;
     hipEvent_t* ev = prof ? &ctx->prof_events[(size_t)ctx->prof_steps * 4] : nullptr;
 
     if (prof && hipEventRecord(ev[0], stream) != hipSuccess) return ADAGC_ERR_HIP;
     if (launch_sumsq_partials(ctx->tables, bf16g, ctx->nontemporal, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
     if (prof && hipEventRecord(ev[1], stream) != hipSuccess) return ADAGC_ERR_HIP;
-    hipError_t e = warmup ? launch_finalize_warmup(ctx->tables, ema_norms, r, stream)
-                          : launch_finalize_adagc(ctx->tables, ema_norms, r, stream);
+    hipError_t e = global_rule ? launch_finalize_global(ctx->tables, ema_norms, r, stream)
+                               : launch_finalize_adagc(ctx->tables, ema_norms, r, stream);
     if (e != hipSuccess) return ADAGC_ERR_HIP;
     if (prof && hipEventRecord(ev[2], stream) != hipSuccess) return ADAGC_ERR_HIP;
     if (launch_update(ctx->tables, u, ctx->cfg.optimizer, bf16g, copy, ctx->unroll, ctx->nontemporal,

@@ -2,8 +2,10 @@
 //
 //   sumsq_partials_kernel   per chunk:   sum of g^2 in fp64                        (Sec. 4.1, Eq. 3)
 //   finalize_adagc_kernel   per tensor:  norm, h_i, clip flag, EMA update          (Eq. 3, Alg. 1)
-//   tensor_sumsq_kernel / global_coef_kernel / finalize_warmup_kernel
-//                           warm-up branch: GlobalGC + running minimum             (Eq. 2, Alg. 1)
+//   tensor_sumsq_kernel / global_rule_kernel / finalize_global_kernel
+//                           one coefficient for the whole model: warm-up branch of Alg. 1
+//                           (GlobalGC + running minimum), GlobalGC on every step (Eq. 2),
+//                           Global AdaGC (Eq. 3 on the model's norm; Sec. 5.4 ablation)
 //   update_kernel           per chunk:   clipped gradient into AdamW / Lion        (Alg. 1)
 //
 // Nothing here is a dense contraction, so there is no MFMA: the streaming kernels
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(kBlock) void finalize_adagc_kernel(DeviceTables t, 
     ema[i] = (float)gamma_new;
 }
 
-// Warm-up branch, stage 1: per-tensor sum of squares only.
+// Global stage 1: per-tensor sum of squares only.
 __global__ __launch_bounds__(kBlock) void tensor_sumsq_kernel(DeviceTables t)
 {
     __shared__ double wave_sums[kWavesPerBlock];
@@ -265,8 +267,11 @@ __global__ __launch_bounds__(kBlock) void tensor_sumsq_kernel(DeviceTables t)
     if (threadIdx.x == 0) t.sumsq[i] = s;
 }
 
-// Warm-up branch, stage 2: global norm over all tensors (fixed order) and the coefficient of Eq. 2.
-__global__ __launch_bounds__(kBlock) void global_coef_kernel(DeviceTables t, RuleArgs r)
+// Global stage 2: the model's norm over all tensors (fixed order) and one coefficient for the
+// whole model.  Warm-up steps and the GlobalGC mode use Eq. 2; the Global AdaGC mode applies Eq. 3
+// (and, during warm-up, the running minimum of Alg. 1) to the model's norm with the single gamma
+// kept in ema[0].
+__global__ __launch_bounds__(kBlock) void global_rule_kernel(DeviceTables t, float* ema, RuleArgs r)
 {
     __shared__ double wave_sums[kWavesPerBlock];
     const int tid = threadIdx.x;
@@ -275,33 +280,59 @@ __global__ __launch_bounds__(kBlock) void global_coef_kernel(DeviceTables t, Rul
     double s = wave_sum_f64(acc);
     if ((tid & 63) == 0) wave_sums[tid >> 6] = s;
     __syncthreads();
-    if (tid == 0) {
-        double total = wave_sums[0];
+    if (tid != 0) return;
+    double total = wave_sums[0];
 #pragma unroll
-        for (int w = 1; w < kWavesPerBlock; ++w) total += wave_sums[w];
-        const double gnorm = sqrt(total);
-        const bool active = gnorm > r.lambda_abs;
-        t.global[0] = total;
-        t.global[1] = active ? __ddiv_rn(r.lambda_abs, gnorm) : 1.0;
+    for (int w = 1; w < kWavesPerBlock; ++w) total += wave_sums[w];
+    const double gnorm = sqrt(total);
+    double h;
+    bool active, clipped;
+    if (r.mode == ADAGC_MODE_GLOBAL_ADAGC && !r.warmup) {
+        const double gamma_prev = (double)ema[0];
+        const double threshold = __dmul_rn(r.lambda_rel, gamma_prev);
+        active = gnorm > threshold;
+        h = active ? __ddiv_rn(threshold, gnorm) : 1.0;
+        const double clipped_norm = active ? threshold : gnorm;
+        ema[0] = (float)__dadd_rn(__dmul_rn(r.ema_beta, gamma_prev),
+                                  __dmul_rn(__dsub_rn(1.0, r.ema_beta), clipped_norm));
+        clipped = active;
+    } else {
+        active = gnorm > r.lambda_abs;
+        h = active ? __ddiv_rn(r.lambda_abs, gnorm) : 1.0;
+        clipped = h < 1.0;
+        if (r.mode == ADAGC_MODE_GLOBAL_ADAGC) {
+            const double clipped_norm = __dmul_rn(h, gnorm);
+            const double gamma_prev = (double)ema[0];
+            double gamma_new = clipped_norm;
+            if (!r.first_step) gamma_new = clipped_norm < gamma_prev ? clipped_norm : gamma_prev;
+            ema[0] = (float)gamma_new;
+        }
     }
+    t.global[0] = total;
+    t.global[1] = h;
+    t.global[2] = clipped ? 1.0 : 0.0;
 }
 
-// Warm-up branch, stage 3: gamma_i = min{gamma_i, h*n_i}, or h*n_i on the first step.
-__global__ __launch_bounds__(kBlock) void finalize_warmup_kernel(DeviceTables t, float* ema, RuleArgs r)
+// Global stage 3: every tensor takes the model's coefficient.  In the AdaGC mode (warm-up branch
+// of Alg. 1) gamma_i = min{gamma_i, h*n_i}, or h*n_i on the first step; the global modes keep no
+// per-tensor state.
+__global__ __launch_bounds__(kBlock) void finalize_global_kernel(DeviceTables t, float* ema, RuleArgs r)
 {
     const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
     if (i >= t.n_tensors) return;
     const double h = t.global[1];
     const double norm = sqrt(t.sumsq[i]);
-    const double clipped_norm = __dmul_rn(h, norm);
-    const double gamma_prev = (double)ema[i];
-    double gamma_new = clipped_norm;
-    if (!r.first_step) gamma_new = clipped_norm < gamma_prev ? clipped_norm : gamma_prev;
     t.norm[i] = (float)norm;
     t.coef[i] = (float)h;
     t.coef64[i] = h;
-    t.flag[i] = (h < 1.0) ? 1 : 0;
-    ema[i] = (float)gamma_new;
+    t.flag[i] = (t.global[2] != 0.0) ? 1 : 0;
+    if (r.mode == ADAGC_MODE_ADAGC) {
+        const double clipped_norm = __dmul_rn(h, norm);
+        const double gamma_prev = (double)ema[i];
+        double gamma_new = clipped_norm;
+        if (!r.first_step) gamma_new = clipped_norm < gamma_prev ? clipped_norm : gamma_prev;
+        ema[i] = (float)gamma_new;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -500,16 +531,16 @@ hipError_t launch_finalize_adagc(const DeviceTables& t, float* ema, const RuleAr
     return hipGetLastError();
 }
 
-hipError_t launch_finalize_warmup(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream)
+hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream)
 {
     tensor_sumsq_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    global_coef_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(t, r);
+    global_rule_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(t, ema, r);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const uint32_t blocks = (t.n_tensors + kBlock - 1) / kBlock;
-    finalize_warmup_kernel<<<dim3(blocks), dim3(kBlock), 0, stream>>>(t, ema, r);
+    finalize_global_kernel<<<dim3(blocks), dim3(kBlock), 0, stream>>>(t, ema, r);
     return hipGetLastError();
 }
 

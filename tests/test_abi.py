@@ -29,7 +29,7 @@ def test_header_symbols_are_exported():
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.adagc_tensor_desc) == 16
     assert ctypes.sizeof(B.adagc_config) == 28
-    assert ctypes.sizeof(B.adagc_hyper) == 36
+    assert ctypes.sizeof(B.adagc_hyper) == 40
 
 
 def test_strerror():

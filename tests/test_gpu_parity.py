@@ -40,7 +40,8 @@ def trajectory(run, hp, steps, name, lockstep=False):
         ref_norms, ref_coefs, ref_flags, thr = run.oracle_step(grads_np, hp, step)
         warm = (step - 1) < hp.t_start
         P.check_scalars("%s step %d" % (name, step), norms, coefs, flags, to_numpy(run.gamma),
-                        ref_norms, ref_coefs, ref_flags, run.h_gamma, None if warm else thr)
+                        ref_norms, ref_coefs, ref_flags, run.h_gamma,
+                        None if (warm or hp.clip_mode != B.ADAGC_MODE_ADAGC) else thr)
         exempt = None
         if run.optimizer == B.ADAGC_OPT_LION:
             exempt = [run.lion_exempt(i, grads_np[i], m_before[i], ref_coefs[i], hp)
@@ -250,6 +251,53 @@ def test_warmup_branch_global_clip_and_running_min():
     run.compare_state("warmup")
 
 
+def test_globalgc_mode_every_step():
+    """Eq. 2 on every step: one coefficient for the model, no state."""
+    specs = W.gpt2_like_list(2, 128, 512, 1024, 0)
+    w = W.Workload(specs, sigma_lo=1e-2, sigma_hi=1e-1, spikes={3: (np.arange(0, len(specs), 2), 20.0)})
+    run = P.Run(w)
+    g2 = w.make_grads(2, DEV)
+    total = math.sqrt(sum(float((g.double() ** 2).sum()) for g in g2))
+    hp = B.make_hyper(lambda_abs=2.0 * total, t_start=0, clip_mode=B.ADAGC_MODE_GLOBALGC)
+    run.gamma.fill_(3.0)
+    run.h_gamma[:] = 3.0
+    for step in range(1, 6):
+        grads = w.make_grads(step, DEV)
+        norms, coefs, flags = run.gpu_step(grads, hp, step)
+        rn, rc, rf, _ = run.oracle_step([to_numpy(g) for g in grads], hp, step)
+        P.check_scalars("globalgc step %d" % step, norms, coefs, flags, to_numpy(run.gamma), rn, rc, rf, run.h_gamma)
+        assert len(set(coefs.tolist())) == 1
+        assert bool(rf.all()) == (step == 3) and bool(rf.any()) == (step == 3)
+    assert (to_numpy(run.gamma) == 3.0).all()
+    run.compare_state("globalgc")
+
+
+def test_global_adagc_mode_single_adaptive_threshold():
+    """One gamma for the whole model (kept in ema_norms[0]): warm-up with Eq. 2, then Eq. 3 on the
+    model's norm."""
+    specs = W.gpt2_like_list(2, 128, 512, 1024, 0)
+    every = np.arange(len(specs))
+    w = W.Workload(specs, sigma_lo=1e-2, sigma_hi=1e-1, spikes={1: (every, 5.0), 5: (every[::3], 30.0), 8: (every, 0.2)})
+    run = P.Run(w)
+    g2 = w.make_grads(2, DEV)
+    total = math.sqrt(sum(float((g.double() ** 2).sum()) for g in g2))
+    hp = B.make_hyper(lambda_abs=2.0 * total, t_start=2, clip_mode=B.ADAGC_MODE_GLOBAL_ADAGC)
+    run.gamma[1:].fill_(7.0)
+    run.h_gamma[1:] = 7.0
+    seen = []
+    for step in range(1, 10):
+        grads = w.make_grads(step, DEV)
+        norms, coefs, flags = run.gpu_step(grads, hp, step)
+        rn, rc, rf, _ = run.oracle_step([to_numpy(g) for g in grads], hp, step)
+        P.check_scalars("global-adagc step %d" % step, norms, coefs, flags, to_numpy(run.gamma), rn, rc, rf,
+                        run.h_gamma)
+        assert len(set(coefs.tolist())) == 1 and len(set(flags.tolist())) == 1
+        seen.append(int(rf[0]))
+    assert seen[0] == 1 and seen[4] == 1 and 0 in seen
+    assert (to_numpy(run.gamma)[1:] == 7.0).all()
+    run.compare_state("global-adagc")
+
+
 # --------------------------------------------------------------------------- determinism, state, errors
 
 def test_run_to_run_and_permutation_determinism():
@@ -323,6 +371,8 @@ def test_step_errors_leave_state_untouched():
     assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, hp, 0)) == B.ADAGC_ERR_INVALID_ARG
     assert code(lambda: run.ctx.step(run.params, grads, run.m, None, run.gamma, hp, 1)) == B.ADAGC_ERR_INVALID_ARG
     bad = B.make_hyper(beta1=1.0)
+    assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, bad, 1)) == B.ADAGC_ERR_INVALID_ARG
+    bad = B.make_hyper(clip_mode=3)
     assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, bad, 1)) == B.ADAGC_ERR_INVALID_ARG
     bad = B.make_hyper(lambda_rel=float("nan"))
     assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, bad, 1)) == B.ADAGC_ERR_INVALID_ARG

@@ -99,6 +99,9 @@ def lib():
                                           ctypes.POINTER(_OptHyper), i64, vp]
         L.oracle_lion_update.restype = None
         L.oracle_lion_update.argtypes = [vp, vp, vp, i32, i64, dbl, ctypes.POINTER(_OptHyper), vp]
+        L.oracle_state_norms.restype = None
+        L.oracle_state_norms.argtypes = [vp, vp, vp, vp, i64, ctypes.POINTER(dbl), ctypes.POINTER(dbl),
+                                         ctypes.POINTER(dbl)]
         L.oracle_adagc_step.restype = i32
         L.oracle_adagc_step.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp,
                                         ctypes.POINTER(_StepHyper), i64, vp, vp, vp]
@@ -173,6 +176,16 @@ def lion_update(theta, m, g, h, hyper, theta_bf16=None):
                              _check(g, g.dtype, n), _grad_dtype(g), n, float(h),
                              ctypes.byref(oh),
                              None if theta_bf16 is None else _check(theta_bf16, np.uint16, n))
+
+
+def state_norms(theta_before, theta_after, m, v=None):
+    """(||m||, ||v||, ||theta_after - theta_before||) of one tensor, from the stored float32 values."""
+    n = theta_after.size
+    a, b, c = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    lib().oracle_state_norms(_check(theta_before, np.float32, n), _check(theta_after, np.float32, n),
+                             _check(m, np.float32, n), None if v is None else _check(v, np.float32, n), n,
+                             ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    return a.value, b.value, c.value
 
 
 def adagc_step(theta, grad, m, v, gamma, hyper, step, theta_bf16=None):

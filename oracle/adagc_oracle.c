@@ -91,6 +91,30 @@ double oracle_l2_norm(const void *g, int64_t numel, int grad_dtype)
     return sqrt(oracle_sum_squares(g, numel, grad_dtype));
 }
 
+/* ---- per-tensor quantities the paper plots next to the gradient norm (Fig. 2 and the
+ *      optimizer-state figures of the appendix): l2 norms of the first moment, of the
+ *      second moment, and of the parameter update theta_t - theta_{t-1}, all from the
+ *      stored float32 values ------------------------------------------------------------ */
+
+double oracle_l2_norm_of_difference(const float *a, const float *b, int64_t numel)
+{
+    double s = 0.0;
+    for (int64_t j = 0; j < numel; ++j) {
+        double d = (double)a[j] - (double)b[j];
+        s += d * d;
+    }
+    return sqrt(s);
+}
+
+void oracle_state_norms(const float *theta_before, const float *theta_after, const float *m,
+                        const float *v /* may be NULL */, int64_t numel, double *m_norm,
+                        double *v_norm, double *update_norm)
+{
+    *m_norm = oracle_l2_norm(m, numel, 0);
+    *v_norm = v ? oracle_l2_norm(v, numel, 0) : 0.0;
+    *update_norm = oracle_l2_norm_of_difference(theta_after, theta_before, numel);
+}
+
 /* ---- Eq. 3, Alg. 1 AdaGC branch: one tensor's scalars --------------------- */
 
 /* norm = ||g_{t,i}||, gamma_prev = gamma_{t-1,i}.

@@ -602,3 +602,39 @@ def test_step_rejects_unknown_mode():
     theta, m, v = _lists([[1]]), _lists([[0]]), _lists([[0]])
     with pytest.raises(ValueError):
         oracle.adagc_step(theta, _lists([[1]]), m, v, np.zeros(1, np.float32), Hyper(clip_mode=3), 1)
+
+
+# ------------------------------------------------------------------ state norms (Fig. 2 quantities)
+
+def test_state_norms_hand_values_and_library():
+    before = np.array([1.0, 1.0, 1.0], np.float32)
+    after = np.array([4.0, 5.0, 1.0], np.float32)            # update (3, 4, 0)
+    m = np.array([1.0, 2.0, 2.0], np.float32)
+    v = np.array([0.0, 5.0, 12.0], np.float32)
+    assert oracle.state_norms(before, after, m, v) == (3.0, 13.0, 5.0)
+    assert oracle.state_norms(before, after, m) == (3.0, 0.0, 5.0)       # Lion keeps no second moment
+    rng = np.random.default_rng(30)
+    a, b, mm, vv = (rng.standard_normal(1000).astype(np.float32) for _ in range(4))
+    got = oracle.state_norms(a, b, mm, vv)
+    ref = (np.linalg.norm(mm.astype(np.float64)), np.linalg.norm(vv.astype(np.float64)),
+           np.linalg.norm(b.astype(np.float64) - a.astype(np.float64)))
+    assert got == pytest.approx(ref, rel=1e-13)
+    assert oracle.state_norms(a, a, mm, vv)[2] == 0.0
+
+
+def test_state_norms_after_first_adamw_step_closed_form():
+    """m0 = v0 = 0, t = 1: ||m|| = (1-b1)||h g||, ||v|| = (1-b2)||(h g)^2||, and without weight decay
+    every coordinate moves by about lr, so ||update|| ~ lr*sqrt(n)."""
+    rng = np.random.default_rng(31)
+    n = 400
+    hp = Hyper(weight_decay=0.0, eps=0.0)
+    g = (rng.standard_normal(n) * 0.3).astype(np.float32)
+    theta = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    before = theta.copy()
+    m, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    oracle.adamw_update(theta, m, v, g, 0.5, hp, 1)
+    mn, vn, un = oracle.state_norms(before, theta, m, v)
+    gd = 0.5 * g.astype(np.float64)
+    assert mn == pytest.approx((1 - f32(0.9)) * np.linalg.norm(gd), rel=1e-6)
+    assert vn == pytest.approx((1 - f32(0.95)) * np.linalg.norm(gd * gd), rel=1e-6)
+    assert un == pytest.approx(f32(3e-4) * math.sqrt(n), rel=1e-4)

@@ -111,6 +111,10 @@ def main():
     ap.add_argument("--grid-blocks", type=int, default=0, help="launch tuning: workgroups of the persistent grids")
     ap.add_argument("--unroll", type=int, default=0, help="launch tuning: vectors in flight per lane per stream")
     ap.add_argument("--nontemporal", type=int, default=0, help="launch tuning: 1 on, 2 off")
+    ap.add_argument("--schedule", type=int, default=0, help="launch tuning: parts of the visiting order")
+    ap.add_argument("--telemetry", action="store_true", help="also reduce per-tensor |m|, |v|, |update| norms")
+    ap.add_argument("--clip-mode", type=int, default=0, help="0 AdaGC (default), 1 GlobalGC, 2 Global AdaGC")
+    ap.add_argument("--t-start", type=int, default=1, help="warm-up steps (1 = only the initialising step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -129,7 +133,9 @@ def main():
     lion = args.workload == "config4"
     optimizer = B.ADAGC_OPT_LION if lion else B.ADAGC_OPT_ADAMW
     grad_dtype = B.ADAGC_GRAD_BF16 if w.grad_dtype == torch.bfloat16 else B.ADAGC_GRAD_F32
-    hp = (B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1) if lion else B.make_hyper())
+    rule = dict(t_start=args.t_start, clip_mode=args.clip_mode,
+                lambda_abs=1.0 if (args.clip_mode or args.t_start > 1) else float("inf"))
+    hp = (B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1, **rule) if lion else B.make_hyper(**rule))
 
     # Allocation order: gradients, then master params, moments, bf16 copies.  In a fresh process
     # the driver hands out physical memory linearly, and the relative placement of the five arrays
@@ -139,7 +145,8 @@ def main():
     params, m, v, copies = w.make_state(dev, "lion" if lion else "adamw")
     gamma = torch.zeros(w.n_tensors, dtype=torch.float32, device=dev)
     ctx = B.AdaGC(w.numels, optimizer, grad_dtype, w.bf16_copy, grid_blocks=args.grid_blocks,
-                  unroll=args.unroll, nontemporal=args.nontemporal)
+                  unroll=args.unroll, nontemporal=args.nontemporal, schedule=args.schedule,
+                  telemetry=args.telemetry)
     if copies is not None:
         ctx.set_param_copies(copies)
     ptrs = tuple(B.ptr_array(x) if x is not None else None for x in (params, grads, m, v))
@@ -191,7 +198,8 @@ def main():
         "config": {"workload": "%s: %d tensors, %d params, %s grads, %s%s" % (
             args.workload, w.n_tensors, n, "bf16" if grad_dtype else "fp32",
             "Lion fp32 theta/m" if lion else "AdamW fp32 theta/m/v", ", bf16 param copy" if w.bf16_copy else ""),
-            "bytes_per_param_two_pass": rd + ur + uw, "bytes_per_param_each_array_once": ur + uw},
+            "bytes_per_param_two_pass": rd + ur + uw, "bytes_per_param_each_array_once": ur + uw,
+            "clip_mode": args.clip_mode, "t_start": args.t_start, "telemetry": bool(args.telemetry)},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "effective_gbps_each_array_once": round(bytes_once / (ms_per_step * 1e-3) / 1e9, 1),
         "kernels_ms": {"sumsq_partials": round(k_norm, 4), "finalize": round(k_fin, 4), "update": round(k_upd, 4)},

@@ -72,12 +72,15 @@ typedef struct {
     int32_t grad_dtype;           /* ADAGC_GRAD_F32 or ADAGC_GRAD_BF16 (widened exactly in-kernel) */
     int32_t has_bf16_param_copy;  /* 1: every step also writes round-to-nearest-even bf16 copies of the
                                      updated params to the buffers given to adagc_set_param_copies */
+    int32_t telemetry;            /* 1: every step also reduces, inside the update kernel, the per-tensor l2
+                                     norms of the first moment, the second moment and the parameter update
+                                     (the quantities the paper plots per tensor, Fig. 2); read them with
+                                     adagc_get_state_norms.  Costs no extra HBM traffic. */
     /* Launch tuning of the streaming kernels; 0 = library default for each. */
     int32_t grid_blocks;          /* > 0: persistent grid of that many workgroups, each walking chunks
                                      b, b+grid, ...; default: one chunk per workgroup */
     int32_t unroll;               /* 128-bit vectors per lane per stream kept in flight: 1, 2 or 4 (default 2) */
-    int32_t nontemporal;          /* streaming (non-temporal) memory hints: 1 = loads and stores (default),
-                                     2 = off, 3 = loads only, 4 = stores only */
+    int32_t nontemporal;          /* streaming (non-temporal) loads and stores: 1 = on (default), 2 = off */
     int32_t schedule;             /* order in which workgroups visit chunks: 1 = list order; w >= 2 = the list is
                                      cut into w contiguous parts and workgroup b walks part b mod w
                                      (default 8 = the number of XCDs workgroups are dealt to in turn) */
@@ -175,6 +178,15 @@ int adagc_step(adagc_ctx* ctx, void* const* params, const void* const* grads,
  */
 int adagc_get_norms(adagc_ctx* ctx, float* host_norms, float* host_coefs, uint8_t* host_clipped,
                     int64_t n_tensors, void* stream);
+
+/*
+ * Telemetry of the most recently enqueued step (context created with telemetry = 1): per-tensor
+ * l2 norms of the updated first moment m, of the updated second moment v (zeros for Lion) and of
+ * the parameter update theta_t - theta_{t-1}, from the stored fp32 values.  Copies to the host
+ * and waits for `stream`.  Any output may be NULL.  Errors: INVALID_ARG, STATE (telemetry off), HIP.
+ */
+int adagc_get_state_norms(adagc_ctx* ctx, float* host_m_norms, float* host_v_norms,
+                          float* host_update_norms, int64_t n_tensors, void* stream);
 
 /* Number of tensors / chunks of the context's segment table (negative error code for NULL). */
 int64_t adagc_num_tensors(const adagc_ctx* ctx);

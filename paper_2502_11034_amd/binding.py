@@ -25,7 +25,7 @@ ADAGC_MODE_ADAGC, ADAGC_MODE_GLOBALGC, ADAGC_MODE_GLOBAL_ADAGC = 0, 1, 2
 
 EXPORTS = [
     "adagc_chunk_elems", "adagc_build_segment_table", "adagc_create", "adagc_destroy",
-    "adagc_set_param_copies", "adagc_step", "adagc_get_norms", "adagc_num_tensors",
+    "adagc_set_param_copies", "adagc_step", "adagc_get_norms", "adagc_get_state_norms", "adagc_num_tensors",
     "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end",
     "adagc_strerror",
 ]
@@ -37,7 +37,8 @@ class adagc_tensor_desc(ctypes.Structure):
 
 class adagc_config(ctypes.Structure):
     _fields_ = [("optimizer", ctypes.c_int32), ("grad_dtype", ctypes.c_int32),
-                ("has_bf16_param_copy", ctypes.c_int32), ("grid_blocks", ctypes.c_int32),
+                ("has_bf16_param_copy", ctypes.c_int32), ("telemetry", ctypes.c_int32),
+                ("grid_blocks", ctypes.c_int32),
                 ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32), ("schedule", ctypes.c_int32)]
 
 
@@ -82,6 +83,8 @@ def lib():
     L.adagc_step.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(adagc_hyper), i64, vp]
     L.adagc_get_norms.restype = ctypes.c_int
     L.adagc_get_norms.argtypes = [vp, vp, vp, vp, i64, vp]
+    L.adagc_get_state_norms.restype = ctypes.c_int
+    L.adagc_get_state_norms.argtypes = [vp, vp, vp, vp, i64, vp]
     L.adagc_num_tensors.restype = i64
     L.adagc_num_tensors.argtypes = [vp]
     L.adagc_num_chunks.restype = i64
@@ -153,12 +156,12 @@ class AdaGC:
     """Owner of one adagc_ctx.  Methods mirror the C entry points one to one."""
 
     def __init__(self, numels, optimizer=ADAGC_OPT_ADAMW, grad_dtype=ADAGC_GRAD_F32,
-                 has_bf16_param_copy=False, grid_blocks=0, unroll=0, nontemporal=0, schedule=0):
+                 has_bf16_param_copy=False, grid_blocks=0, unroll=0, nontemporal=0, schedule=0, telemetry=False):
         L = lib()
         self._ctx = ctypes.c_void_p(None)
         self.n_tensors = len(numels)
         self.numels = [int(n) for n in numels]
-        cfg = adagc_config(int(optimizer), int(grad_dtype), int(bool(has_bf16_param_copy)),
+        cfg = adagc_config(int(optimizer), int(grad_dtype), int(bool(has_bf16_param_copy)), int(bool(telemetry)),
                            int(grid_blocks), int(unroll), int(nontemporal), int(schedule))
         descs = _descs(self.numels)
         _check(L.adagc_create(ctypes.byref(self._ctx), ctypes.cast(descs, ctypes.c_void_p), self.n_tensors,
@@ -196,6 +199,14 @@ class AdaGC:
         _check(lib().adagc_get_norms(self._ctx, norms.ctypes.data, coefs.ctypes.data, clipped.ctypes.data, n,
                                      ctypes.c_void_p(stream) if stream else None), "adagc_get_norms")
         return norms, coefs, clipped
+
+    # -- adagc_get_state_norms
+    def get_state_norms(self, stream=None):
+        n = self.n_tensors
+        out = [np.zeros(n, dtype=np.float32) for _ in range(3)]
+        _check(lib().adagc_get_state_norms(self._ctx, out[0].ctypes.data, out[1].ctypes.data, out[2].ctypes.data,
+                                           n, ctypes.c_void_p(stream) if stream else None), "adagc_get_state_norms")
+        return tuple(out)
 
     # -- adagc_num_chunks / adagc_get_segment_table
     def num_chunks(self):

@@ -107,7 +107,8 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     if (cfg->optimizer != ADAGC_OPT_ADAMW && cfg->optimizer != ADAGC_OPT_LION) return ADAGC_ERR_INVALID_ARG;
     if (cfg->grad_dtype != ADAGC_GRAD_F32 && cfg->grad_dtype != ADAGC_GRAD_BF16) return ADAGC_ERR_INVALID_ARG;
     if (cfg->has_bf16_param_copy != 0 && cfg->has_bf16_param_copy != 1) return ADAGC_ERR_INVALID_ARG;
-    if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 4 || cfg->schedule < 0)
+    if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 2 || cfg->schedule < 0 ||
+        cfg->telemetry < 0 || cfg->telemetry > 1)
         return ADAGC_ERR_INVALID_ARG;
     if (cfg->unroll != 0 && cfg->unroll != 1 && cfg->unroll != 2 && cfg->unroll != 4) return ADAGC_ERR_INVALID_ARG;
 
@@ -151,10 +152,7 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     //    (workgroup b goes to XCD b mod 8) stream one contiguous eighth of the list: +0.5-1.3 %,
     //    +5 % on the norm kernel.
     c->unroll = cfg->unroll ? cfg->unroll : 2;
-    {   // knob -> bit mask: bit 0 loads, bit 1 stores
-        static const int mask_of[5] = {3, 3, 0, 1, 2};
-        c->nontemporal = mask_of[cfg->nontemporal];
-    }
+    c->nontemporal = cfg->nontemporal == 2 ? 0 : 1;
     const int64_t want = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : c->n_chunks;
     c->grid_norm = (int)(want < c->n_chunks ? want : c->n_chunks);
     c->grid_update = c->grid_norm;
@@ -173,6 +171,8 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     const size_t o_norm = carve(nt * sizeof(float));
     const size_t o_coef = carve(nt * sizeof(float));
     const size_t o_flag = carve(nt);
+    const size_t o_tele_partials = carve(cfg->telemetry ? 3 * nc * sizeof(double) : 0);
+    const size_t o_tele_norm = carve(cfg->telemetry ? 3 * nt * sizeof(float) : 0);
     const size_t slab_bytes = off;
 
     hipError_t e = hipMalloc(&c->slab, slab_bytes);
@@ -234,6 +234,8 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     t.norm = reinterpret_cast<float*>(base + o_norm);
     t.coef = reinterpret_cast<float*>(base + o_coef);
     t.flag = reinterpret_cast<uint8_t*>(base + o_flag);
+    t.tele_partials = cfg->telemetry ? reinterpret_cast<double*>(base + o_tele_partials) : nullptr;
+    t.tele_norm = cfg->telemetry ? reinterpret_cast<float*>(base + o_tele_norm) : nullptr;
     t.n_chunks = (uint32_t)c->n_chunks;
     t.n_tensors = (uint32_t)c->n_tensors;
 
@@ -348,7 +350,7 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
                                : launch_finalize_adagc(ctx->tables, ema_norms, r, stream);
     if (e != hipSuccess) return ADAGC_ERR_HIP;
     if (prof && hipEventRecord(ev[2], stream) != hipSuccess) return ADAGC_ERR_HIP;
-    if (launch_update(ctx->tables, u, ctx->cfg.optimizer, bf16g, copy, ctx->unroll, ctx->nontemporal,
+    if (launch_update(ctx->tables, u, ctx->cfg.optimizer, bf16g, copy, ctx->unroll, ctx->nontemporal, ctx->cfg.telemetry,
                       ctx->grid_update, stream) != hipSuccess)
         return ADAGC_ERR_HIP;
     if (prof) {
@@ -373,6 +375,23 @@ extern "C" int adagc_get_norms(adagc_ctx* ctx, float* host_norms, float* host_co
         return ADAGC_ERR_HIP;
     if (host_clipped && hipMemcpyAsync(host_clipped, t.flag, n, hipMemcpyDeviceToHost, stream) != hipSuccess)
         return ADAGC_ERR_HIP;
+    return hipStreamSynchronize(stream) == hipSuccess ? ADAGC_OK : ADAGC_ERR_HIP;
+}
+
+extern "C" int adagc_get_state_norms(adagc_ctx* ctx, float* host_m_norms, float* host_v_norms,
+                                     float* host_update_norms, int64_t n_tensors, void* stream_v)
+{
+    if (!ctx || n_tensors != ctx->n_tensors) return ADAGC_ERR_INVALID_ARG;
+    if (!ctx->cfg.telemetry) return ADAGC_ERR_STATE;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const size_t n = (size_t)n_tensors;
+    float* out[3] = {host_m_norms, host_v_norms, host_update_norms};
+    for (int q = 0; q < 3; ++q)
+        if (out[q] && hipMemcpyAsync(out[q], ctx->tables.tele_norm + q * n, n * sizeof(float),
+                                     hipMemcpyDeviceToHost, stream) != hipSuccess)
+            return ADAGC_ERR_HIP;
     return hipStreamSynchronize(stream) == hipSuccess ? ADAGC_OK : ADAGC_ERR_HIP;
 }
 

@@ -211,11 +211,12 @@ __global__ __launch_bounds__(kBlock) void sumsq_partials_kernel(DeviceTables t)
 // accumulators (slot row mod 4) so that four loads are in flight; lanes are combined by the
 // wave tree, waves through LDS in wave order.
 
-__device__ __forceinline__ double tensor_sumsq(const DeviceTables& t, uint32_t i, double* wave_sums)
+__device__ __forceinline__ double tensor_slot_sum(const DeviceTables& t, const double* slots, uint32_t i,
+                                                  double* wave_sums)
 {
     const uint32_t begin = t.targs[i].chunk_begin;
     const uint32_t count = t.targs[i].chunk_count;
-    const double* p = t.partials + begin;
+    const double* p = slots + begin;
     double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     uint32_t k = threadIdx.x;
     for (; k + 3 * kBlock < count; k += 4 * kBlock) {
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(kBlock) void finalize_adagc_kernel(DeviceTables t, 
 {
     __shared__ double wave_sums[kWavesPerBlock];
     const uint32_t i = blockIdx.x;
-    const double s = tensor_sumsq(t, i, wave_sums);
+    const double s = tensor_slot_sum(t, t.partials, i, wave_sums);
     if (threadIdx.x != 0) return;
 
     const double norm = sqrt(s);
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(kBlock) void tensor_sumsq_kernel(DeviceTables t)
 {
     __shared__ double wave_sums[kWavesPerBlock];
     const uint32_t i = blockIdx.x;
-    const double s = tensor_sumsq(t, i, wave_sums);
+    const double s = tensor_slot_sum(t, t.partials, i, wave_sums);
     if (threadIdx.x == 0) t.sumsq[i] = s;
 }
 
@@ -387,13 +388,37 @@ __device__ __forceinline__ void apply_vec(const UpdateArgs& a, float h, double h
     s = {p.w, m.w, v.w}; apply_elem<OPT>(a, h, h64, g.w, s); p.w = s.p; m.w = s.m; v.w = s.v;
 }
 
-template <int OPT, bool BF16G, bool COPY, int U, int NT>
+// Telemetry: per-lane fp64 sums of m^2, v^2 and (theta_new - theta_old)^2 over the lane's elements,
+// in element order; they become one slot per chunk and per quantity, reduced per tensor afterwards.
+template <bool HAS_V>
+__device__ __forceinline__ void tele_elem(double (&acc)[3], float p_old, float p_new, float m, float v)
+{
+    const double dm = (double)m;
+    acc[0] = fma(dm, dm, acc[0]);
+    if constexpr (HAS_V) {
+        const double dv = (double)v;
+        acc[1] = fma(dv, dv, acc[1]);
+    }
+    const double du = (double)p_new - (double)p_old;
+    acc[2] = fma(du, du, acc[2]);
+}
+
+template <bool HAS_V>
+__device__ __forceinline__ void tele_vec(double (&acc)[3], f32x4 p_old, f32x4 p_new, f32x4 m, f32x4 v)
+{
+    tele_elem<HAS_V>(acc, p_old.x, p_new.x, m.x, v.x);
+    tele_elem<HAS_V>(acc, p_old.y, p_new.y, m.y, v.y);
+    tele_elem<HAS_V>(acc, p_old.z, p_new.z, m.z, v.z);
+    tele_elem<HAS_V>(acc, p_old.w, p_new.w, m.w, v.w);
+}
+
+template <int OPT, bool BF16G, bool COPY, int U, bool NT, bool TELE>
 __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateArgs a)
 {
-    constexpr bool NTL = (NT & 1) != 0;   // non-temporal loads
-    constexpr bool NTS = (NT & 2) != 0;   // non-temporal stores
+    constexpr bool NTL = NT, NTS = NT;    // non-temporal loads and stores
     constexpr bool kHasV = (OPT == ADAGC_OPT_ADAMW);
     const int tid = threadIdx.x;
+    __shared__ double tele_sums[3][kWavesPerBlock];
 
     for (uint32_t k = blockIdx.x; k < t.n_chunks; k += gridDim.x) {
         const uint32_t c = t.schedule[k];
@@ -407,6 +432,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
         float* m = reinterpret_cast<float*>(ta.exp_avg) + cv.first;
         float* v = kHasV ? reinterpret_cast<float*>(ta.exp_avg_sq) + cv.first : nullptr;
         uint16_t* pc = COPY ? reinterpret_cast<uint16_t*>(ta.param_copy) + cv.first : nullptr;
+        double tele[3] = {0.0, 0.0, 0.0};
 
         if (ta.vec_ok) {
             f32x4* p4 = reinterpret_cast<f32x4*>(p);
@@ -431,7 +457,9 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const int idx = (it + u) * kBlock + tid;
+                        const f32x4 p_old = pp[u];
                         apply_vec<OPT>(a, h, h64, gg[u], pp[u], mm[u], vv[u]);
+                        if constexpr (TELE) tele_vec<kHasV>(tele, p_old, pp[u], mm[u], vv[u]);
                         st<NTS>(p4 + idx, pp[u]);
                         st<NTS>(m4 + idx, mm[u]);
                         if constexpr (kHasV) st<NTS>(v4 + idx, vv[u]);
@@ -445,7 +473,9 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                     f32x4 mm = ld<NTL>(m4 + idx);
                     f32x4 vv = f32x4{0.f, 0.f, 0.f, 0.f};
                     if constexpr (kHasV) vv = ld<NTL>(v4 + idx);
+                    const f32x4 p_old = pp;
                     apply_vec<OPT>(a, h, h64, gg, pp, mm, vv);
+                    if constexpr (TELE) tele_vec<kHasV>(tele, p_old, pp, mm, vv);
                     st<NTS>(p4 + idx, pp);
                     st<NTS>(m4 + idx, mm);
                     if constexpr (kHasV) st<NTS>(v4 + idx, vv);
@@ -454,7 +484,9 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                 const int j = (nvec << 2) + tid;
                 if (j < cv.len) {
                     ElemState s = {p[j], m[j], kHasV ? v[j] : 0.f};
+                    const float p_old = s.p;
                     apply_elem<OPT>(a, h, h64, load_grad1<BF16G>(g, j), s);
+                    if constexpr (TELE) tele_elem<kHasV>(tele, p_old, s.p, s.m, s.v);
                     p[j] = s.p;
                     m[j] = s.m;
                     if constexpr (kHasV) v[j] = s.v;
@@ -464,13 +496,43 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
         } else {
             for (int j = tid; j < cv.len; j += kBlock) {
                 ElemState s = {p[j], m[j], kHasV ? v[j] : 0.f};
+                const float p_old = s.p;
                 apply_elem<OPT>(a, h, h64, load_grad1<BF16G>(g, j), s);
+                if constexpr (TELE) tele_elem<kHasV>(tele, p_old, s.p, s.m, s.v);
                 p[j] = s.p;
                 m[j] = s.m;
                 if constexpr (kHasV) v[j] = s.v;
                 if constexpr (COPY) pc[j] = (uint16_t)float_to_bf16_bits(s.p);
             }
         }
+
+        if constexpr (TELE) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                const double w = wave_sum_f64(tele[q]);
+                if ((tid & 63) == 0) tele_sums[q][tid >> 6] = w;
+            }
+            __syncthreads();
+            if (tid < 3) {
+                double b = tele_sums[tid][0];
+#pragma unroll
+                for (int w = 1; w < kWavesPerBlock; ++w) b += tele_sums[tid][w];
+                t.tele_partials[(size_t)tid * t.n_chunks + c] = b;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Telemetry finalize: per tensor, the three norms from the chunk slots (same fixed order as K2).
+__global__ __launch_bounds__(kBlock) void finalize_telemetry_kernel(DeviceTables t)
+{
+    __shared__ double wave_sums[kWavesPerBlock];
+    const uint32_t i = blockIdx.x;
+    for (int q = 0; q < 3; ++q) {
+        const double s = tensor_slot_sum(t, t.tele_partials + (size_t)q * t.n_chunks, i, wave_sums);
+        if (threadIdx.x == 0) t.tele_norm[(size_t)q * t.n_tensors + i] = (float)sqrt(s);
+        __syncthreads();
     }
 }
 
@@ -478,42 +540,38 @@ using UpdateFn = void (*)(DeviceTables, UpdateArgs);
 using SumsqFn = void (*)(DeviceTables);
 
 template <int OPT, bool BF16G, bool COPY, int U>
-UpdateFn select_update_nt(int nt)
+UpdateFn select_update_flags(int nt, int tele)
 {
-    switch (nt & 3) {
-    case 0: return update_kernel<OPT, BF16G, COPY, U, 0>;
-    case 1: return update_kernel<OPT, BF16G, COPY, U, 1>;
-    case 2: return update_kernel<OPT, BF16G, COPY, U, 2>;
-    default: return update_kernel<OPT, BF16G, COPY, U, 3>;
-    }
+    if (nt) return tele ? update_kernel<OPT, BF16G, COPY, U, true, true> : update_kernel<OPT, BF16G, COPY, U, true, false>;
+    return tele ? update_kernel<OPT, BF16G, COPY, U, false, true> : update_kernel<OPT, BF16G, COPY, U, false, false>;
 }
 
 template <int OPT, bool BF16G, bool COPY>
-UpdateFn select_update_variant(int unroll, int nt)
+UpdateFn select_update_variant(int unroll, int nt, int tele)
 {
-    if (unroll == 4) return select_update_nt<OPT, BF16G, COPY, 4>(nt);
-    if (unroll == 2) return select_update_nt<OPT, BF16G, COPY, 2>(nt);
-    return select_update_nt<OPT, BF16G, COPY, 1>(nt);
+    if (unroll == 4) return select_update_flags<OPT, BF16G, COPY, 4>(nt, tele);
+    if (unroll == 2) return select_update_flags<OPT, BF16G, COPY, 2>(nt, tele);
+    return select_update_flags<OPT, BF16G, COPY, 1>(nt, tele);
 }
 
-UpdateFn select_update(int optimizer, int grad_bf16, int with_copy, int unroll, int nt)
+UpdateFn select_update(int optimizer, int grad_bf16, int with_copy, int unroll, int nt, int tele)
 {
     const int key = (optimizer == ADAGC_OPT_LION ? 4 : 0) | (grad_bf16 ? 2 : 0) | (with_copy ? 1 : 0);
     switch (key) {
-    case 0: return select_update_variant<ADAGC_OPT_ADAMW, false, false>(unroll, nt);
-    case 1: return select_update_variant<ADAGC_OPT_ADAMW, false, true>(unroll, nt);
-    case 2: return select_update_variant<ADAGC_OPT_ADAMW, true, false>(unroll, nt);
-    case 3: return select_update_variant<ADAGC_OPT_ADAMW, true, true>(unroll, nt);
-    case 4: return select_update_variant<ADAGC_OPT_LION, false, false>(unroll, nt);
-    case 5: return select_update_variant<ADAGC_OPT_LION, false, true>(unroll, nt);
-    case 6: return select_update_variant<ADAGC_OPT_LION, true, false>(unroll, nt);
-    default: return select_update_variant<ADAGC_OPT_LION, true, true>(unroll, nt);
+    case 0: return select_update_variant<ADAGC_OPT_ADAMW, false, false>(unroll, nt, tele);
+    case 1: return select_update_variant<ADAGC_OPT_ADAMW, false, true>(unroll, nt, tele);
+    case 2: return select_update_variant<ADAGC_OPT_ADAMW, true, false>(unroll, nt, tele);
+    case 3: return select_update_variant<ADAGC_OPT_ADAMW, true, true>(unroll, nt, tele);
+    case 4: return select_update_variant<ADAGC_OPT_LION, false, false>(unroll, nt, tele);
+    case 5: return select_update_variant<ADAGC_OPT_LION, false, true>(unroll, nt, tele);
+    case 6: return select_update_variant<ADAGC_OPT_LION, true, false>(unroll, nt, tele);
+    default: return select_update_variant<ADAGC_OPT_LION, true, true>(unroll, nt, tele);
     }
 }
 
 SumsqFn select_sumsq(int grad_bf16, int nt)
 {
-    if (nt & 1) return grad_bf16 ? sumsq_partials_kernel<true, true> : sumsq_partials_kernel<false, true>;
+    if (nt) return grad_bf16 ? sumsq_partials_kernel<true, true> : sumsq_partials_kernel<false, true>;
     return grad_bf16 ? sumsq_partials_kernel<true, false> : sumsq_partials_kernel<false, false>;
 }
 
@@ -545,9 +603,12 @@ hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleA
 }
 
 hipError_t launch_update(const DeviceTables& t, const UpdateArgs& a, int optimizer, int grad_bf16,
-                         int with_copy, int unroll, int nt, int grid, hipStream_t stream)
+                         int with_copy, int unroll, int nt, int tele, int grid, hipStream_t stream)
 {
-    select_update(optimizer, grad_bf16, with_copy, unroll, nt)<<<dim3(grid), dim3(kBlock), 0, stream>>>(t, a);
+    select_update(optimizer, grad_bf16, with_copy, unroll, nt, tele)<<<dim3(grid), dim3(kBlock), 0, stream>>>(t, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !tele) return e;
+    finalize_telemetry_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t);
     return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ def declared_symbols():
 def test_header_symbols_are_exported():
     L = B.lib()
     names = declared_symbols()
-    assert len(names) >= 13
+    assert len(names) >= 14
     for name in names:
         assert hasattr(L, name), name
     assert sorted(B.EXPORTS) == names
@@ -28,7 +28,7 @@ def test_header_symbols_are_exported():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.adagc_tensor_desc) == 16
-    assert ctypes.sizeof(B.adagc_config) == 28
+    assert ctypes.sizeof(B.adagc_config) == 32
     assert ctypes.sizeof(B.adagc_hyper) == 40
 
 
@@ -41,7 +41,7 @@ def test_strerror():
 def _create(numels, **cfg_kw):
     L = B.lib()
     ctx = ctypes.c_void_p(None)
-    fields = dict(optimizer=0, grad_dtype=0, has_bf16_param_copy=0, grid_blocks=0, unroll=0, nontemporal=0, schedule=0)
+    fields = dict(optimizer=0, grad_dtype=0, has_bf16_param_copy=0, telemetry=0, grid_blocks=0, unroll=0, nontemporal=0, schedule=0)
     fields.update(cfg_kw)
     cfg = B.adagc_config(**fields)
     descs = (B.adagc_tensor_desc * max(1, len(numels)))()
@@ -60,6 +60,8 @@ def test_create_validates_before_touching_the_device():
     assert _create([4], has_bf16_param_copy=3)[0] == B.ADAGC_ERR_INVALID_ARG
     assert _create([4], unroll=3)[0] == B.ADAGC_ERR_INVALID_ARG
     assert _create([4], grid_blocks=-1)[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], telemetry=2)[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], nontemporal=3)[0] == B.ADAGC_ERR_INVALID_ARG
     cfg = B.adagc_config()
     assert L.adagc_create(None, None, 1, ctypes.byref(cfg)) == B.ADAGC_ERR_INVALID_ARG
     rc, ctx = _create([4])
@@ -75,6 +77,7 @@ def test_null_context_is_rejected_everywhere():
     hp = B.make_hyper()
     assert L.adagc_step(None, None, None, None, None, None, ctypes.byref(hp), 1, None) == B.ADAGC_ERR_INVALID_ARG
     assert L.adagc_get_norms(None, None, None, None, 1, None) == B.ADAGC_ERR_INVALID_ARG
+    assert L.adagc_get_state_norms(None, None, None, None, 1, None) == B.ADAGC_ERR_INVALID_ARG
     assert L.adagc_set_param_copies(None, None) == B.ADAGC_ERR_INVALID_ARG
     assert L.adagc_get_segment_table(None, None, None, None) == B.ADAGC_ERR_INVALID_ARG
     assert L.adagc_profile_begin(None, 4) == B.ADAGC_ERR_INVALID_ARG

@@ -298,6 +298,58 @@ def test_global_adagc_mode_single_adaptive_threshold():
     run.compare_state("global-adagc")
 
 
+def _telemetry_case(optimizer, w, hp, name):
+    run = P.Run(w, optimizer=optimizer, telemetry=True)
+    plain = P.Run(w, optimizer=optimizer, mirror=False)
+    for step in range(1, 5):
+        grads = w.make_grads(step, DEV)
+        grads_np = [to_numpy(g) for g in grads]
+        run.h_params = [to_numpy(t) for t in run.params]          # lockstep
+        run.h_m = [to_numpy(t) for t in run.m]
+        if run.v is not None:
+            run.h_v = [to_numpy(t) for t in run.v]
+        run.h_gamma = to_numpy(run.gamma)
+        before = [x.copy() for x in run.h_params]
+        run.gpu_step(grads, hp, step)
+        plain.gpu_step(grads, hp, step)
+        run.oracle_step(grads_np, hp, step)
+        m_n, v_n, u_n = run.ctx.get_state_norms()
+        for i in range(w.n_tensors):
+            rm, rv, ru = oracle.state_norms(before[i], run.h_params[i], run.h_m[i],
+                                            run.h_v[i] if run.h_v is not None else None)
+            tag = "%s step %d tensor %d" % (name, step, i)
+            assert m_n[i] == pytest.approx(rm, rel=P.RTOL, abs=1e-30), tag + " |m|"
+            assert v_n[i] == pytest.approx(rv, rel=P.RTOL, abs=1e-30), tag + " |v|"
+            # the update is a difference of stored fp32 values: allow one fp32 rounding of theta per element
+            slack = 6e-8 * float(np.linalg.norm(run.h_params[i].astype(np.float64)))
+            assert abs(u_n[i] - ru) <= P.RTOL * ru + slack, tag + " |update|"
+        if optimizer == "lion":
+            assert (v_n == 0).all()
+    # telemetry does not change the step itself
+    for a, b in zip(run.params + run.m + [run.gamma], plain.params + plain.m + [plain.gamma]):
+        assert torch.equal(a, b)
+    code = None
+    try:
+        plain.ctx.get_state_norms()
+    except B.AdagcError as e:
+        code = e.code
+    assert code == B.ADAGC_ERR_STATE
+
+
+def test_telemetry_state_norms_adamw():
+    specs = W.llama_like_list(1, 256, 4, 2, 896, 4000) + W.ragged_stress_list(40, 1 << 15, None)
+    w = W.config3(specs)
+    w.spikes = {3: (np.arange(0, len(specs), 4), 50.0)}
+    _telemetry_case("adamw", w, B.make_hyper(), "telemetry-adamw")
+
+
+def test_telemetry_state_norms_lion_bf16_grads():
+    specs = W.llama_like_list(1, 256, 4, 2, 896, 4000)
+    w = W.config4(specs)
+    w.spikes = {3: (np.arange(0, len(specs), 4), 50.0)}
+    _telemetry_case("lion", w, B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99), "telemetry-lion")
+
+
 # --------------------------------------------------------------------------- determinism, state, errors
 
 def test_run_to_run_and_permutation_determinism():

@@ -485,3 +485,26 @@ def test_steps_on_a_side_stream_and_profile_events():
         assert np.array_equal(x, y)
     for x, y in zip(run.params, ref.params):
         assert torch.equal(x, y)
+
+
+def test_non_finite_gradient_propagates_like_plain_adamw():
+    """A NaN in one tensor's gradient makes that tensor's norm NaN: the comparison with the threshold
+    is false, the tensor is not clipped, and the NaN flows into its own state only."""
+    numels = [300, 5000, 70]
+    rng = np.random.default_rng(3)
+    grads = [rng.standard_normal(n).astype(np.float32) * 0.01 for n in numels]
+    grads[1][1234] = np.nan
+    grads[2][5] = np.inf
+    hp = B.make_hyper(t_start=0)
+    run, got, ref = _single(numels, grads, [1.0, 1.0, 1.0], hp, 2)
+    norms, coefs, flags = got
+    assert np.isnan(norms[1]) and coefs[1] == 1.0 and flags[1] == 0
+    assert np.isinf(norms[2]) and flags[2] == 1 and coefs[2] == 0.0            # thr / inf = 0
+    assert np.isnan(ref[0][1]) and ref[1][1] == 1.0 and ref[2][1] == 0 and ref[2][2] == 1
+    assert np.isnan(to_numpy(run.gamma)[1]) and np.isnan(run.h_gamma[1])
+    P.assert_close("finite tensor theta", to_numpy(run.params[0]), run.h_params[0])
+    P.assert_close("finite tensor m", to_numpy(run.m[0]), run.h_m[0])
+    gpu_m1, ref_m1 = to_numpy(run.m[1]), run.h_m[1]
+    assert np.array_equal(np.isnan(gpu_m1), np.isnan(ref_m1)) and int(np.isnan(gpu_m1).sum()) == 1
+    # inf * 0 = NaN in the clipped gradient of the inf element, on both sides
+    assert np.array_equal(np.isnan(to_numpy(run.m[2])), np.isnan(run.h_m[2]))

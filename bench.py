@@ -23,8 +23,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 
 
 def algorithmic_bytes(workload_name):
-    """Bytes per parameter that the method itself must move:
-    norm pass reads g once; update pass reads g, theta, m(, v) and writes theta, m(, v)(, bf16 copy)."""
+    """Bytes per parameter that the method itself must move: the norm pass reads g once (the norm of a
+    tensor must be complete before any of its elements is updated, Eq. 3); the update pass reads
+    g, theta, m(, v) and writes theta, m(, v)(, bf16 copy)."""
     table = {
         # name: (norm read, update read, update write)
         "config2": (4, 16, 12),     # fp32 everything, no copy
@@ -118,7 +119,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
+        sys.exit("bench.py: this library runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
 
     import torch
     from paper_2502_11034_amd import binding as B

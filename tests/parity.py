@@ -1,7 +1,7 @@
 """Helpers of the GPU parity tests: run the HIP path and the CPU oracle on the same seeded
 inputs and compare element by element.
 
-Tolerances (stated by the task this library was built for, forms derived from the arithmetic):
+Tolerances (relative 1e-5 throughout; the forms below are derived from the arithmetic):
   - segment table, tensor indexing: bit-exact.
   - clip / no-clip decision: bit-exact for every tensor whose norm is not within 1e-6 relative
     of its threshold (inside that band either outcome is accepted: h is continuous there).

@@ -508,3 +508,22 @@ def test_non_finite_gradient_propagates_like_plain_adamw():
     assert np.array_equal(np.isnan(gpu_m1), np.isnan(ref_m1)) and int(np.isnan(gpu_m1).sum()) == 1
     # inf * 0 = NaN in the clipped gradient of the inf element, on both sides
     assert np.array_equal(np.isnan(to_numpy(run.m[2])), np.isnan(run.h_m[2]))
+
+
+def test_remaining_dtype_combinations():
+    """AdamW with bf16 gradients (no copy) and Lion with fp32 gradients plus the bf16 copy."""
+    specs = W.llama_like_list(1, 256, 4, 2, 896, 4000)
+    w = W.Workload(specs, grad_dtype=torch.bfloat16, spikes={3: (np.arange(0, len(specs), 3), 40.0)})
+    trajectory(P.Run(w), B.make_hyper(), 4, "adamw-bf16-grads", lockstep=True)
+    w = W.Workload(specs, bf16_copy=True, spikes={3: (np.arange(0, len(specs), 3), 40.0)})
+    trajectory(P.Run(w, optimizer="lion"), B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99), 4, "lion-fp32-grads-copy",
+               lockstep=True)
+
+
+def test_list_of_one_tensor_of_one_element():
+    hp = B.make_hyper(t_start=0)
+    run, got, ref = _single([1], [np.array([0.5])], [0.25], hp, 9)
+    norms, coefs, flags = got
+    assert norms[0] == 0.5 and flags[0] == 1 and coefs[0] == np.float32(np.float32(1.04) * 0.25 / 0.5)
+    P.check_scalars("one-element", norms, coefs, flags, to_numpy(run.gamma), ref[0], ref[1], ref[2], run.h_gamma, ref[3])
+    run.compare_state("one-element")

@@ -132,3 +132,44 @@ def test_config5_full_size_ragged_stress():
                         [20000]))                                                  # the 128256x4096 tensor
     early = [i for i in subset if w.numels[i] <= (1 << 20)]
     run_fullsize(w, "adamw", B.make_hyper(), 2, subset, 2, "config5-full", early)
+
+
+def test_one_tensor_beyond_2_to_31_elements():
+    """Maximum sizes: a single tensor of 2^31 + 12345 elements (8.6 GB per fp32 array), so that element
+    offsets pass 2^31 and byte offsets pass 2^33.  The oracle computes the full norm; the update is
+    replayed on slices at the start, across the 2^31-element mark and at the ragged end."""
+    n = (1 << 31) + 12345
+    dev = DEV
+    gen = torch.Generator(device=dev).manual_seed(77)
+    g = torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 3e-3, generator=gen)
+    p = torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 0.02, generator=gen)
+    m = torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 1e-3, generator=gen)
+    v = torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 1e-3, generator=gen).square_()
+    copy = torch.empty(n, dtype=torch.bfloat16, device=dev)
+    gamma = torch.tensor([1.0], dtype=torch.float32, device=dev)
+    slices = [(0, 1 << 20), ((1 << 31) - (1 << 19), (1 << 31) + 4096), (n - 70001, n)]
+    pre = [(to_numpy(p[a:b]), to_numpy(m[a:b]), to_numpy(v[a:b]), to_numpy(g[a:b])) for a, b in slices]
+    hp = B.make_hyper(t_start=0)
+    ctx = B.AdaGC([n], has_bf16_param_copy=True)
+    assert ctx.num_chunks() == -(-n // B.adagc_chunk_elems())
+    ctx.set_param_copies([copy])
+    ctx.step([p], [g], [m], [v], gamma, hp, 3)
+    norms, coefs, flags = ctx.get_norms()
+    ref_norm = oracle.l2_norm(to_numpy(g))
+    h, gamma_new, clipped = oracle.adagc_rule(ref_norm, 1.0, f32(hp.lambda_rel), f32(hp.ema_beta))
+    say("2^31+ tensor: norm %.6f (ref %.6f), h %.6f, clipped %d" % (norms[0], ref_norm, coefs[0], clipped))
+    assert clipped and flags[0] == 1
+    np.testing.assert_allclose(norms[0], ref_norm, rtol=P.RTOL)
+    np.testing.assert_allclose(coefs[0], h, rtol=P.RTOL)
+    np.testing.assert_allclose(to_numpy(gamma)[0], np.float32(gamma_new), rtol=P.RTOL)
+    ohp = P.oracle_hyper(hp, 0, 0)
+    for (a, b), (th, mm, vv, gg) in zip(slices, pre):
+        ref_copy = np.zeros(b - a, np.uint16)
+        oracle.adamw_update(th, mm, vv, gg, h, ohp, 3, ref_copy)
+        tag = "2^31+ tensor slice [%d, %d)" % (a, b)
+        gpu_theta = to_numpy(p[a:b])
+        P.assert_close(tag + " theta", gpu_theta, th, floor=hp.lr)
+        P.assert_close(tag + " m", to_numpy(m[a:b]), mm, floor=h * P.rms(gg))
+        P.assert_close(tag + " v", to_numpy(v[a:b]), vv)
+        P.assert_bf16_copy(tag, to_numpy(copy[a:b]), gpu_theta, th)
+    ctx.close()

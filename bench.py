@@ -194,7 +194,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f64",
         "data": "synthetic",
         "config": {"workload": "%s: %d tensors, %d params, %s grads, %s%s" % (
             args.workload, w.n_tensors, n, "bf16" if grad_dtype else "fp32",

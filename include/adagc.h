@@ -79,7 +79,7 @@ typedef struct {
     /* Launch tuning of the streaming kernels; 0 = library default for each. */
     int32_t grid_blocks;          /* > 0: persistent grid of that many workgroups, each walking chunks
                                      b, b+grid, ...; default: one chunk per workgroup */
-    int32_t unroll;               /* 128-bit vectors per lane per stream kept in flight: 1, 2 or 4 (default 2) */
+    int32_t unroll;               /* 128-bit vectors per lane per stream kept in flight: 1, 2 or 4 (default 4) */
     int32_t nontemporal;          /* streaming (non-temporal) loads and stores: 1 = on (default), 2 = off */
     int32_t schedule;             /* order in which workgroups visit chunks: 1 = list order; w >= 2 = the list is
                                      cut into w contiguous parts and workgroup b walks part b mod w

@@ -52,17 +52,17 @@ struct RuleArgs {
     int    mode;         // ADAGC_MODE_*
 };
 
-// Scalars of the elementwise update, precomputed on the host in double.
+// Scalars of the elementwise update, precomputed on the host in double from the caller's fp32
+// hyper-parameters.
 struct UpdateArgs {
-    float  beta1, one_minus_beta1;
-    float  beta2, one_minus_beta2;
-    float  inv_bias2;      // 1 / (1 - beta2^t)
-    float  step_size;      // lr / (1 - beta1^t)
-    float  decay;          // 1 - lr * weight_decay
-    float  eps;
-    float  lr;             // Lion
-    float  weight_decay;   // Lion
-    double beta1_d, one_minus_beta1_d;   // Lion: sign decision in double
+    double beta1, one_minus_beta1;
+    double beta2, one_minus_beta2;
+    double inv_bias2;      // 1 / (1 - beta2^t)
+    double step_size;      // lr / (1 - beta1^t)
+    double lr_wd;          // lr * weight_decay
+    double eps;
+    double lr;             // Lion
+    double weight_decay;   // Lion
 };
 
 struct DeviceTables {
@@ -73,8 +73,8 @@ struct DeviceTables {
     double*           sumsq;      // one per tensor
     double*           global;     // [0] = model's sum of squares, [1] = its coefficient, [2] = 1 if clipped
     float*            norm;       // per tensor, pre-clip
-    float*            coef;       // per tensor, fp32
-    double*           coef64;     // per tensor, as computed
+    float*            coef;       // per tensor, fp32 (reported to the caller)
+    double*           coef64;     // per tensor, as computed (what the update kernel multiplies by)
     uint8_t*          flag;       // per tensor, 1 = clip active
     double*           tele_partials;  // telemetry: [3][n_chunks] sums of m^2, v^2, (dtheta)^2 (or null)
     float*            tele_norm;      // telemetry: [3][n_tensors] norms

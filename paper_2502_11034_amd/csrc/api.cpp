@@ -151,7 +151,7 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     //  - visiting order cut into 8 parts, so that the workgroups that land on one XCD
     //    (workgroup b goes to XCD b mod 8) stream one contiguous eighth of the list: +0.5-1.3 %,
     //    +5 % on the norm kernel.
-    c->unroll = cfg->unroll ? cfg->unroll : 2;
+    c->unroll = cfg->unroll ? cfg->unroll : 4;
     c->nontemporal = cfg->nontemporal == 2 ? 0 : 1;
     const int64_t want = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : c->n_chunks;
     c->grid_norm = (int)(want < c->n_chunks ? want : c->n_chunks);
@@ -324,18 +324,16 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
     r.first_step = (step == 1) ? 1 : 0;
     r.mode = hp->clip_mode;
     UpdateArgs u;
-    u.beta1 = hp->beta1;
-    u.one_minus_beta1 = (float)(1.0 - b1);
-    u.beta2 = hp->beta2;
-    u.one_minus_beta2 = (float)(1.0 - b2);
-    u.inv_bias2 = (float)(1.0 / (1.0 - std::pow(b2, t)));
-    u.step_size = (float)(lr / (1.0 - std::pow(b1, t)));
-    u.decay = (float)(1.0 - lr * wd);
-    u.eps = hp->eps;
-    u.lr = hp->lr;
-    u.weight_decay = hp->weight_decay;
-    u.beta1_d = b1;
-    u.one_minus_beta1_d = 1.0 - b1;
+    u.beta1 = b1;
+    u.one_minus_beta1 = 1.0 - b1;
+    u.beta2 = b2;
+    u.one_minus_beta2 = 1.0 - b2;
+    u.inv_bias2 = 1.0 / (1.0 - std::pow(b2, t));
+    u.step_size = lr / (1.0 - std::pow(b1, t));
+    u.lr_wd = lr * wd;
+    u.eps = (double)hp->eps;
+    u.lr = lr;
+    u.weight_decay = wd;
 
     const bool warmup = (step - 1) < (int64_t)hp->t_start;   // steps 1..t_start
     r.warmup = warmup ? 1 : 0;

@@ -69,7 +69,7 @@ def main():
         show("schedule=%d%s" % (parts, " (default)" if parts == 8 else ""), schedule=parts)
     print("-- 128-bit vectors per lane per array in flight")
     for unroll in (1, 2, 4):
-        show("unroll=%d%s" % (unroll, " (default)" if unroll == 2 else ""), unroll=unroll)
+        show("unroll=%d%s" % (unroll, " (default)" if unroll == 4 else ""), unroll=unroll)
     print("-- combinations")
     for grid, nt, parts in itertools.product((0, 1024), (1, 2), (1, 8)):
         show("grid_blocks=%d nontemporal=%d schedule=%d" % (grid, nt, parts), grid_blocks=grid, nontemporal=nt,

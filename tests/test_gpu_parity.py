@@ -47,9 +47,9 @@ def trajectory(run, hp, steps, name, lockstep=False):
             exempt = [run.lion_exempt(i, grads_np[i], m_before[i], ref_coefs[i], hp)
                       for i in range(run.w.n_tensors)]
         if lockstep or step == steps or step in run.w.spikes:
-            strict = run.compare_state("%s step %d" % (name, step), exempt, grads_np, ref_coefs, hp.lr)
-            say("%s step %d: state ok (%d strict-relative misses), %d clipped"
-                % (name, step, strict, int(ref_flags.sum())))
+            differ = run.compare_state("%s step %d" % (name, step), exempt)
+            say("%s step %d: state within relative 1e-5 everywhere (%d values not bit-identical), %d clipped"
+                % (name, step, differ, int(ref_flags.sum())))
         clipped_total += int(ref_flags.sum())
     return clipped_total
 

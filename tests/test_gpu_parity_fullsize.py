@@ -83,15 +83,15 @@ def run_fullsize(w, optimizer, hp, steps, subset, scalar_step, name, early_subse
                 assert flags[i] == rf1[0], tag
             ex = run.lion_exempt(i, g_np, m_before, rc1[0], hp) if lion else None
             gpu_theta = to_numpy(run.params[i])
-            floor_m = float(rc1[0]) * P.rms(P.widen_grad(g_np))
-            strict += P.assert_close(tag + " theta", gpu_theta, th, exempt=ex, floor=hp.lr)
-            strict += P.assert_close(tag + " m", to_numpy(run.m[i]), mm, floor=floor_m)
+            strict += P.assert_close(tag + " theta", gpu_theta, th, exempt=ex)
+            strict += P.assert_close(tag + " m", to_numpy(run.m[i]), mm)
             if vv is not None:
                 strict += P.assert_close(tag + " v", to_numpy(run.v[i]), vv)
             if copy is not None:
                 P.assert_bf16_copy(tag, to_numpy(run.copies[i]), gpu_theta, th, ex)
             del th, mm, vv, g_np, copy
-        say("%s step %d: update ok on %d tensors (%d strict-relative misses)" % (name, step, len(subset), strict))
+        say("%s step %d: update within relative 1e-5 on every element of %d tensors (%d values not bit-identical)"
+            % (name, step, len(subset), strict))
         del grads, pre
     run.ctx.close()
     del run
@@ -168,8 +168,8 @@ def test_one_tensor_beyond_2_to_31_elements():
         oracle.adamw_update(th, mm, vv, gg, h, ohp, 3, ref_copy)
         tag = "2^31+ tensor slice [%d, %d)" % (a, b)
         gpu_theta = to_numpy(p[a:b])
-        P.assert_close(tag + " theta", gpu_theta, th, floor=hp.lr)
-        P.assert_close(tag + " m", to_numpy(m[a:b]), mm, floor=h * P.rms(gg))
+        P.assert_close(tag + " theta", gpu_theta, th)
+        P.assert_close(tag + " m", to_numpy(m[a:b]), mm)
         P.assert_close(tag + " v", to_numpy(v[a:b]), vv)
         P.assert_bf16_copy(tag, to_numpy(copy[a:b]), gpu_theta, th)
     ctx.close()

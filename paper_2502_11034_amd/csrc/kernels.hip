@@ -337,7 +337,7 @@ __global__ __launch_bounds__(kBlock) void finalize_global_kernel(DeviceTables t,
 }
 
 // ---------------------------------------------------------------------------------------------
-// K3: clipped gradient into the optimizer, elementwise in fp32.
+// K3: clipped gradient into the optimizer, element by element.
 
 struct ElemState {
     float p, m, v;

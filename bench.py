@@ -1,6 +1,6 @@
 """Benchmark of the fused AdaGC + AdamW step on Llama-3-8B-shaped synthetic tensors, one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config3|config4|config2|config5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1|config2|config3|config4|config5]
 
 A "step" is one pass of the whole hot path (segmented norms, per-tensor clip rule + EMA, fused
 clip + optimizer update) over the full parameter list, inputs resident in HBM.  Prints ONE JSON
@@ -28,6 +28,7 @@ def algorithmic_bytes(workload_name):
     g, theta, m(, v) and writes theta, m(, v)(, bf16 copy)."""
     table = {
         # name: (norm read, update read, update write)
+        "config1": (4, 16, 12),     # fp32 everything, no copy (launch-bound: 17 MB per step)
         "config2": (4, 16, 12),     # fp32 everything, no copy
         "config3": (4, 16, 14),     # + bf16 copy
         "config4": (2, 10, 10),     # Lion: bf16 g; theta, m fp32; + bf16 copy
@@ -68,6 +69,9 @@ def cpu_baseline(workload_name, target_seconds=15.0):
     if workload_name in ("config3", "config4"):
         specs = [s for s in W.llama3_8b_list() if s.name.startswith("l0.")]
         sample = "layer 0 of the Llama-3-8B-shaped list (9 tensors, %d params)"
+    elif workload_name == "config1":
+        specs = W.tiny_transformer_list()
+        sample = "the whole tiny-transformer list (27 tensors, %d params)"
     elif workload_name == "config2":
         specs = W.gpt2_small_list()
         sample = "the whole GPT-2-small-shaped list (148 tensors, %d params)"
@@ -108,7 +112,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config2", "config3", "config4", "config5"])
+    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4", "config5"])
     ap.add_argument("--grid-blocks", type=int, default=0, help="launch tuning: workgroups of the persistent grids")
     ap.add_argument("--unroll", type=int, default=0, help="launch tuning: vectors in flight per lane per stream")
     ap.add_argument("--nontemporal", type=int, default=0, help="launch tuning: 1 on, 2 off")
@@ -130,7 +134,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
-    w = {"config2": W.config2, "config3": W.config3, "config4": W.config4, "config5": W.config5}[args.workload]()
+    w = {"config1": W.config1, "config2": W.config2, "config3": W.config3, "config4": W.config4, "config5": W.config5}[args.workload]()
     lion = args.workload == "config4"
     optimizer = B.ADAGC_OPT_LION if lion else B.ADAGC_OPT_ADAMW
     grad_dtype = B.ADAGC_GRAD_BF16 if w.grad_dtype == torch.bfloat16 else B.ADAGC_GRAD_F32
@@ -183,7 +187,7 @@ def main():
     out = {
         "metric": "fused AdaGC+%s step: effective GB/s (two-pass algorithmic bytes), %s" % (
             "Lion" if lion else "AdamW",
-            {"config2": "GPT-2-small shapes", "config3": "Llama-3-8B shapes", "config4": "Llama-3-8B shapes",
+            {"config1": "tiny 2-layer transformer shapes", "config2": "GPT-2-small shapes", "config3": "Llama-3-8B shapes", "config4": "Llama-3-8B shapes",
              "config5": "ragged stress list"}[args.workload]),
         "value": round(value, 1),
         "unit": "GB/s",

@@ -170,8 +170,9 @@ class AdaGC:
 
     # -- adagc_destroy
     def close(self):
-        if getattr(self, "_ctx", None) is not None and self._ctx.value:
-            lib().adagc_destroy(self._ctx)
+        ctx = getattr(self, "_ctx", None)
+        if ctx is not None and ctx.value and _lib is not None:     # _lib is gone at interpreter shutdown
+            _lib.adagc_destroy(ctx)
             self._ctx = ctypes.c_void_p(None)
 
     __del__ = close

@@ -28,6 +28,11 @@
  *     throws or aborts.  Arguments are validated before any work is enqueued,
  *     so a failed call leaves all state untouched.
  *   - A context is not thread-safe; use one per host thread or lock around it.
+ *   - All steps of one context share its pointer table, reduction scratch and
+ *     result arrays on the GPU, so they must execute one after another: issue
+ *     them on one stream, or order the streams yourself (an event between a
+ *     step on stream A and the next step or adagc_get_* call on stream B).
+ *     Steps of different contexts may overlap freely.
  */
 #ifndef ADAGC_H
 #define ADAGC_H
@@ -42,7 +47,7 @@ extern "C" {
 #define ADAGC_ERR_INVALID_ARG     (-1)  /* NULL pointer, non-positive size, bad enum, bad hyper-parameter */
 #define ADAGC_ERR_OOM             (-2)  /* host or device allocation failed */
 #define ADAGC_ERR_HIP             (-3)  /* a HIP runtime call failed (no device, launch error, ...) */
-#define ADAGC_ERR_TOO_LARGE       (-4)  /* the list needs more than 2^32-1 chunks */
+#define ADAGC_ERR_TOO_LARGE       (-4)  /* the list needs more than 2^32-1 chunks, or has more than 2^24-1 tensors */
 #define ADAGC_ERR_STATE           (-5)  /* call made in the wrong state (e.g. bf16 copies not set) */
 
 #define ADAGC_OPT_ADAMW 0

@@ -58,6 +58,9 @@ struct DeviceGuard {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Largest grid this library launches: the runtime wants workgroups x lanes below 2^32.
+constexpr int64_t kMaxGridBlocks = (int64_t)(0xFFFFFFFFu / (uint32_t)kBlock);
+
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 bool hyper_ok(const adagc_hyper& h, int optimizer)
@@ -94,7 +97,7 @@ extern "C" const char* adagc_strerror(int code)
     case ADAGC_ERR_INVALID_ARG: return "invalid argument";
     case ADAGC_ERR_OOM: return "out of memory";
     case ADAGC_ERR_HIP: return "HIP runtime error";
-    case ADAGC_ERR_TOO_LARGE: return "tensor list needs too many chunks";
+    case ADAGC_ERR_TOO_LARGE: return "tensor list too large (too many chunks or tensors)";
     case ADAGC_ERR_STATE: return "call made in the wrong state";
     default: return "unknown error code";
     }
@@ -111,6 +114,7 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
         cfg->telemetry < 0 || cfg->telemetry > 1)
         return ADAGC_ERR_INVALID_ARG;
     if (cfg->unroll != 0 && cfg->unroll != 1 && cfg->unroll != 2 && cfg->unroll != 4) return ADAGC_ERR_INVALID_ARG;
+    if (n_tensors > kMaxGridBlocks) return ADAGC_ERR_TOO_LARGE;   // the per-tensor kernels run one workgroup per tensor
 
     adagc_ctx* c = new (std::nothrow) adagc_ctx;
     if (!c) return ADAGC_ERR_OOM;
@@ -153,7 +157,8 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     //    +5 % on the norm kernel.
     c->unroll = cfg->unroll ? cfg->unroll : 4;
     c->nontemporal = cfg->nontemporal == 2 ? 0 : 1;
-    const int64_t want = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : c->n_chunks;
+    int64_t want = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : c->n_chunks;
+    if (want > kMaxGridBlocks) want = kMaxGridBlocks;            // the kernels walk chunks b, b+grid, ...
     c->grid_norm = (int)(want < c->n_chunks ? want : c->n_chunks);
     c->grid_update = c->grid_norm;
 

@@ -72,6 +72,20 @@ def test_create_validates_before_touching_the_device():
         assert rc == B.ADAGC_ERR_HIP
 
 
+def test_create_rejects_a_list_with_too_many_tensors():
+    """One workgroup per tensor in the per-tensor kernels bounds the tensor count at 2^24 - 1; the check
+    comes before anything touches the device."""
+    import numpy as np
+    L = B.lib()
+    n = 1 << 24
+    descs = np.zeros(n, dtype=[("numel", "<i8"), ("flags", "<u4"), ("reserved", "<u4")])
+    descs["numel"] = 1
+    cfg = B.adagc_config()
+    ctx = ctypes.c_void_p()
+    rc = L.adagc_create(ctypes.byref(ctx), ctypes.c_void_p(descs.ctypes.data), n, ctypes.byref(cfg))
+    assert rc == B.ADAGC_ERR_TOO_LARGE and ctx.value is None
+
+
 def test_null_context_is_rejected_everywhere():
     L = B.lib()
     hp = B.make_hyper()

@@ -530,3 +530,83 @@ def test_list_of_one_tensor_of_one_element():
     assert norms[0] == 0.5 and flags[0] == 1 and coefs[0] == np.float32(np.float32(1.04) * 0.25 / 0.5)
     P.check_scalars("one-element", norms, coefs, flags, to_numpy(run.gamma), ref[0], ref[1], ref[2], run.h_gamma, ref[3])
     run.compare_state("one-element")
+
+
+# --------------------------------------------------------------------------- the published schedule, and a seeded sweep
+
+@pytest.mark.parametrize("quiet_warmup", [False, True])
+def test_paper_default_schedule_warmup_100_then_adagc(quiet_warmup):
+    """Alg. 1 with the defaults of Sec. 4.2 / 5.1 (lambda_rel 1.04, beta 0.99, T_start 100, lambda_abs 1.0) run
+    free for 150 steps on the tiny transformer list: 100 GlobalGC warm-up steps with the running minimum, then
+    per-tensor AdaGC with spikes.  The oracle is never re-seeded from the device.
+    quiet_warmup=False: the model's norm is far above lambda_abs and one warm-up step spikes, so every step of the
+    warm-up clips globally and the thresholds start low (every tensor clips afterwards).
+    quiet_warmup=True: gradients are scaled so that the model's norm stays below lambda_abs; the thresholds start
+    at each tensor's smallest norm and only some tensors clip afterwards."""
+    specs = W.tiny_transformer_list()
+    spike_steps = {101, 120, 135} if quiet_warmup else {50, 101, 120, 135}
+    w = W.Workload(specs, spikes=W.forced_spike_schedule(len(specs), 150, spike_steps, 3, 100.0))
+    if quiet_warmup:
+        w.sigma = w.sigma * (0.9 / math.sqrt(sum(float(s) ** 2 * k for s, k in zip(w.sigma, w.numels))))
+    hp = B.make_hyper(t_start=100, lambda_abs=1.0)
+    run = P.Run(w)
+    name = "paper-defaults%s" % (" (quiet warm-up)" if quiet_warmup else "")
+    warm_clips, after = 0, []
+    for step in range(1, 151):
+        grads = w.make_grads(step, DEV)
+        norms, coefs, flags = run.gpu_step(grads, hp, step)
+        ref_norms, ref_coefs, ref_flags, thr = run.oracle_step([to_numpy(g) for g in grads], hp, step)
+        P.check_scalars("%s step %d" % (name, step), norms, coefs, flags, to_numpy(run.gamma), ref_norms,
+                        ref_coefs, ref_flags, run.h_gamma, None if step <= 100 else thr)
+        if step <= 100:
+            assert np.all(coefs == coefs[0]) and np.all(flags == flags[0])   # one decision for the whole model
+            warm_clips += int(flags[0])
+        else:
+            after.append(int(flags.sum()))
+        if step in (50, 100, 101, 120, 150):
+            differ = run.compare_state("%s step %d" % (name, step))
+            say("%s step %d: %d values not bit-identical, %d clipped" % (name, step, differ, int(flags.sum())))
+    if quiet_warmup:
+        assert warm_clips == 0 and 0 < min(after) < len(specs) and max(after) > min(after)
+    else:
+        assert warm_clips == 100 and min(after) == len(specs)
+
+
+def test_seeded_sweep_of_lists_modes_and_dtypes():
+    """32 seeded random cases: list length, sizes next to every vector / chunk boundary, optimizer, gradient
+    type, bf16 copy, clipping mode, warm-up length, thresholds and launch knobs, three lockstep steps each."""
+    c = B.adagc_chunk_elems()
+    pool = [1, 2, 3, 4, 5, 7, 8, 9, 63, 64, 65, 255, 256, 257, 1020, 1023, 1024, 1025, 1027, 4095, 4097,
+            c - 4, c - 1, c, c + 1, c + 4, 2 * c - 1, 2 * c + 2, 3 * c + 3, 50001]
+    rng = np.random.default_rng(20250211)
+    for case in range(32):
+        n = int(rng.integers(1, 13))
+        numels = [int(pool[k]) for k in rng.integers(0, len(pool), n)]
+        lion = bool(rng.integers(0, 2))
+        bf16g = bool(rng.integers(0, 2))
+        copy = bool(rng.integers(0, 2))
+        mode = int(rng.integers(0, 3))
+        t_start = int(rng.integers(0, 4))
+        knobs = dict(unroll=int(rng.choice([0, 1, 2, 4])), schedule=int(rng.choice([0, 1, 3, 8])),
+                     grid_blocks=int(rng.choice([0, 0, 5, 64])), nontemporal=int(rng.choice([0, 1, 2])))
+        specs = [W.TensorSpec("t%d" % i, (k,), "matrix") for i, k in enumerate(numels)]
+        spikes = {2: (np.arange(0, n, 2), 30.0), 3: (np.arange(1, n, 2), 30.0)}
+        w = W.Workload(specs, seed=1000 + case, spikes=spikes, bf16_copy=copy,
+                       grad_dtype=torch.bfloat16 if bf16g else torch.float32)
+        # a GlobalGC threshold near the unspiked model norm, so that some steps clip and some do not
+        model_norm = math.sqrt(sum(float(s) ** 2 * k for s, k in zip(w.sigma, numels)))
+        hp = B.make_hyper(lr=1e-4 if lion else 3e-4, beta2=0.99 if lion else 0.95, t_start=t_start,
+                          clip_mode=mode, lambda_abs=float(rng.choice([0.5, 2.0, math.inf])) * model_norm,
+                          lambda_rel=float(rng.choice([1.04, 1.0, 2.0])))
+        name = "sweep case %d (%s, %s grads%s, mode %d, t_start %d, %d tensors, %s)" % (
+            case, "lion" if lion else "adamw", "bf16" if bf16g else "fp32", ", copy" if copy else "", mode, t_start,
+            n, knobs)
+        say(name)
+        run = P.Run(w, optimizer="lion" if lion else "adamw", **knobs)
+        if t_start == 0:       # no initialising step: the caller provides gamma
+            g0 = np.array([0.7 * float(s) * math.sqrt(k) for s, k in zip(w.sigma, numels)], dtype=np.float32)
+            if mode == B.ADAGC_MODE_GLOBAL_ADAGC:
+                g0[0] = np.float32(0.7 * model_norm)
+            run.gamma.copy_(torch.from_numpy(g0))
+        trajectory(run, hp, 3, name, lockstep=True)
+        run.ctx.close()

@@ -8,6 +8,7 @@ All arrays are numpy arrays owned by the caller; float32 state arrays are
 updated in place.  bf16 data travels as ``uint16`` bit patterns.
 """
 import ctypes
+import os
 from dataclasses import dataclass
 
 import numpy as np
@@ -77,7 +78,8 @@ class Hyper:
 def lib():
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(_build.build())
+        # ADAGC_ORACLE_LIB: a test may point at a deliberately broken build to show that the pins notice
+        L = ctypes.CDLL(os.environ.get("ADAGC_ORACLE_LIB") or _build.build())
         vp, i64, dbl, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double, ctypes.c_int
         L.oracle_bf16_to_float.restype = ctypes.c_float
         L.oracle_bf16_to_float.argtypes = [ctypes.c_uint16]

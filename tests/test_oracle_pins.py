@@ -308,6 +308,45 @@ def test_adamw_dyadic_hand_worked_two_steps():
     assert copy[0] == 0x4008                                   # bf16(2.125) = 2 + 2^-3
 
 
+def test_updates_read_bf16_gradients_as_their_values():
+    """The two hand-worked dyadic cases again, with the gradient given as bf16 bits
+    (4.0 = 0x4080, -8.0 = 0xC100): the results are the same numbers."""
+    hp = Hyper(lr=0.5, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.25, grad_dtype=oracle.GRAD_BF16)
+    theta, m, v = (np.array([4.0], np.float32), np.zeros(1, np.float32), np.zeros(1, np.float32))
+    oracle.adamw_update(theta, m, v, np.array([0x4080], np.uint16), 0.5, hp, 1)
+    assert (theta[0], m[0], v[0]) == (3.0, 1.0, 1.0)
+    hp = Hyper(lr=0.25, beta1=0.5, beta2=0.75, weight_decay=0.5, optimizer=oracle.LION, grad_dtype=oracle.GRAD_BF16)
+    theta, m = np.array([1.0], np.float32), np.array([2.0], np.float32)
+    oracle.lion_update(theta, m, np.array([0xC100], np.uint16), 0.5, hp)
+    assert (theta[0], m[0]) == (1.125, 0.5)
+
+
+@pytest.mark.parametrize("optimizer", [oracle.ADAMW, oracle.LION])
+def test_step_on_bf16_gradients_equals_step_on_the_widened_values(optimizer):
+    """Every bf16 value is an fp32 value (same sign, exponent, top 7 mantissa bits), so a step fed bf16 bits
+    must leave exactly the state of a step fed those values as fp32; the widening here is a plain shift."""
+    rng = np.random.default_rng(21)
+    numels = [1, 5, 300, 77]
+    bits = [(rng.standard_normal(n) * 0.05).astype(np.float32).view(np.uint32) >> 16 for n in numels]
+    bits = [b.astype(np.uint16) for b in bits]
+    wide = [(b.astype(np.uint32) << 16).view(np.float32) for b in bits]
+    states = []
+    for grads, gd in ((bits, oracle.GRAD_BF16), (wide, oracle.GRAD_F32)):
+        hp = Hyper(optimizer=optimizer, grad_dtype=gd, lambda_abs=0.5, t_start=2)
+        theta = [np.full(n, 0.25, np.float32) for n in numels]
+        m = [np.zeros(n, np.float32) for n in numels]
+        v = [np.zeros(n, np.float32) for n in numels] if optimizer == oracle.ADAMW else None
+        gamma = np.zeros(len(numels), np.float32)
+        outs = [oracle.adagc_step(theta, grads, m, v, gamma, hp, t) for t in (1, 2, 3)]
+        states.append((theta, m, v, gamma, outs))
+    a, b = states
+    for x, y in zip(a[0] + a[1] + (a[2] or []) + [a[3]], b[0] + b[1] + (b[2] or []) + [b[3]]):
+        assert np.array_equal(x, y)
+    for (n1, c1, f1), (n2, c2, f2) in zip(a[4], b[4]):
+        assert np.array_equal(n1, n2) and np.array_equal(c1, c2) and np.array_equal(f1, f2)
+    assert not np.array_equal(a[0][2], np.full(300, 0.25, np.float32))
+
+
 def test_adamw_step1_closed_form():
     """m0=v0=0, t=1: m=(1-b1)g, v=(1-b2)g^2, theta1 = theta0(1-lr*wd) - lr*g/(|g|+eps)."""
     rng = np.random.default_rng(8)

@@ -610,3 +610,49 @@ def test_seeded_sweep_of_lists_modes_and_dtypes():
             run.gamma.copy_(torch.from_numpy(g0))
         trajectory(run, hp, 3, name, lockstep=True)
         run.ctx.close()
+
+
+# --------------------------------------------------------------------------- the comparisons have teeth
+
+class _ZeroHead(W.Workload):
+    """Gradients whose first three elements are exactly zero (Lion's sign(0) case while m is still zero)."""
+
+    def fill_grad(self, out, i, step):
+        super().fill_grad(out, i, step)
+        out[:3] = 0
+        return out
+
+
+def _teeth_scenarios():
+    """Two short lockstep runs that between them exercise every statement of Alg. 1 and of the Lion rule:
+    warm-up with an active global clip and the running minimum, AdaGC with clipped and unclipped tensors,
+    AdamW with a bf16 copy, Lion on bf16 gradients with exact zeros."""
+    specs = W.llama_like_list(1, 64, 4, 2, 224, 500)
+    spikes = {4: (np.arange(0, len(specs), 2), 40.0), 5: (np.arange(1, len(specs), 2), 40.0)}
+    w = W.Workload(specs, spikes=spikes, bf16_copy=True)
+    model_norm = math.sqrt(sum(float(s) ** 2 * k for s, k in zip(w.sigma, w.numels)))
+    trajectory(P.Run(w), B.make_hyper(t_start=2, lambda_abs=0.5 * model_norm, eps=1e-3), 6, "teeth-adamw", lockstep=True)
+    w = _ZeroHead(specs, spikes=spikes, grad_dtype=torch.bfloat16)
+    trajectory(P.Run(w, optimizer="lion"), B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99), 5, "teeth-lion", lockstep=True)
+
+
+def test_parity_comparisons_notice_a_wrong_oracle(tmp_path):
+    """Plant each mistake of tests/planted.py in a copy of the CPU oracle (the GPU library is untouched) and run
+    the scenarios: the comparison must fail for every mistake that changes what a step computes.  Two entries
+    are left to the CPU pins: ties of the bf16 rounding (the copy is compared to within one bf16 ulp) and
+    '>=' for '>' (differs only at exact equality of norm and threshold)."""
+    import planted
+    _teeth_scenarios()                                  # the real oracle agrees
+    cpu_only = {"bf16 ties always round up", "clip on >= instead of >"}
+    unnoticed = []
+    for k, (what, _, _) in enumerate(planted.MISTAKES):
+        if what in cpu_only:
+            continue
+        with planted.wrong_oracle(tmp_path, k):
+            try:
+                _teeth_scenarios()
+                unnoticed.append(what)
+            except AssertionError:
+                pass
+        say("planted: %s -> %s" % (what, "NOT NOTICED" if unnoticed and unnoticed[-1] == what else "noticed"))
+    assert not unnoticed, "mistakes the GPU parity comparison does not notice: %s" % unnoticed

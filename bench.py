@@ -161,6 +161,10 @@ def main():
     for _ in range(args.warmup):
         step += 1
         ctx.step(ptrs[0], ptrs[1], ptrs[2], ptrs[3], gamma, hp, step, stream=stream)
+    # The same gradient batch is presented on every step, so after the warm-up steps gamma_i sits at
+    # the norm and nothing would clip.  Halve every fifth tensor's gamma: those tensors are clipped
+    # (h ~ 0.52) throughout the timed steps, the others are not; the kernels do the same work either way.
+    gamma[::5] *= 0.5
     torch.cuda.synchronize()
 
     ctx.profile_begin(args.steps)

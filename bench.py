@@ -117,6 +117,8 @@ def main():
     ap.add_argument("--unroll", type=int, default=0, help="launch tuning: vectors in flight per lane per stream")
     ap.add_argument("--nontemporal", type=int, default=0, help="launch tuning: 1 on, 2 off")
     ap.add_argument("--schedule", type=int, default=0, help="launch tuning: parts of the visiting order")
+    ap.add_argument("--schedule-run", type=int, default=0, help="launch tuning: chunks an XCD takes in a row")
+    ap.add_argument("--update-split", type=int, default=0, help="launch tuning: work items of the update kernel per chunk")
     ap.add_argument("--telemetry", action="store_true", help="also reduce per-tensor |m|, |v|, |update| norms")
     ap.add_argument("--clip-mode", type=int, default=0, help="0 AdaGC (default), 1 GlobalGC, 2 Global AdaGC")
     ap.add_argument("--t-start", type=int, default=1, help="warm-up steps (1 = only the initialising step)")
@@ -151,7 +153,8 @@ def main():
     gamma = torch.zeros(w.n_tensors, dtype=torch.float32, device=dev)
     ctx = B.AdaGC(w.numels, optimizer, grad_dtype, w.bf16_copy, grid_blocks=args.grid_blocks,
                   unroll=args.unroll, nontemporal=args.nontemporal, schedule=args.schedule,
-                  telemetry=args.telemetry)
+                  telemetry=args.telemetry, update_split=args.update_split,
+                  schedule_run=args.schedule_run)
     if copies is not None:
         ctx.set_param_copies(copies)
     ptrs = tuple(B.ptr_array(x) if x is not None else None for x in (params, grads, m, v))

@@ -82,13 +82,19 @@ typedef struct {
                                      (the quantities the paper plots per tensor, Fig. 2); read them with
                                      adagc_get_state_norms.  Costs no extra HBM traffic. */
     /* Launch tuning of the streaming kernels; 0 = library default for each. */
-    int32_t grid_blocks;          /* > 0: persistent grid of that many workgroups, each walking chunks
-                                     b, b+grid, ...; default: one chunk per workgroup */
-    int32_t unroll;               /* 128-bit vectors per lane per stream kept in flight: 1, 2 or 4 (default 4) */
+    int32_t grid_blocks;          /* > 0: persistent grid of that many workgroups, each walking work items
+                                     b, b+grid, ...; default: one work item per workgroup (a chunk in the
+                                     norm kernel; a chunk or a part of one in the update kernel) */
+    int32_t unroll;               /* 128-bit vectors per lane per array kept in flight by the update kernel:
+                                     1, 2 or 4 (default 4) */
     int32_t nontemporal;          /* streaming (non-temporal) loads and stores: 1 = on (default), 2 = off */
-    int32_t schedule;             /* order in which workgroups visit chunks: 1 = list order; w >= 2 = the list is
-                                     cut into w contiguous parts and workgroup b walks part b mod w
-                                     (default 8 = the number of XCDs workgroups are dealt to in turn) */
+    int32_t schedule;             /* visiting order of the chunks, see adagc_build_visiting_order: number of
+                                     contiguous parts the list is cut into (default 2; 1 = list order) */
+    int32_t update_split;         /* work items of the update kernel per chunk: 1 = whole chunks, or 2, 4, ...
+                                     up to chunk_elems / (unroll*1024).  Default (0): 4096-element items
+                                     (small items shorten the tail of the launch and give short lists more
+                                     workgroups; whole chunks cost the fewest dispatches) */
+    int32_t schedule_run;         /* visiting order: chunks an XCD takes in a row (default 8) */
 } adagc_config;
 
 /* Hyper-parameters of Alg. 1, passed by the caller on every step (the learning
@@ -126,6 +132,19 @@ int64_t adagc_chunk_elems(void);
 int adagc_build_segment_table(const adagc_tensor_desc* descs, int64_t n_tensors, int64_t chunk_elems,
                               int64_t* chunk_begin, uint32_t* chunk_tensor, uint32_t* chunk_index,
                               int64_t capacity, int64_t* n_chunks);
+
+/*
+ * Host-only: the order in which the streaming kernels visit the chunks.  Workgroups
+ * are dealt to the GPU's 8 XCDs (each with its own L2) in turn, so position k of the
+ * order is worked on by XCD k mod 8.  With parts in {1, 2, 4, 8} the list is cut into
+ * that many contiguous parts, XCD x works in part x mod parts, and the 8/parts XCDs
+ * that share a part take runs of `run` consecutive chunks in turn.  Any other parts
+ * value deals position k to part k mod parts (run is ignored).  The order changes
+ * which workgroup touches which chunk and when, never a result.
+ *   order  HOST  out, n_chunks entries: a permutation of 0 .. n_chunks-1
+ * Errors: INVALID_ARG (NULL, n_chunks/parts/run <= 0), TOO_LARGE.
+ */
+int adagc_build_visiting_order(int64_t n_chunks, int32_t parts, int32_t run, uint32_t* order);
 
 /*
  * Create a context for a fixed tensor list on the current GPU: validates the

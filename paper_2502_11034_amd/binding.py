@@ -24,7 +24,7 @@ ADAGC_GRAD_F32, ADAGC_GRAD_BF16 = 0, 1
 ADAGC_MODE_ADAGC, ADAGC_MODE_GLOBALGC, ADAGC_MODE_GLOBAL_ADAGC = 0, 1, 2
 
 EXPORTS = [
-    "adagc_chunk_elems", "adagc_build_segment_table", "adagc_create", "adagc_destroy",
+    "adagc_chunk_elems", "adagc_build_segment_table", "adagc_build_visiting_order", "adagc_create", "adagc_destroy",
     "adagc_set_param_copies", "adagc_step", "adagc_get_norms", "adagc_get_state_norms", "adagc_num_tensors",
     "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end",
     "adagc_strerror",
@@ -39,7 +39,8 @@ class adagc_config(ctypes.Structure):
     _fields_ = [("optimizer", ctypes.c_int32), ("grad_dtype", ctypes.c_int32),
                 ("has_bf16_param_copy", ctypes.c_int32), ("telemetry", ctypes.c_int32),
                 ("grid_blocks", ctypes.c_int32),
-                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32), ("schedule", ctypes.c_int32)]
+                ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32), ("schedule", ctypes.c_int32),
+                ("update_split", ctypes.c_int32), ("schedule_run", ctypes.c_int32)]
 
 
 class adagc_hyper(ctypes.Structure):
@@ -71,6 +72,8 @@ def lib():
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
     L.adagc_chunk_elems.restype = i64
     L.adagc_chunk_elems.argtypes = []
+    L.adagc_build_visiting_order.restype = ctypes.c_int
+    L.adagc_build_visiting_order.argtypes = [i64, ctypes.c_int32, ctypes.c_int32, vp]
     L.adagc_build_segment_table.restype = ctypes.c_int
     L.adagc_build_segment_table.argtypes = [vp, i64, i64, vp, vp, vp, i64, ctypes.POINTER(i64)]
     L.adagc_create.restype = ctypes.c_int
@@ -152,17 +155,27 @@ def adagc_build_segment_table(numels, chunk_elems=None):
     return begin, tensor, index
 
 
+def adagc_build_visiting_order(n_chunks, parts=2, run=8):
+    """Host-only.  Returns the visiting order, uint32[n_chunks]."""
+    order = np.zeros(max(int(n_chunks), 0), dtype=np.uint32)
+    _check(lib().adagc_build_visiting_order(int(n_chunks), int(parts), int(run),
+                                            order.ctypes.data if order.size else None),
+           "adagc_build_visiting_order")
+    return order
+
+
 class AdaGC:
     """Owner of one adagc_ctx.  Methods mirror the C entry points one to one."""
 
     def __init__(self, numels, optimizer=ADAGC_OPT_ADAMW, grad_dtype=ADAGC_GRAD_F32,
-                 has_bf16_param_copy=False, grid_blocks=0, unroll=0, nontemporal=0, schedule=0, telemetry=False):
+                 has_bf16_param_copy=False, grid_blocks=0, unroll=0, nontemporal=0, schedule=0, telemetry=False,
+                 update_split=0, schedule_run=0):
         L = lib()
         self._ctx = ctypes.c_void_p(None)
         self.n_tensors = len(numels)
         self.numels = [int(n) for n in numels]
         cfg = adagc_config(int(optimizer), int(grad_dtype), int(bool(has_bf16_param_copy)), int(bool(telemetry)),
-                           int(grid_blocks), int(unroll), int(nontemporal), int(schedule))
+                           int(grid_blocks), int(unroll), int(nontemporal), int(schedule), int(update_split), int(schedule_run))
         descs = _descs(self.numels)
         _check(L.adagc_create(ctypes.byref(self._ctx), ctypes.cast(descs, ctypes.c_void_p), self.n_tensors,
                               ctypes.byref(cfg)), "adagc_create")

@@ -76,7 +76,7 @@ struct DeviceTables {
     float*            coef;       // per tensor, fp32 (reported to the caller)
     double*           coef64;     // per tensor, as computed (what the update kernel multiplies by)
     uint8_t*          flag;       // per tensor, 1 = clip active
-    double*           tele_partials;  // telemetry: [3][n_chunks] sums of m^2, v^2, (dtheta)^2 (or null)
+    double*           tele_partials;  // telemetry: [3][n_chunks][items per chunk] sums of m^2, v^2, (dtheta)^2 (or null)
     float*            tele_norm;      // telemetry: [3][n_tensors] norms
     uint32_t          n_chunks;
     uint32_t          n_tensors;
@@ -87,6 +87,7 @@ hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int nt, i
 hipError_t launch_finalize_adagc(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
 hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
 hipError_t launch_update(const DeviceTables& t, const UpdateArgs& u, int optimizer, int grad_bf16,
-                         int with_copy, int unroll, int nt, int tele, int grid, hipStream_t stream);
+                         int with_copy, int unroll, int items_per_chunk, int nt, int tele, int grid,
+                         hipStream_t stream);
 
 }  // namespace adagc

@@ -19,6 +19,7 @@ struct adagc_ctx {
     int          grid_update = 0;   // workgroups of the update kernel
     int          unroll = 0;
     int          nontemporal = 0;
+    int          items_per_chunk = 1;   // work items of the update kernel per chunk
 
     std::vector<int64_t>    numel;
     std::vector<int64_t>    chunk_begin;      // n_tensors + 1
@@ -111,9 +112,14 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     if (cfg->grad_dtype != ADAGC_GRAD_F32 && cfg->grad_dtype != ADAGC_GRAD_BF16) return ADAGC_ERR_INVALID_ARG;
     if (cfg->has_bf16_param_copy != 0 && cfg->has_bf16_param_copy != 1) return ADAGC_ERR_INVALID_ARG;
     if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 2 || cfg->schedule < 0 ||
-        cfg->telemetry < 0 || cfg->telemetry > 1)
+        cfg->schedule_run < 0 || cfg->telemetry < 0 || cfg->telemetry > 1)
         return ADAGC_ERR_INVALID_ARG;
     if (cfg->unroll != 0 && cfg->unroll != 1 && cfg->unroll != 2 && cfg->unroll != 4) return ADAGC_ERR_INVALID_ARG;
+    {
+        const int tiles = kVecPerLane / (cfg->unroll ? cfg->unroll : 4);       // unroll*1024-element tiles per chunk
+        const int sp = cfg->update_split;
+        if (sp < 0 || sp > tiles || (sp & (sp - 1)) != 0) return ADAGC_ERR_INVALID_ARG;
+    }
     if (n_tensors > kMaxGridBlocks) return ADAGC_ERR_TOO_LARGE;   // the per-tensor kernels run one workgroup per tensor
 
     adagc_ctx* c = new (std::nothrow) adagc_ctx;
@@ -148,19 +154,34 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
         return ADAGC_ERR_HIP;
     }
     // Launch defaults, each chosen by measurement on Llama-3-8B shapes (see the profiles):
-    //  - one chunk per workgroup, dispatched by the hardware, beat a static persistent grid by
-    //    1.5-2 % (a CU that falls behind simply receives fewer chunks); grid_blocks > 0 selects
-    //    a persistent grid of that many workgroups, each walking chunks b, b+grid, ...
+    //  - one work item (a chunk in the norm kernel, a tile in the update kernel) per workgroup,
+    //    dispatched by the hardware, beat a static persistent grid by 1.5-2 % (a CU that falls
+    //    behind simply receives fewer); grid_blocks > 0 selects a persistent grid of that many
+    //    workgroups, each walking items b, b+grid, ...
     //  - non-temporal loads/stores in the update kernel: +4.5 %
-    //  - visiting order cut into 8 parts, so that the workgroups that land on one XCD
-    //    (workgroup b goes to XCD b mod 8) stream one contiguous eighth of the list: +0.5-1.3 %,
-    //    +5 % on the norm kernel.
+    //  - visiting order: the list cut into 2 halves, the 4 XCDs that share a half (workgroup b goes
+    //    to XCD b mod 8) taking runs of 8 chunks (512 KiB of each fp32 array) in turn.  Against
+    //    list order: norm kernel -5 %, update -3.5 %; against 8 parts (one per XCD): update
+    //    -1.9 % (AdamW, 8 B parameters), -0.4 % (Lion), -1.2 % (20 001 ragged tensors).  Fewer
+    //    address fronts per array mean fewer DRAM rows open at once; runs keep each XCD on
+    //    its own pages.
     c->unroll = cfg->unroll ? cfg->unroll : 4;
     c->nontemporal = cfg->nontemporal == 2 ? 0 : 1;
-    int64_t want = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : c->n_chunks;
-    if (want > kMaxGridBlocks) want = kMaxGridBlocks;            // the kernels walk chunks b, b+grid, ...
-    c->grid_norm = (int)(want < c->n_chunks ? want : c->n_chunks);
-    c->grid_update = c->grid_norm;
+    //  - work items of the update kernel: 4096 elements, a quarter of a chunk.  Against whole
+    //    chunks: AdamW on Llama-3-8B shapes -0.1 %, Lion -3.1 %, a 20 001-tensor ragged list
+    //    +0.2 %, 0.1-0.5 B-parameter lists -1.5...-3.7 % (shorter tail of the launch), a list of
+    //    50 chunks -25 % (more workgroups to spread over the CUs).  Halves are 0.9 % slower than
+    //    either on the 8 B list, and 1024-element items 16 % slower.
+    // Both streaming kernels walk their work items b, b+grid, ..., so any grid size is valid.
+    c->items_per_chunk = cfg->update_split ? cfg->update_split : (kChunkElems >= 4096 ? kChunkElems / 4096 : 1);
+    const int64_t tiles = ((c->n_chunks + 7) / 8 * 8) * c->items_per_chunk;
+    auto grid_for = [cfg](int64_t items) {
+        int64_t want = cfg->grid_blocks > 0 ? (int64_t)cfg->grid_blocks : items;
+        if (want > items) want = items;
+        return (int)(want > kMaxGridBlocks ? kMaxGridBlocks : want);
+    };
+    c->grid_norm = grid_for(c->n_chunks);
+    c->grid_update = grid_for(tiles);
 
     // One slab, carved into 256-byte aligned arrays.
     const size_t nt = (size_t)n_tensors, nc = (size_t)c->n_chunks;
@@ -176,7 +197,8 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     const size_t o_norm = carve(nt * sizeof(float));
     const size_t o_coef = carve(nt * sizeof(float));
     const size_t o_flag = carve(nt);
-    const size_t o_tele_partials = carve(cfg->telemetry ? 3 * nc * sizeof(double) : 0);
+    const size_t tiles_per_chunk = (size_t)c->items_per_chunk;
+    const size_t o_tele_partials = carve(cfg->telemetry ? 3 * nc * tiles_per_chunk * sizeof(double) : 0);
     const size_t o_tele_norm = carve(cfg->telemetry ? 3 * nt * sizeof(float) : 0);
     const size_t slab_bytes = off;
 
@@ -194,27 +216,15 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
         free_ctx(c);
         return ADAGC_ERR_HIP;
     }
-    // Visiting order.  With w parts, position k goes to part k mod w, at offset k / w inside it
-    // (parts differ in length by at most one chunk); w = 1 is the list order.
+    // Visiting order of the streaming kernels (see adagc_build_visiting_order).
     {
-        const size_t wparts = cfg->schedule == 0 ? 8 : (size_t)cfg->schedule;
         std::vector<uint32_t> order;
         try {
             order.resize(nc);
         } catch (const std::bad_alloc&) { free_ctx(c); return ADAGC_ERR_OOM; }
-        if (wparts <= 1 || wparts > nc) {
-            for (size_t k = 0; k < nc; ++k) order[k] = (uint32_t)k;
-        } else {
-            const size_t base_len = nc / wparts, extra = nc % wparts;   // first `extra` parts are one longer
-            size_t k = 0;
-            for (size_t row = 0; row <= base_len; ++row)
-                for (size_t part = 0; part < wparts; ++part) {
-                    const size_t len = base_len + (part < extra ? 1 : 0);
-                    if (row >= len) continue;
-                    const size_t start = part * base_len + (part < extra ? part : extra);
-                    order[k++] = (uint32_t)(start + row);
-                }
-        }
+        rc = adagc_build_visiting_order(c->n_chunks, cfg->schedule ? cfg->schedule : 2,
+                                        cfg->schedule_run ? cfg->schedule_run : 8, order.data());
+        if (rc != ADAGC_OK) { free_ctx(c); return rc; }
         if (hipMemcpy(base + o_schedule, order.data(), nc * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) {
             free_ctx(c);
             return ADAGC_ERR_HIP;
@@ -353,8 +363,8 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
                                : launch_finalize_adagc(ctx->tables, ema_norms, r, stream);
     if (e != hipSuccess) return ADAGC_ERR_HIP;
     if (prof && hipEventRecord(ev[2], stream) != hipSuccess) return ADAGC_ERR_HIP;
-    if (launch_update(ctx->tables, u, ctx->cfg.optimizer, bf16g, copy, ctx->unroll, ctx->nontemporal, ctx->cfg.telemetry,
-                      ctx->grid_update, stream) != hipSuccess)
+    if (launch_update(ctx->tables, u, ctx->cfg.optimizer, bf16g, copy, ctx->unroll, ctx->items_per_chunk,
+                      ctx->nontemporal, ctx->cfg.telemetry, ctx->grid_update, stream) != hipSuccess)
         return ADAGC_ERR_HIP;
     if (prof) {
         if (hipEventRecord(ev[3], stream) != hipSuccess) return ADAGC_ERR_HIP;

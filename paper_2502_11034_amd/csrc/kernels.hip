@@ -212,11 +212,10 @@ __global__ __launch_bounds__(kBlock) void sumsq_partials_kernel(DeviceTables t)
 // wave tree, waves through LDS in wave order.
 
 __device__ __forceinline__ double tensor_slot_sum(const DeviceTables& t, const double* slots, uint32_t i,
-                                                  double* wave_sums)
+                                                  double* wave_sums, uint32_t slots_per_chunk = 1)
 {
-    const uint32_t begin = t.targs[i].chunk_begin;
-    const uint32_t count = t.targs[i].chunk_count;
-    const double* p = slots + begin;
+    const uint32_t count = t.targs[i].chunk_count * slots_per_chunk;
+    const double* p = slots + (size_t)t.targs[i].chunk_begin * slots_per_chunk;
     double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     uint32_t k = threadIdx.x;
     for (; k + 3 * kBlock < count; k += 4 * kBlock) {
@@ -416,20 +415,38 @@ __device__ __forceinline__ void tele_vec(double (&acc)[3], f32x4 p_old, f32x4 p_
     tele_elem<HAS_V>(acc, p_old.w, p_new.w, m.w, v.w);
 }
 
+// A tile is U*kBlock consecutive 128-bit vectors (U*1024 elements) of one chunk, handled with U vectors per
+// lane and per array in flight; a chunk has kVecPerLane/U tiles.  A workgroup's work item is 1/items_per_chunk
+// of a chunk: a run of consecutive tiles (the whole chunk when items_per_chunk is 1).  Small items shorten
+// the tail of the launch and give short lists more workgroups; whole chunks cost the fewest dispatches.
+// Workgroups are dealt to the XCDs in turn (workgroup b to XCD b mod 8), so items are numbered such that
+// eight consecutive workgroups work on eight consecutive positions of the visiting order (one from each of
+// its parts) and the items of one chunk all go to the same XCD:
+//   item T  ->  position 8*(T / (8*I)) + T % 8,  item (T / 8) % I of that chunk      (I = items_per_chunk).
 template <int OPT, bool BF16G, bool COPY, int U, bool NT, bool TELE>
-__global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateArgs a)
+__global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateArgs a, uint32_t items_per_chunk)
 {
+    static_assert(kVecPerLane % U == 0, "a chunk is a whole number of tiles");
     constexpr bool NTL = NT, NTS = NT;    // non-temporal loads and stores
     constexpr bool kHasV = (OPT == ADAGC_OPT_ADAMW);
+    constexpr int kTiles = kVecPerLane / U;
+    constexpr int kTileVecs = U * kBlock;
+    constexpr int kTileElems = kTileVecs * 4;
     const int tid = threadIdx.x;
     __shared__ double tele_sums[3][kWavesPerBlock];
 
-    for (uint32_t k = blockIdx.x; k < t.n_chunks; k += gridDim.x) {
+    const uint32_t group = 8u * items_per_chunk;
+    const int tiles_per_item = kTiles / (int)items_per_chunk;
+    const uint64_t n_items = (uint64_t)((t.n_chunks + 7u) & ~7u) * items_per_chunk;
+    for (uint64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const uint32_t r = (uint32_t)(item % group);
+        const uint32_t k = (uint32_t)(item / group) * 8u + (r & 7u);
+        const int isub = (int)(r >> 3);
+        if (k >= t.n_chunks) continue;
         const uint32_t c = t.schedule[k];
         const ChunkView cv = chunk_view(t, c);
         const TensorArgs& ta = t.targs[cv.tensor];
         const double h = t.coef64[cv.tensor];     // the tensor's coefficient as computed, in double
-
         const void* g = grad_chunk_ptr<BF16G>(ta.grad, cv.first);
         float* p = reinterpret_cast<float*>(ta.param) + cv.first;
         float* m = reinterpret_cast<float*>(ta.exp_avg) + cv.first;
@@ -437,20 +454,24 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
         uint16_t* pc = COPY ? reinterpret_cast<uint16_t*>(ta.param_copy) + cv.first : nullptr;
         double tele[3] = {0.0, 0.0, 0.0};
 
-        if (ta.vec_ok) {
-            f32x4* p4 = reinterpret_cast<f32x4*>(p);
-            f32x4* m4 = reinterpret_cast<f32x4*>(m);
-            f32x4* v4 = reinterpret_cast<f32x4*>(v);
-            u32x2* c4 = reinterpret_cast<u32x2*>(pc);
-            const int nvec = cv.len >> 2;
-
-            if (cv.len == kChunkElems) {
 #pragma unroll 1
-                for (int it = 0; it < kVecPerLane; it += U) {
+        for (int tt = 0; tt < tiles_per_item; ++tt) {
+            const int sub = isub * tiles_per_item + tt;
+            const int e0 = sub * kTileElems;                                   // the tile's elements inside the chunk:
+            const int e1 = cv.len < e0 + kTileElems ? cv.len : e0 + kTileElems; // [e0, e1), empty past a ragged end
+            if (e0 >= e1) break;
+            if (ta.vec_ok) {
+                f32x4* p4 = reinterpret_cast<f32x4*>(p);
+                f32x4* m4 = reinterpret_cast<f32x4*>(m);
+                f32x4* v4 = reinterpret_cast<f32x4*>(v);
+                u32x2* c4 = reinterpret_cast<u32x2*>(pc);
+                const int v0 = sub * kTileVecs;
+
+                if (e1 - e0 == kTileElems) {
                     f32x4 gg[U], pp[U], mm[U], vv[U];
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const int idx = (it + u) * kBlock + tid;
+                        const int idx = v0 + u * kBlock + tid;
                         gg[u] = load_grad4<BF16G, NTL>(g, idx);
                         pp[u] = ld<NTL>(p4 + idx);
                         mm[u] = ld<NTL>(m4 + idx);
@@ -459,7 +480,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const int idx = (it + u) * kBlock + tid;
+                        const int idx = v0 + u * kBlock + tid;
                         const f32x4 p_old = pp[u];
                         apply_vec<OPT>(a, h, gg[u], pp[u], mm[u], vv[u]);
                         if constexpr (TELE) tele_vec<kHasV>(tele, p_old, pp[u], mm[u], vv[u]);
@@ -468,24 +489,37 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                         if constexpr (kHasV) st<NTS>(v4 + idx, vv[u]);
                         if constexpr (COPY) st<NTS>(c4 + idx, pack_bf16x4(pp[u]));
                     }
+                } else {
+                    // the last tile of a ragged chunk: its whole vectors, then up to three single elements
+                    const int nvec = cv.len >> 2;
+                    for (int idx = v0 + tid; idx < nvec; idx += kBlock) {
+                        f32x4 gg = load_grad4<BF16G, NTL>(g, idx);
+                        f32x4 pp = ld<NTL>(p4 + idx);
+                        f32x4 mm = ld<NTL>(m4 + idx);
+                        f32x4 vv = f32x4{0.f, 0.f, 0.f, 0.f};
+                        if constexpr (kHasV) vv = ld<NTL>(v4 + idx);
+                        const f32x4 p_old = pp;
+                        apply_vec<OPT>(a, h, gg, pp, mm, vv);
+                        if constexpr (TELE) tele_vec<kHasV>(tele, p_old, pp, mm, vv);
+                        st<NTS>(p4 + idx, pp);
+                        st<NTS>(m4 + idx, mm);
+                        if constexpr (kHasV) st<NTS>(v4 + idx, vv);
+                        if constexpr (COPY) st<NTS>(c4 + idx, pack_bf16x4(pp));
+                    }
+                    const int j = (nvec << 2) + tid;
+                    if (j < cv.len) {
+                        ElemState s = {p[j], m[j], kHasV ? v[j] : 0.f};
+                        const float p_old = s.p;
+                        apply_elem<OPT>(a, h, load_grad1<BF16G>(g, j), s);
+                        if constexpr (TELE) tele_elem<kHasV>(tele, p_old, s.p, s.m, s.v);
+                        p[j] = s.p;
+                        m[j] = s.m;
+                        if constexpr (kHasV) v[j] = s.v;
+                        if constexpr (COPY) pc[j] = (uint16_t)float_to_bf16_bits(s.p);
+                    }
                 }
             } else {
-                for (int idx = tid; idx < nvec; idx += kBlock) {
-                    f32x4 gg = load_grad4<BF16G, NTL>(g, idx);
-                    f32x4 pp = ld<NTL>(p4 + idx);
-                    f32x4 mm = ld<NTL>(m4 + idx);
-                    f32x4 vv = f32x4{0.f, 0.f, 0.f, 0.f};
-                    if constexpr (kHasV) vv = ld<NTL>(v4 + idx);
-                    const f32x4 p_old = pp;
-                    apply_vec<OPT>(a, h, gg, pp, mm, vv);
-                    if constexpr (TELE) tele_vec<kHasV>(tele, p_old, pp, mm, vv);
-                    st<NTS>(p4 + idx, pp);
-                    st<NTS>(m4 + idx, mm);
-                    if constexpr (kHasV) st<NTS>(v4 + idx, vv);
-                    if constexpr (COPY) st<NTS>(c4 + idx, pack_bf16x4(pp));
-                }
-                const int j = (nvec << 2) + tid;
-                if (j < cv.len) {
+                for (int j = e0 + tid; j < e1; j += kBlock) {
                     ElemState s = {p[j], m[j], kHasV ? v[j] : 0.f};
                     const float p_old = s.p;
                     apply_elem<OPT>(a, h, load_grad1<BF16G>(g, j), s);
@@ -496,20 +530,10 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                     if constexpr (COPY) pc[j] = (uint16_t)float_to_bf16_bits(s.p);
                 }
             }
-        } else {
-            for (int j = tid; j < cv.len; j += kBlock) {
-                ElemState s = {p[j], m[j], kHasV ? v[j] : 0.f};
-                const float p_old = s.p;
-                apply_elem<OPT>(a, h, load_grad1<BF16G>(g, j), s);
-                if constexpr (TELE) tele_elem<kHasV>(tele, p_old, s.p, s.m, s.v);
-                p[j] = s.p;
-                m[j] = s.m;
-                if constexpr (kHasV) v[j] = s.v;
-                if constexpr (COPY) pc[j] = (uint16_t)float_to_bf16_bits(s.p);
-            }
         }
 
         if constexpr (TELE) {
+            // every item of every chunk writes its slots, an empty item writes zeros
 #pragma unroll
             for (int q = 0; q < 3; ++q) {
                 const double w = wave_sum_f64(tele[q]);
@@ -520,26 +544,27 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                 double b = tele_sums[tid][0];
 #pragma unroll
                 for (int w = 1; w < kWavesPerBlock; ++w) b += tele_sums[tid][w];
-                t.tele_partials[(size_t)tid * t.n_chunks + c] = b;
+                t.tele_partials[((size_t)tid * t.n_chunks + c) * items_per_chunk + isub] = b;
             }
             __syncthreads();
         }
     }
 }
 
-// Telemetry finalize: per tensor, the three norms from the chunk slots (same fixed order as K2).
-__global__ __launch_bounds__(kBlock) void finalize_telemetry_kernel(DeviceTables t)
+// Telemetry finalize: per tensor, the three norms from the item slots (same fixed order as K2).
+__global__ __launch_bounds__(kBlock) void finalize_telemetry_kernel(DeviceTables t, uint32_t items_per_chunk)
 {
     __shared__ double wave_sums[kWavesPerBlock];
     const uint32_t i = blockIdx.x;
     for (int q = 0; q < 3; ++q) {
-        const double s = tensor_slot_sum(t, t.tele_partials + (size_t)q * t.n_chunks, i, wave_sums);
+        const double s = tensor_slot_sum(t, t.tele_partials + (size_t)q * t.n_chunks * items_per_chunk, i, wave_sums,
+                                         items_per_chunk);
         if (threadIdx.x == 0) t.tele_norm[(size_t)q * t.n_tensors + i] = (float)sqrt(s);
         __syncthreads();
     }
 }
 
-using UpdateFn = void (*)(DeviceTables, UpdateArgs);
+using UpdateFn = void (*)(DeviceTables, UpdateArgs, uint32_t);
 using SumsqFn = void (*)(DeviceTables);
 
 template <int OPT, bool BF16G, bool COPY, int U>
@@ -606,12 +631,14 @@ hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleA
 }
 
 hipError_t launch_update(const DeviceTables& t, const UpdateArgs& a, int optimizer, int grad_bf16,
-                         int with_copy, int unroll, int nt, int tele, int grid, hipStream_t stream)
+                         int with_copy, int unroll, int items_per_chunk, int nt, int tele, int grid,
+                         hipStream_t stream)
 {
-    select_update(optimizer, grad_bf16, with_copy, unroll, nt, tele)<<<dim3(grid), dim3(kBlock), 0, stream>>>(t, a);
+    select_update(optimizer, grad_bf16, with_copy, unroll, nt, tele)<<<dim3(grid), dim3(kBlock), 0, stream>>>(
+        t, a, (uint32_t)items_per_chunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !tele) return e;
-    finalize_telemetry_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t);
+    finalize_telemetry_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t, (uint32_t)items_per_chunk);
     return hipGetLastError();
 }
 

@@ -4,6 +4,8 @@
 
 #include <stdint.h>
 
+#include <vector>
+
 #include "adagc.h"
 
 extern "C" int adagc_build_segment_table(const adagc_tensor_desc* descs, int64_t n_tensors,
@@ -43,5 +45,51 @@ extern "C" int adagc_build_segment_table(const adagc_tensor_desc* descs, int64_t
     }
     chunk_begin[n_tensors] = c;
     *n_chunks = c;
+    return ADAGC_OK;
+}
+
+// Visiting order of the streaming kernels.  Workgroups are dealt to the 8 XCDs in turn, so position k of
+// the order is worked on by XCD k mod 8.  With `parts` in {1, 2, 4, 8} the list is cut into that many
+// contiguous parts, XCD x works in part x mod parts, and the 8/parts XCDs that share a part take runs of
+// `run` consecutive chunks in turn.  Any other `parts` value deals position k to part k mod parts.
+extern "C" int adagc_build_visiting_order(int64_t n_chunks, int32_t parts, int32_t run, uint32_t* order)
+{
+    if (!order || n_chunks <= 0 || parts <= 0 || run <= 0) return ADAGC_ERR_INVALID_ARG;
+    if (n_chunks > (int64_t)UINT32_MAX) return ADAGC_ERR_TOO_LARGE;
+    const uint64_t nc = (uint64_t)n_chunks, w = (uint64_t)parts, R = (uint64_t)run;
+    if (w == 1 && R == 1) {
+        for (uint64_t k = 0; k < nc; ++k) order[k] = (uint32_t)k;
+        return ADAGC_OK;
+    }
+    if (w > nc) {                                     // more parts than chunks: list order
+        for (uint64_t k = 0; k < nc; ++k) order[k] = (uint32_t)k;
+        return ADAGC_OK;
+    }
+    const uint64_t base_len = nc / w, extra = nc % w;     // the first `extra` parts are one chunk longer
+    auto part_start = [&](uint64_t p) { return p * base_len + (p < extra ? p : extra); };
+    auto part_len = [&](uint64_t p) { return base_len + (p < extra ? 1 : 0); };
+    if (8 % w != 0) {
+        // position k -> part k mod w, at offset k / w inside it
+        uint64_t k = 0;
+        for (uint64_t row = 0; row <= base_len; ++row)
+            for (uint64_t p = 0; p < w; ++p)
+                if (row < part_len(p)) order[k++] = (uint32_t)(part_start(p) + row);
+        return ADAGC_OK;
+    }
+    // One cursor per XCD: the XCD's share index among the `share` XCDs of its part, and its position
+    // inside the current run.  Positions are handed out XCD by XCD; an XCD whose part is used up is
+    // skipped (this only happens in the last few positions).
+    const uint64_t share = 8 / w;
+    uint64_t block[8] = {0, 0, 0, 0, 0, 0, 0, 0}, within[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint64_t k = 0;
+    while (k < nc) {
+        for (uint64_t x = 0; x < 8 && k < nc; ++x) {
+            const uint64_t p = x % w, sidx = x / w, len = part_len(p);
+            uint64_t off = (block[x] * share + sidx) * R + within[x];
+            if (off >= len) continue;
+            order[k++] = (uint32_t)(part_start(p) + off);
+            if (++within[x] == R) { within[x] = 0; ++block[x]; }
+        }
+    }
     return ADAGC_OK;
 }

@@ -58,20 +58,26 @@ def main():
               flush=True)
 
     show("defaults")
-    print("-- workgroups: one chunk each (default) against persistent grids")
+    print("-- workgroups: one work item each (default) against persistent grids")
     for grid in (512, 1024, 2048, 4096):
         show("grid_blocks=%d (persistent, static round-robin)" % grid, grid_blocks=grid)
     print("-- non-temporal hints")
     for nt, name in ((1, "on (default)"), (2, "off")):
         show("nontemporal %s" % name, nontemporal=nt)
-    print("-- visiting order: parts (workgroup b walks part b mod parts)")
-    for parts in (1, 2, 8, 64, 1021):
-        show("schedule=%d%s" % (parts, " (default)" if parts == 8 else ""), schedule=parts)
+    print("-- visiting order: parts x run (XCD x works in part x mod parts; sharing XCDs take runs of chunks in turn)")
+    for parts, runlen in ((1, 1), (1, 8), (2, 1), (2, 4), (2, 8), (2, 16), (2, 64), (4, 1), (4, 4), (4, 8), (8, 1), (64, 1),
+                       (1021, 1)):
+        show("schedule=%d schedule_run=%d%s" % (parts, runlen, " (default)" if (parts, runlen) == (2, 8) else ""),
+             schedule=parts, schedule_run=runlen)
     print("-- 128-bit vectors per lane per array in flight")
     for unroll in (1, 2, 4):
         show("unroll=%d%s" % (unroll, " (default)" if unroll == 4 else ""), unroll=unroll)
+    print("-- work items of the update kernel per chunk (1 = whole chunks; default 4 = 4096 elements)")
+    for split in (1, 2, 4):
+        show("update_split=%d" % split, update_split=split)
+    show("update_split=16 unroll=1", update_split=16, unroll=1)
     print("-- combinations")
-    for grid, nt, parts in itertools.product((0, 1024), (1, 2), (1, 8)):
+    for grid, nt, parts in itertools.product((0, 1024), (1, 2), (2, 8)):
         show("grid_blocks=%d nontemporal=%d schedule=%d" % (grid, nt, parts), grid_blocks=grid, nontemporal=nt,
              schedule=parts)
     print("-- telemetry")

@@ -55,6 +55,20 @@ int main()
     std::vector<int64_t> begin(n + 1);
     CHECK(adagc_build_segment_table(descs.data(), n, 16, begin.data(), nullptr, nullptr, 0, &total) == ADAGC_ERR_INVALID_ARG);
 
+    // ---- visiting order: a permutation for every (parts, run)
+    for (int64_t nc : {1, 7, 8, 9, 63, 64, 65, 1000, 4099})
+        for (int32_t parts : {1, 2, 3, 4, 8, 16, 5000})
+            for (int32_t run : {1, 2, 8, 13}) {
+                std::vector<uint32_t> order((size_t)nc, 0xFFFFFFFFu);
+                CHECK(adagc_build_visiting_order(nc, parts, run, order.data()) == ADAGC_OK);
+                std::vector<char> seen((size_t)nc, 0);
+                for (uint32_t c : order) {
+                    CHECK(c < (uint32_t)nc && !seen[c]);
+                    seen[c] = 1;
+                }
+            }
+    CHECK(adagc_build_visiting_order(0, 2, 8, nullptr) == ADAGC_ERR_INVALID_ARG);
+
     // ---- oracle: several steps through warm-up, AdaGC, the global modes, AdamW and Lion, fp32 and bf16
     for (int optimizer = 0; optimizer < 2; ++optimizer)
         for (int dtype = 0; dtype < 2; ++dtype)

@@ -28,7 +28,7 @@ def test_header_symbols_are_exported():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.adagc_tensor_desc) == 16
-    assert ctypes.sizeof(B.adagc_config) == 32
+    assert ctypes.sizeof(B.adagc_config) == 40
     assert ctypes.sizeof(B.adagc_hyper) == 40
 
 
@@ -41,7 +41,8 @@ def test_strerror():
 def _create(numels, **cfg_kw):
     L = B.lib()
     ctx = ctypes.c_void_p(None)
-    fields = dict(optimizer=0, grad_dtype=0, has_bf16_param_copy=0, telemetry=0, grid_blocks=0, unroll=0, nontemporal=0, schedule=0)
+    fields = dict(optimizer=0, grad_dtype=0, has_bf16_param_copy=0, telemetry=0, grid_blocks=0, unroll=0, nontemporal=0, schedule=0,
+                  update_split=0, schedule_run=0)
     fields.update(cfg_kw)
     cfg = B.adagc_config(**fields)
     descs = (B.adagc_tensor_desc * max(1, len(numels)))()
@@ -62,6 +63,10 @@ def test_create_validates_before_touching_the_device():
     assert _create([4], grid_blocks=-1)[0] == B.ADAGC_ERR_INVALID_ARG
     assert _create([4], telemetry=2)[0] == B.ADAGC_ERR_INVALID_ARG
     assert _create([4], nontemporal=3)[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], update_split=3)[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], update_split=8)[0] == B.ADAGC_ERR_INVALID_ARG      # more than 16384 / (4*1024)
+    assert _create([4], update_split=16, unroll=2)[0] == B.ADAGC_ERR_INVALID_ARG
+    assert _create([4], schedule_run=-1)[0] == B.ADAGC_ERR_INVALID_ARG
     cfg = B.adagc_config()
     assert L.adagc_create(None, None, 1, ctypes.byref(cfg)) == B.ADAGC_ERR_INVALID_ARG
     rc, ctx = _create([4])

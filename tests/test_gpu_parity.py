@@ -301,8 +301,8 @@ def test_global_adagc_mode_single_adaptive_threshold():
     run.compare_state("global-adagc")
 
 
-def _telemetry_case(optimizer, w, hp, name):
-    run = P.Run(w, optimizer=optimizer, telemetry=True)
+def _telemetry_case(optimizer, w, hp, name, **knobs):
+    run = P.Run(w, optimizer=optimizer, telemetry=True, **knobs)
     plain = P.Run(w, optimizer=optimizer, mirror=False)
     for step in range(1, 5):
         grads = w.make_grads(step, DEV)
@@ -350,7 +350,7 @@ def test_telemetry_state_norms_lion_bf16_grads():
     specs = W.llama_like_list(1, 256, 4, 2, 896, 4000)
     w = W.config4(specs)
     w.spikes = {3: (np.arange(0, len(specs), 4), 50.0)}
-    _telemetry_case("lion", w, B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99), "telemetry-lion")
+    _telemetry_case("lion", w, B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99), "telemetry-lion", update_split=1)
 
 
 # --------------------------------------------------------------------------- determinism, state, errors
@@ -457,7 +457,10 @@ def test_launch_tuning_knobs_do_not_change_results():
     outs = []
     for kw in (dict(), dict(grid_blocks=7), dict(unroll=1), dict(unroll=4, nontemporal=1),
                dict(grid_blocks=100000, unroll=2, nontemporal=2), dict(schedule=1), dict(schedule=7, grid_blocks=50),
-               dict(schedule=1000000), dict(grid_blocks=1024, schedule=2, unroll=1, nontemporal=2)):
+               dict(schedule=1000000), dict(grid_blocks=1024, schedule=2, unroll=1, nontemporal=2),
+               dict(schedule=8), dict(schedule=2, schedule_run=1), dict(schedule=4, schedule_run=3),
+               dict(update_split=1), dict(update_split=2, grid_blocks=33), dict(update_split=4, schedule=3),
+               dict(update_split=16, unroll=1), dict(update_split=8, unroll=2, nontemporal=2)):
         run = P.Run(w, mirror=False, **kw)
         for step in range(1, 4):
             run.gpu_step(w.make_grads(step, DEV), hp, step)
@@ -588,7 +591,8 @@ def test_seeded_sweep_of_lists_modes_and_dtypes():
         mode = int(rng.integers(0, 3))
         t_start = int(rng.integers(0, 4))
         knobs = dict(unroll=int(rng.choice([0, 1, 2, 4])), schedule=int(rng.choice([0, 1, 3, 8])),
-                     grid_blocks=int(rng.choice([0, 0, 5, 64])), nontemporal=int(rng.choice([0, 1, 2])))
+                     grid_blocks=int(rng.choice([0, 0, 5, 64])), nontemporal=int(rng.choice([0, 1, 2])),
+                     update_split=int(rng.choice([0, 1, 2, 4])), schedule_run=int(rng.choice([0, 1, 3])))
         specs = [W.TensorSpec("t%d" % i, (k,), "matrix") for i, k in enumerate(numels)]
         spikes = {2: (np.arange(0, n, 2), 30.0), 3: (np.arange(1, n, 2), 30.0)}
         w = W.Workload(specs, seed=1000 + case, spikes=spikes, bf16_copy=copy,

@@ -79,3 +79,38 @@ def test_builder_rejects_bad_input():
     with pytest.raises(B.AdagcError) as e:
         B.adagc_build_segment_table([2 ** 40], 1)
     assert e.value.code == B.ADAGC_ERR_TOO_LARGE
+
+
+# --------------------------------------------------------------------------- visiting order (host only)
+
+@pytest.mark.parametrize("parts", [1, 2, 3, 4, 5, 8, 16, 1021])
+@pytest.mark.parametrize("run", [1, 2, 7, 8, 64])
+def test_visiting_order_is_a_permutation(parts, run):
+    for n in (1, 2, 7, 8, 9, 50, 63, 64, 65, 1000, 7686, 100003):
+        order = B.adagc_build_visiting_order(n, parts, run)
+        assert np.array_equal(np.sort(order), np.arange(n, dtype=np.uint32)), (n, parts, run)
+
+
+def test_visiting_order_shapes():
+    assert list(B.adagc_build_visiting_order(10, 1, 1)) == list(range(10))
+    # 2 parts of 32 chunks, runs of 8: XCD 0 (positions 0, 8, 16, ...) walks chunks 0..7 of the first half,
+    # XCD 1 walks chunks 0..7 of the second half, XCD 2 walks chunks 8..15 of the first half, ...
+    order = B.adagc_build_visiting_order(64, 2, 8)
+    assert list(order[0::8][:8]) == list(range(0, 8))
+    assert list(order[1::8][:8]) == list(range(32, 40))
+    assert list(order[2::8][:8]) == list(range(8, 16))
+    assert list(order[7::8][:8]) == list(range(56, 64))
+    # 8 parts: one XCD per part, the run length does not matter
+    assert np.array_equal(B.adagc_build_visiting_order(4096, 8, 8), B.adagc_build_visiting_order(4096, 8, 1))
+    assert list(B.adagc_build_visiting_order(4096, 8, 1)[:9]) == [0, 512, 1024, 1536, 2048, 2560, 3072, 3584, 1]
+    # parts that do not divide 8: position k -> part k mod parts
+    assert list(B.adagc_build_visiting_order(9, 3, 5)) == [0, 3, 6, 1, 4, 7, 2, 5, 8]
+    # more parts than chunks: list order
+    assert list(B.adagc_build_visiting_order(5, 8, 8)) == [0, 1, 2, 3, 4]
+
+
+def test_visiting_order_rejects_bad_arguments():
+    for args in ((0, 2, 8), (-1, 2, 8), (10, 0, 8), (10, 2, 0), (10, -2, 8)):
+        with pytest.raises(B.AdagcError) as e:
+            B.adagc_build_visiting_order(*args)
+        assert e.value.code == B.ADAGC_ERR_INVALID_ARG

@@ -102,3 +102,38 @@ def test_null_context_is_rejected_everywhere():
     assert L.adagc_profile_begin(None, 4) == B.ADAGC_ERR_INVALID_ARG
     assert L.adagc_num_chunks(None) < 0 and L.adagc_num_tensors(None) < 0
     L.adagc_destroy(None)   # no-op
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/adagc.h compiles as C99 with -pedantic, its struct sizes are the ones the binding assumes, and a C
+    program that only uses the host-side entry points links against libadagc.so and runs without a GPU."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "adagc.h"
+int main(void)
+{
+    adagc_tensor_desc d[3] = {{5, 0, 0}, {40000, 0, 0}, {1, 0, 0}};
+    int64_t begin[4], total = 0;
+    uint32_t order[8];
+    if (adagc_build_segment_table(d, 3, adagc_chunk_elems(), begin, NULL, NULL, 0, &total) != ADAGC_OK) return 1;
+    if (total != 5 || begin[3] != 5) return 2;
+    if (adagc_build_visiting_order(8, 2, 8, order) != ADAGC_OK) return 3;
+    if (adagc_step(NULL, NULL, NULL, NULL, NULL, NULL, NULL, 1, NULL) != ADAGC_ERR_INVALID_ARG) return 4;
+    printf("%d %d %d %s\n", (int)sizeof(adagc_tensor_desc), (int)sizeof(adagc_config), (int)sizeof(adagc_hyper),
+           adagc_strerror(ADAGC_ERR_STATE));
+    return 0;
+}
+''')
+    lib = B._build.LIB
+    exe = str(tmp_path / "use_header")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", exe, lib, "-Wl,-rpath," + os.path.dirname(lib)], check=True)
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert res.stdout.split()[:3] == ["16", "40", "40"]
+    assert "wrong state" in res.stdout

@@ -113,6 +113,13 @@ typedef struct {
     int32_t clip_mode;     /* ADAGC_MODE_*; 0 = the paper's method */
 } adagc_hyper;
 
+/* Device-resident inputs of adagc_step_graph: the hyper-parameters and the step number are read by the
+ * GPU when the step runs, not by the host when it is enqueued. */
+typedef struct {
+    adagc_hyper hp;
+    int64_t     step;      /* 1-based t of Alg. 1 */
+} adagc_step_params;
+
 /* Elements per chunk of the segment table (a compile-time constant of the library). */
 int64_t adagc_chunk_elems(void);
 
@@ -191,6 +198,28 @@ int adagc_set_param_copies(adagc_ctx* ctx, void* const* params_bf16);
 int adagc_step(adagc_ctx* ctx, void* const* params, const void* const* grads,
                void* const* exp_avg, void* const* exp_avg_sq, float* ema_norms,
                const adagc_hyper* hp, int64_t step, void* stream);
+
+/*
+ * adagc_step for callers that record their work into a HIP graph: the same step, except that the
+ * hyper-parameters and the step number come from DEVICE memory and are read when the kernels run.
+ * A launch sequence recorded once (stream capture) can therefore be replayed for every later step;
+ * between replays the caller updates *step_params (a copy or kernel of its own, ordered before the
+ * replay).  Which branch of Alg. 1 applies (warm-up or not, clip_mode) is decided on the device, so
+ * the recorded sequence is the same for all of them: two more small kernels than adagc_step.
+ *   step_params  DEVICE adagc_step_params, read by the GPU during the step
+ *   other arguments as for adagc_step
+ * The parameters cannot be validated on the host: a step whose parameters adagc_step would reject
+ * leaves all state untouched, and the next adagc_get_norms / adagc_get_state_norms returns
+ * INVALID_ARG.  The bias corrections use the device's pow(), which may differ from the host's in
+ * the last bit of a double (invisible after rounding to fp32 in all but about one value in 10^8).
+ * While `stream` is capturing, the call records kernels only: the tensor pointers must be the ones
+ * of the previous call on this context (make one uncaptured call first; otherwise STATE), and
+ * adagc_profile_begin must not be active.  Allocates nothing.
+ * Errors: INVALID_ARG, STATE, HIP.
+ */
+int adagc_step_graph(adagc_ctx* ctx, void* const* params, const void* const* grads,
+                     void* const* exp_avg, void* const* exp_avg_sq, float* ema_norms,
+                     const adagc_step_params* step_params, void* stream);
 
 /*
  * Per-tensor results of the most recently enqueued step: copies them to the host

@@ -25,7 +25,7 @@ ADAGC_MODE_ADAGC, ADAGC_MODE_GLOBALGC, ADAGC_MODE_GLOBAL_ADAGC = 0, 1, 2
 
 EXPORTS = [
     "adagc_chunk_elems", "adagc_build_segment_table", "adagc_build_visiting_order", "adagc_create", "adagc_destroy",
-    "adagc_set_param_copies", "adagc_step", "adagc_get_norms", "adagc_get_state_norms", "adagc_num_tensors",
+    "adagc_set_param_copies", "adagc_step", "adagc_step_graph", "adagc_get_norms", "adagc_get_state_norms", "adagc_num_tensors",
     "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end",
     "adagc_strerror",
 ]
@@ -48,6 +48,10 @@ class adagc_hyper(ctypes.Structure):
                 ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
                 ("lambda_rel", ctypes.c_float), ("ema_beta", ctypes.c_float),
                 ("lambda_abs", ctypes.c_float), ("t_start", ctypes.c_int32), ("clip_mode", ctypes.c_int32)]
+
+
+class adagc_step_params(ctypes.Structure):
+    _fields_ = [("hp", adagc_hyper), ("step", ctypes.c_int64)]
 
 
 class AdagcError(RuntimeError):
@@ -84,6 +88,8 @@ def lib():
     L.adagc_set_param_copies.argtypes = [vp, vp]
     L.adagc_step.restype = ctypes.c_int
     L.adagc_step.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(adagc_hyper), i64, vp]
+    L.adagc_step_graph.restype = ctypes.c_int
+    L.adagc_step_graph.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.adagc_get_norms.restype = ctypes.c_int
     L.adagc_get_norms.argtypes = [vp, vp, vp, vp, i64, vp]
     L.adagc_get_state_norms.restype = ctypes.c_int
@@ -155,6 +161,11 @@ def adagc_build_segment_table(numels, chunk_elems=None):
     return begin, tensor, index
 
 
+def step_params_bytes(hyper, step):
+    """The 48 bytes of an adagc_step_params, ready to be copied into device memory."""
+    return bytes(adagc_step_params(hyper, int(step)))
+
+
 def adagc_build_visiting_order(n_chunks, parts=2, run=8):
     """Host-only.  Returns the visiting order, uint32[n_chunks]."""
     order = np.zeros(max(int(n_chunks), 0), dtype=np.uint32)
@@ -203,6 +214,15 @@ class AdaGC:
         v = ptr_array(exp_avg_sq) if exp_avg_sq is not None else None
         _check(lib().adagc_step(self._ctx, p, g, m, v, ema_norms.data_ptr(), ctypes.byref(hyper), int(step),
                                 ctypes.c_void_p(stream) if stream else None), "adagc_step")
+
+    # -- adagc_step_graph
+    def step_graph(self, params, grads, exp_avg, exp_avg_sq, ema_norms, step_params, stream=None):
+        """As step(), with hyper-parameters and step number read on the GPU from `step_params`: a device
+        tensor of 48 bytes holding an adagc_step_params (see step_params_bytes)."""
+        p, g, m = (ptr_array(x) for x in (params, grads, exp_avg))
+        v = ptr_array(exp_avg_sq) if exp_avg_sq is not None else None
+        _check(lib().adagc_step_graph(self._ctx, p, g, m, v, ema_norms.data_ptr(), step_params.data_ptr(),
+                                      ctypes.c_void_p(stream) if stream else None), "adagc_step_graph")
 
     # -- adagc_get_norms
     def get_norms(self, stream=None):

@@ -65,6 +65,16 @@ struct UpdateArgs {
     double weight_decay;   // Lion
 };
 
+// Scalars of one step kept in device memory: written by a small kernel from the caller's
+// device-resident adagc_step_params, read by the rule kernels and the update kernel.  This is what
+// lets a step be recorded into a HIP graph once and replayed for other step numbers.
+struct StepScalars {
+    RuleArgs   r;
+    UpdateArgs u;
+    int32_t    status;   // 0 = valid; otherwise the step leaves all state untouched
+    int32_t    pad;
+};
+
 struct DeviceTables {
     const ChunkRef*   chunks;     // canonical order: tensor by tensor; slot c of `partials` belongs to chunk c
     const uint32_t*   schedule;   // order in which the streaming kernels visit the chunks
@@ -78,6 +88,7 @@ struct DeviceTables {
     uint8_t*          flag;       // per tensor, 1 = clip active
     double*           tele_partials;  // telemetry: [3][n_chunks][items per chunk] sums of m^2, v^2, (dtheta)^2 (or null)
     float*            tele_norm;      // telemetry: [3][n_tensors] norms
+    StepScalars*      scalars;        // used by adagc_step_graph only
     uint32_t          n_chunks;
     uint32_t          n_tensors;
 };
@@ -88,6 +99,10 @@ hipError_t launch_finalize_adagc(const DeviceTables& t, float* ema, const RuleAr
 hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream);
 hipError_t launch_update(const DeviceTables& t, const UpdateArgs& u, int optimizer, int grad_bf16,
                          int with_copy, int unroll, int items_per_chunk, int nt, int tele, int grid,
-                         hipStream_t stream);
+                         hipStream_t stream, bool device_scalars = false);
+// Rule stage of adagc_step_graph: scalars from device-resident step parameters, then the per-tensor
+// sums, the model-wide rule (a no-op outside warm-up and the global modes) and the per-tensor rule.
+hipError_t launch_rules_from_device(const DeviceTables& t, float* ema, const adagc_step_params* params,
+                                    int optimizer, hipStream_t stream);
 
 }  // namespace adagc

@@ -34,6 +34,7 @@ struct adagc_ctx {
     TensorArgs*  staging = nullptr;           // pinned host mirror for the async upload
     hipEvent_t   upload_done = nullptr;
     bool         upload_pending = false;
+    bool         device_scalars_used = false;   // adagc_step_graph was called: its status word is meaningful
 
     std::vector<hipEvent_t> prof_events;      // 4 per step while profiling
     int32_t                 prof_capacity = 0;
@@ -193,6 +194,7 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     const size_t o_partials = carve(nc * sizeof(double));
     const size_t o_sumsq = carve(nt * sizeof(double));
     const size_t o_global = carve(4 * sizeof(double));
+    const size_t o_scalars = carve(sizeof(StepScalars));
     const size_t o_coef64 = carve(nt * sizeof(double));
     const size_t o_norm = carve(nt * sizeof(float));
     const size_t o_coef = carve(nt * sizeof(float));
@@ -245,6 +247,7 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     t.partials = reinterpret_cast<double*>(base + o_partials);
     t.sumsq = reinterpret_cast<double*>(base + o_sumsq);
     t.global = reinterpret_cast<double*>(base + o_global);
+    t.scalars = reinterpret_cast<StepScalars*>(base + o_scalars);
     t.coef64 = reinterpret_cast<double*>(base + o_coef64);
     t.norm = reinterpret_cast<float*>(base + o_norm);
     t.coef = reinterpret_cast<float*>(base + o_coef);
@@ -280,16 +283,17 @@ extern "C" int adagc_set_param_copies(adagc_ctx* ctx, void* const* params_bf16)
     return ADAGC_OK;
 }
 
-extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const* grads,
-                          void* const* exp_avg, void* const* exp_avg_sq, float* ema_norms,
-                          const adagc_hyper* hp, int64_t step, void* stream_v)
+namespace {
+
+// Shared front half of the two step entry points: argument checks, per-tensor records, upload of the
+// pointer table when it changed.  `capturing` forbids everything but kernel launches.
+int prepare_tables(adagc_ctx* ctx, void* const* params, const void* const* grads, void* const* exp_avg,
+                   void* const* exp_avg_sq, hipStream_t stream, bool capturing)
 {
-    if (!ctx || !params || !grads || !exp_avg || !ema_norms || !hp || step < 1) return ADAGC_ERR_INVALID_ARG;
     const bool adamw = ctx->cfg.optimizer == ADAGC_OPT_ADAMW;
     const bool bf16g = ctx->cfg.grad_dtype == ADAGC_GRAD_BF16;
     const bool copy = ctx->cfg.has_bf16_param_copy != 0;
     if (adamw && !exp_avg_sq) return ADAGC_ERR_INVALID_ARG;
-    if (!hyper_ok(*hp, ctx->cfg.optimizer)) return ADAGC_ERR_INVALID_ARG;
     if (copy && ctx->param_copies.size() != (size_t)ctx->n_tensors) return ADAGC_ERR_STATE;
 
     // Rebuild the per-tensor records from the caller's pointer arrays.
@@ -311,13 +315,10 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
         a.pad = 0;
     }
 
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return ADAGC_ERR_HIP;
-    hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const size_t args_bytes = (size_t)ctx->n_tensors * sizeof(TensorArgs);
-
     if (!ctx->args_uploaded ||
         std::memcmp(ctx->scratch_args.data(), ctx->cached_args.data(), args_bytes) != 0) {
+        if (capturing) return ADAGC_ERR_STATE;   // a recorded copy would re-read the staging buffer on every replay
         // The pinned staging buffer may still be the source of an earlier asynchronous upload.
         if (ctx->upload_pending && hipEventSynchronize(ctx->upload_done) != hipSuccess) return ADAGC_ERR_HIP;
         std::memcpy(ctx->staging, ctx->scratch_args.data(), args_bytes);
@@ -328,6 +329,24 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
         ctx->cached_args.swap(ctx->scratch_args);
         ctx->args_uploaded = true;
     }
+    return ADAGC_OK;
+}
+
+}  // namespace
+
+extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const* grads,
+                          void* const* exp_avg, void* const* exp_avg_sq, float* ema_norms,
+                          const adagc_hyper* hp, int64_t step, void* stream_v)
+{
+    if (!ctx || !params || !grads || !exp_avg || !ema_norms || !hp || step < 1) return ADAGC_ERR_INVALID_ARG;
+    if (!hyper_ok(*hp, ctx->cfg.optimizer)) return ADAGC_ERR_INVALID_ARG;
+    const bool bf16g = ctx->cfg.grad_dtype == ADAGC_GRAD_BF16;
+    const bool copy = ctx->cfg.has_bf16_param_copy != 0;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const int rc = prepare_tables(ctx, params, grads, exp_avg, exp_avg_sq, stream, false);
+    if (rc != ADAGC_OK) return rc;
 
     // Scalars of this step, in double from the caller's fp32 values.
     const double lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, wd = hp->weight_decay;
@@ -353,6 +372,7 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
     const bool warmup = (step - 1) < (int64_t)hp->t_start;   // steps 1..t_start
     r.warmup = warmup ? 1 : 0;
     const bool global_rule = warmup || hp->clip_mode != ADAGC_MODE_ADAGC;
+    ctx->device_scalars_used = false;
     const bool prof = ctx->prof_steps < ctx->prof_capacity;
     hipEvent_t* ev = prof ? &ctx->prof_events[(size_t)ctx->prof_steps * 4] : nullptr;
 
@@ -373,6 +393,57 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
     return ADAGC_OK;
 }
 
+extern "C" int adagc_step_graph(adagc_ctx* ctx, void* const* params, const void* const* grads,
+                                void* const* exp_avg, void* const* exp_avg_sq, float* ema_norms,
+                                const adagc_step_params* step_params, void* stream_v)
+{
+    if (!ctx || !params || !grads || !exp_avg || !ema_norms || !step_params) return ADAGC_ERR_INVALID_ARG;
+    const bool bf16g = ctx->cfg.grad_dtype == ADAGC_GRAD_BF16;
+    const bool copy = ctx->cfg.has_bf16_param_copy != 0;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess) return ADAGC_ERR_HIP;
+    const bool capturing = cap != hipStreamCaptureStatusNone;
+    if (capturing && ctx->prof_capacity > 0) return ADAGC_ERR_STATE;     // event records do not belong in a graph
+    const int rc = prepare_tables(ctx, params, grads, exp_avg, exp_avg_sq, stream, capturing);
+    if (rc != ADAGC_OK) return rc;
+
+    const bool prof = !capturing && ctx->prof_steps < ctx->prof_capacity;
+    hipEvent_t* ev = prof ? &ctx->prof_events[(size_t)ctx->prof_steps * 4] : nullptr;
+    ctx->device_scalars_used = true;
+    if (prof && hipEventRecord(ev[0], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (launch_sumsq_partials(ctx->tables, bf16g, ctx->nontemporal, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (prof && hipEventRecord(ev[1], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (launch_rules_from_device(ctx->tables, ema_norms, step_params, ctx->cfg.optimizer, stream) != hipSuccess)
+        return ADAGC_ERR_HIP;
+    if (prof && hipEventRecord(ev[2], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (launch_update(ctx->tables, UpdateArgs{}, ctx->cfg.optimizer, bf16g, copy, ctx->unroll, ctx->items_per_chunk,
+                      ctx->nontemporal, ctx->cfg.telemetry, ctx->grid_update, stream, true) != hipSuccess)
+        return ADAGC_ERR_HIP;
+    if (prof) {
+        if (hipEventRecord(ev[3], stream) != hipSuccess) return ADAGC_ERR_HIP;
+        ctx->prof_steps++;
+    }
+    return ADAGC_OK;
+}
+
+namespace {
+
+// Wait for the copies; after adagc_step_graph also fetch the status word the device wrote for that step.
+int finish_readback(adagc_ctx* ctx, hipStream_t stream)
+{
+    int32_t status = 0;
+    if (ctx->device_scalars_used &&
+        hipMemcpyAsync(&status, &ctx->tables.scalars->status, sizeof(status), hipMemcpyDeviceToHost, stream) != hipSuccess)
+        return ADAGC_ERR_HIP;
+    if (hipStreamSynchronize(stream) != hipSuccess) return ADAGC_ERR_HIP;
+    return status == 0 ? ADAGC_OK : ADAGC_ERR_INVALID_ARG;
+}
+
+}  // namespace
+
 extern "C" int adagc_get_norms(adagc_ctx* ctx, float* host_norms, float* host_coefs, uint8_t* host_clipped,
                                int64_t n_tensors, void* stream_v)
 {
@@ -388,7 +459,7 @@ extern "C" int adagc_get_norms(adagc_ctx* ctx, float* host_norms, float* host_co
         return ADAGC_ERR_HIP;
     if (host_clipped && hipMemcpyAsync(host_clipped, t.flag, n, hipMemcpyDeviceToHost, stream) != hipSuccess)
         return ADAGC_ERR_HIP;
-    return hipStreamSynchronize(stream) == hipSuccess ? ADAGC_OK : ADAGC_ERR_HIP;
+    return finish_readback(ctx, stream);
 }
 
 extern "C" int adagc_get_state_norms(adagc_ctx* ctx, float* host_m_norms, float* host_v_norms,
@@ -405,7 +476,7 @@ extern "C" int adagc_get_state_norms(adagc_ctx* ctx, float* host_m_norms, float*
         if (out[q] && hipMemcpyAsync(out[q], ctx->tables.tele_norm + q * n, n * sizeof(float),
                                      hipMemcpyDeviceToHost, stream) != hipSuccess)
             return ADAGC_ERR_HIP;
-    return hipStreamSynchronize(stream) == hipSuccess ? ADAGC_OK : ADAGC_ERR_HIP;
+    return finish_readback(ctx, stream);
 }
 
 extern "C" int adagc_get_segment_table(adagc_ctx* ctx, int64_t* chunk_begin, uint32_t* chunk_tensor,

@@ -234,14 +234,10 @@ __device__ __forceinline__ double tensor_slot_sum(const DeviceTables& t, const d
     return total;
 }
 
-// AdaGC branch of Alg. 1 / Eq. 3, in double, with separately rounded operations.
-__global__ __launch_bounds__(kBlock) void finalize_adagc_kernel(DeviceTables t, float* ema, RuleArgs r)
+// AdaGC branch of Alg. 1 / Eq. 3 for tensor i with sum of squares s, in double, with separately rounded
+// operations.  One lane.
+__device__ __forceinline__ void adagc_rule(const DeviceTables& t, float* ema, const RuleArgs& r, uint32_t i, double s)
 {
-    __shared__ double wave_sums[kWavesPerBlock];
-    const uint32_t i = blockIdx.x;
-    const double s = tensor_slot_sum(t, t.partials, i, wave_sums);
-    if (threadIdx.x != 0) return;
-
     const double norm = sqrt(s);
     const double gamma_prev = (double)ema[i];
     const double threshold = __dmul_rn(r.lambda_rel, gamma_prev);
@@ -258,6 +254,14 @@ __global__ __launch_bounds__(kBlock) void finalize_adagc_kernel(DeviceTables t, 
     ema[i] = (float)gamma_new;
 }
 
+__global__ __launch_bounds__(kBlock) void finalize_adagc_kernel(DeviceTables t, float* ema, RuleArgs r)
+{
+    __shared__ double wave_sums[kWavesPerBlock];
+    const uint32_t i = blockIdx.x;
+    const double s = tensor_slot_sum(t, t.partials, i, wave_sums);
+    if (threadIdx.x == 0) adagc_rule(t, ema, r, i, s);
+}
+
 // Global stage 1: per-tensor sum of squares only.
 __global__ __launch_bounds__(kBlock) void tensor_sumsq_kernel(DeviceTables t)
 {
@@ -271,9 +275,8 @@ __global__ __launch_bounds__(kBlock) void tensor_sumsq_kernel(DeviceTables t)
 // whole model.  Warm-up steps and the GlobalGC mode use Eq. 2; the Global AdaGC mode applies Eq. 3
 // (and, during warm-up, the running minimum of Alg. 1) to the model's norm with the single gamma
 // kept in ema[0].
-__global__ __launch_bounds__(kBlock) void global_rule_kernel(DeviceTables t, float* ema, RuleArgs r)
+__device__ __forceinline__ void global_rule(const DeviceTables& t, float* ema, const RuleArgs& r, double* wave_sums)
 {
-    __shared__ double wave_sums[kWavesPerBlock];
     const int tid = threadIdx.x;
     double acc = 0.0;
     for (uint32_t i = tid; i < t.n_tensors; i += kBlock) acc += t.sumsq[i];
@@ -313,13 +316,17 @@ __global__ __launch_bounds__(kBlock) void global_rule_kernel(DeviceTables t, flo
     t.global[2] = clipped ? 1.0 : 0.0;
 }
 
-// Global stage 3: every tensor takes the model's coefficient.  In the AdaGC mode (warm-up branch
-// of Alg. 1) gamma_i = min{gamma_i, h*n_i}, or h*n_i on the first step; the global modes keep no
-// per-tensor state.
-__global__ __launch_bounds__(kBlock) void finalize_global_kernel(DeviceTables t, float* ema, RuleArgs r)
+__global__ __launch_bounds__(kBlock) void global_rule_kernel(DeviceTables t, float* ema, RuleArgs r)
 {
-    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
-    if (i >= t.n_tensors) return;
+    __shared__ double wave_sums[kWavesPerBlock];
+    global_rule(t, ema, r, wave_sums);
+}
+
+// Global stage 3 for tensor i: it takes the model's coefficient.  In the AdaGC mode (warm-up branch of
+// Alg. 1) gamma_i = min{gamma_i, h*n_i}, or h*n_i on the first step; the global modes keep no per-tensor
+// state.
+__device__ __forceinline__ void take_global_coefficient(const DeviceTables& t, float* ema, const RuleArgs& r, uint32_t i)
+{
     const double h = t.global[1];
     const double norm = sqrt(t.sumsq[i]);
     t.norm[i] = (float)norm;
@@ -333,6 +340,69 @@ __global__ __launch_bounds__(kBlock) void finalize_global_kernel(DeviceTables t,
         if (!r.first_step) gamma_new = clipped_norm < gamma_prev ? clipped_norm : gamma_prev;
         ema[i] = (float)gamma_new;
     }
+}
+
+__global__ __launch_bounds__(kBlock) void finalize_global_kernel(DeviceTables t, float* ema, RuleArgs r)
+{
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i < t.n_tensors) take_global_coefficient(t, ema, r, i);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same rules with the step's scalars taken from device memory (adagc_step_graph): the step number
+// and the hyper-parameters are read when the kernels run, so a recorded launch sequence stays valid
+// for other steps.  Which branch of Alg. 1 applies is therefore decided on the device as well.
+
+// One lane: validate the caller's step parameters and derive the scalars of both stages from them.
+__global__ void prepare_step_kernel(DeviceTables t, const adagc_step_params* params, int optimizer)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const adagc_hyper hp = params->hp;
+    const int64_t step = params->step;
+    auto unit = [](float b) { return b >= 0.0f && b < 1.0f; };   // false for NaN
+    auto finite = [](float x) { return fabsf(x) <= 3.402823466e+38f; };
+    bool ok = step >= 1 && finite(hp.lr) && finite(hp.weight_decay) && unit(hp.beta1) && unit(hp.beta2) &&
+              unit(hp.ema_beta) && hp.lambda_rel >= 0.0f && hp.lambda_abs > 0.0f && hp.t_start >= 0 &&
+              hp.clip_mode >= ADAGC_MODE_ADAGC && hp.clip_mode <= ADAGC_MODE_GLOBAL_ADAGC;
+    if (optimizer == ADAGC_OPT_ADAMW) ok = ok && hp.eps >= 0.0f && finite(hp.eps);
+    StepScalars sc;
+    const double lr = hp.lr, b1 = hp.beta1, b2 = hp.beta2, wd = hp.weight_decay, tt = (double)step;
+    sc.r.lambda_rel = (double)hp.lambda_rel;
+    sc.r.ema_beta = (double)hp.ema_beta;
+    sc.r.lambda_abs = (double)hp.lambda_abs;
+    sc.r.first_step = (step == 1) ? 1 : 0;
+    sc.r.warmup = ((step - 1) < (int64_t)hp.t_start) ? 1 : 0;
+    sc.r.mode = hp.clip_mode;
+    sc.u.beta1 = b1;
+    sc.u.one_minus_beta1 = 1.0 - b1;
+    sc.u.beta2 = b2;
+    sc.u.one_minus_beta2 = 1.0 - b2;
+    sc.u.inv_bias2 = 1.0 / (1.0 - pow(b2, tt));
+    sc.u.step_size = lr / (1.0 - pow(b1, tt));
+    sc.u.lr_wd = lr * wd;
+    sc.u.eps = (double)hp.eps;
+    sc.u.lr = lr;
+    sc.u.weight_decay = wd;
+    sc.status = ok ? 0 : 1;
+    sc.pad = 0;
+    *t.scalars = sc;
+}
+
+__global__ __launch_bounds__(kBlock) void global_rule_device_kernel(DeviceTables t, float* ema)
+{
+    __shared__ double wave_sums[kWavesPerBlock];
+    const RuleArgs r = t.scalars->r;
+    if (t.scalars->status != 0 || !(r.warmup || r.mode != ADAGC_MODE_ADAGC)) return;   // uniform
+    global_rule(t, ema, r, wave_sums);
+}
+
+__global__ __launch_bounds__(kBlock) void finalize_device_kernel(DeviceTables t, float* ema)
+{
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= t.n_tensors || t.scalars->status != 0) return;
+    const RuleArgs r = t.scalars->r;
+    if (r.warmup || r.mode != ADAGC_MODE_ADAGC) take_global_coefficient(t, ema, r, i);
+    else adagc_rule(t, ema, r, i, t.sumsq[i]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -424,9 +494,14 @@ __device__ __forceinline__ void tele_vec(double (&acc)[3], f32x4 p_old, f32x4 p_
 // its parts) and the items of one chunk all go to the same XCD:
 //   item T  ->  position 8*(T / (8*I)) + T % 8,  item (T / 8) % I of that chunk      (I = items_per_chunk).
 template <int OPT, bool BF16G, bool COPY, int U, bool NT, bool TELE>
-__global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateArgs a, uint32_t items_per_chunk)
+__global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateArgs a, uint32_t items_per_chunk,
+                                                        const StepScalars* device_scalars)
 {
     static_assert(kVecPerLane % U == 0, "a chunk is a whole number of tiles");
+    if (device_scalars) {                      // adagc_step_graph: this step's scalars live in device memory
+        if (device_scalars->status != 0) return;
+        a = device_scalars->u;
+    }
     constexpr bool NTL = NT, NTS = NT;    // non-temporal loads and stores
     constexpr bool kHasV = (OPT == ADAGC_OPT_ADAMW);
     constexpr int kTiles = kVecPerLane / U;
@@ -564,7 +639,7 @@ __global__ __launch_bounds__(kBlock) void finalize_telemetry_kernel(DeviceTables
     }
 }
 
-using UpdateFn = void (*)(DeviceTables, UpdateArgs, uint32_t);
+using UpdateFn = void (*)(DeviceTables, UpdateArgs, uint32_t, const StepScalars*);
 using SumsqFn = void (*)(DeviceTables);
 
 template <int OPT, bool BF16G, bool COPY, int U>
@@ -630,12 +705,29 @@ hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleA
     return hipGetLastError();
 }
 
+hipError_t launch_rules_from_device(const DeviceTables& t, float* ema, const adagc_step_params* params,
+                                    int optimizer, hipStream_t stream)
+{
+    prepare_step_kernel<<<dim3(1), dim3(64), 0, stream>>>(t, params, optimizer);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    tensor_sumsq_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    global_rule_device_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(t, ema);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const uint32_t blocks = (t.n_tensors + kBlock - 1) / kBlock;
+    finalize_device_kernel<<<dim3(blocks), dim3(kBlock), 0, stream>>>(t, ema);
+    return hipGetLastError();
+}
+
 hipError_t launch_update(const DeviceTables& t, const UpdateArgs& a, int optimizer, int grad_bf16,
                          int with_copy, int unroll, int items_per_chunk, int nt, int tele, int grid,
-                         hipStream_t stream)
+                         hipStream_t stream, bool device_scalars)
 {
     select_update(optimizer, grad_bf16, with_copy, unroll, nt, tele)<<<dim3(grid), dim3(kBlock), 0, stream>>>(
-        t, a, (uint32_t)items_per_chunk);
+        t, a, (uint32_t)items_per_chunk, device_scalars ? t.scalars : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !tele) return e;
     finalize_telemetry_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t, (uint32_t)items_per_chunk);

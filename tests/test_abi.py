@@ -29,6 +29,7 @@ def test_header_symbols_are_exported():
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.adagc_tensor_desc) == 16
     assert ctypes.sizeof(B.adagc_config) == 40
+    assert ctypes.sizeof(B.adagc_step_params) == 48
     assert ctypes.sizeof(B.adagc_hyper) == 40
 
 
@@ -95,6 +96,7 @@ def test_null_context_is_rejected_everywhere():
     L = B.lib()
     hp = B.make_hyper()
     assert L.adagc_step(None, None, None, None, None, None, ctypes.byref(hp), 1, None) == B.ADAGC_ERR_INVALID_ARG
+    assert L.adagc_step_graph(None, None, None, None, None, None, None, None) == B.ADAGC_ERR_INVALID_ARG
     assert L.adagc_get_norms(None, None, None, None, 1, None) == B.ADAGC_ERR_INVALID_ARG
     assert L.adagc_get_state_norms(None, None, None, None, 1, None) == B.ADAGC_ERR_INVALID_ARG
     assert L.adagc_set_param_copies(None, None) == B.ADAGC_ERR_INVALID_ARG

@@ -205,7 +205,7 @@ int adagc_step(adagc_ctx* ctx, void* const* params, const void* const* grads,
  * A launch sequence recorded once (stream capture) can therefore be replayed for every later step;
  * between replays the caller updates *step_params (a copy or kernel of its own, ordered before the
  * replay).  Which branch of Alg. 1 applies (warm-up or not, clip_mode) is decided on the device, so
- * the recorded sequence is the same for all of them: two more small kernels than adagc_step.
+ * the recorded sequence is the same for all of them (six kernels where adagc_step launches three to five).
  *   step_params  DEVICE adagc_step_params, read by the GPU during the step
  *   other arguments as for adagc_step
  * The parameters cannot be validated on the host: a step whose parameters adagc_step would reject

@@ -6,7 +6,10 @@
 //                           one coefficient for the whole model: warm-up branch of Alg. 1
 //                           (GlobalGC + running minimum), GlobalGC on every step (Eq. 2),
 //                           Global AdaGC (Eq. 3 on the model's norm; Sec. 5.4 ablation)
-//   update_kernel           per chunk:   clipped gradient into AdamW / Lion        (Alg. 1)
+//   update_kernel           per quarter chunk: clipped gradient into AdamW / Lion  (Alg. 1)
+//   prepare_step_kernel / global_rule_device_kernel / finalize_device_kernel
+//                           the same rules with the step's scalars read from device memory, for a
+//                           launch sequence that is recorded once and replayed for later steps
 //
 // Nothing here is a dense contraction, so there is no MFMA: the streaming kernels
 // are bound by HBM and are built around 128-bit coalesced accesses with many
@@ -144,8 +147,8 @@ __device__ __forceinline__ ChunkView chunk_view(const DeviceTables& t, uint32_t 
 }
 
 // ---------------------------------------------------------------------------------------------
-// K1: one fp64 partial sum of squares per chunk.  Persistent grid: workgroup b takes chunks
-// b, b+grid, b+2*grid, ... so that neighbouring workgroups stream neighbouring memory.
+// K1: one fp64 partial sum of squares per chunk.  Workgroup b takes positions b, b+grid, b+2*grid, ...
+// of the visiting order (by default the grid has one workgroup per chunk).
 
 __device__ __forceinline__ void acc4(double (&acc)[4], f32x4 g)
 {
@@ -512,7 +515,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
 
     const uint32_t group = 8u * items_per_chunk;
     const int tiles_per_item = kTiles / (int)items_per_chunk;
-    const uint64_t n_items = (uint64_t)((t.n_chunks + 7u) & ~7u) * items_per_chunk;
+    const uint64_t n_items = (((uint64_t)t.n_chunks + 7u) & ~(uint64_t)7u) * items_per_chunk;
     for (uint64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
         const uint32_t r = (uint32_t)(item % group);
         const uint32_t k = (uint32_t)(item / group) * 8u + (r & 7u);

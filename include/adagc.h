@@ -7,7 +7,7 @@
  * Alg. 1 in the appendix "Pseudocode of AdamW with AdaGC").  One call of
  * adagc_step performs, for a whole ragged list of parameter tensors:
  *
- *   1. n_i = ||g_i||_2 for every tensor i                      (Sec. 4.1, Eq. 3)
+ *   1. n_i = ||g_i||_2 for every tensor i                      (Sec. 4.1 notation; Eq. 3)
  *   2. warm-up steps (t <= T_start): one global coefficient
  *        h = min{lambda_abs / ||g||, 1}                         (Eq. 2, Alg. 1)
  *        gamma_i = min{gamma_i, h*n_i}  (gamma_i = h*n_i on step 1)
@@ -59,7 +59,7 @@ extern "C" {
 #define ADAGC_MODE_ADAGC         0  /* Alg. 1: GlobalGC warm-up for t_start steps, then per-tensor Eq. 3 */
 #define ADAGC_MODE_GLOBALGC      1  /* Eq. 2 on every step (the paper's baseline); keeps no state */
 #define ADAGC_MODE_GLOBAL_ADAGC  2  /* one adaptive threshold for the whole model (ablation "adaptive but
-                                       non-local", Sec. 5.4): Eq. 3 and the warm-up branch applied to the
+                                       non-local", "Ablation Study", Sec. 5.6): Eq. 3 and the warm-up branch applied to the
                                        model's norm; its single gamma lives in ema_norms[0] */
 
 typedef struct adagc_ctx adagc_ctx; /* opaque; created by adagc_create, freed by adagc_destroy */
@@ -99,7 +99,8 @@ typedef struct {
 
 /* Hyper-parameters of Alg. 1, passed by the caller on every step (the learning
  * rate schedule {eta_t} lives with the caller).  Defaults in the paper:
- * lambda_rel 1.04, ema_beta 0.99, t_start 100, lambda_abs 1.0 (Sec. 4.2, 5.1). */
+ * lambda_rel 1.04 and ema_beta 0.99 ("Critical Hyperparameter Selection", Sec. 5.2), t_start 100
+ * (Sec. 4.2), lambda_abs 1.0 (appendix "Clipping Hyper-Parameters"). */
 typedef struct {
     float   lr;            /* eta_t */
     float   beta1, beta2;  /* AdamW: moment decay rates.  Lion: interpolation / momentum rates */

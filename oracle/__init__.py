@@ -24,7 +24,7 @@ GRAD_F32 = 0
 GRAD_BF16 = 1
 MODE_ADAGC = 0          # Alg. 1
 MODE_GLOBALGC = 1       # Eq. 2 on every step
-MODE_GLOBAL_ADAGC = 2   # one adaptive threshold for the whole model (ablation of Sec. 5.4)
+MODE_GLOBAL_ADAGC = 2   # one adaptive threshold for the whole model ("Ablation Study", Sec. 5.6)
 
 
 class _OptHyper(ctypes.Structure):
@@ -56,8 +56,8 @@ class Hyper:
     beta2: float = 0.95
     eps: float = 1e-8
     weight_decay: float = 0.1
-    lambda_rel: float = 1.04      # Sec. 5.1 default
-    ema_beta: float = 0.99        # Sec. 5.1 default
+    lambda_rel: float = 1.04      # default fixed in "Critical Hyperparameter Selection", Sec. 5.2
+    ema_beta: float = 0.99        # same subsection
     lambda_abs: float = float("inf")
     t_start: int = 1
     optimizer: int = ADAMW

@@ -7,12 +7,12 @@
  * speed: one thread, scalar loops, every floating-point scalar in double.
  *
  * What follows the paper:
- *   - l2 norm of one gradient tensor ............ Sec. 4.1 (notation), Eq. 3
+ *   - l2 norm of one gradient tensor ............ Sec. 4.1 "Preliminaries" (notation); Eq. 3 (Sec. 4.2)
  *   - AdaGC coefficient h_{t,i} and EMA gamma .... Eq. 3, Alg. 1 (AdaGC branch)
  *   - warm-up: GlobalGC + running minimum ........ Eq. 2, Alg. 1 (warm-up branch)
  *   - GlobalGC on every step (the baseline) ...... Eq. 2
  *   - "Global AdaGC" (one adaptive threshold for the whole model; ablation
- *     "Adaptivity Efficacy and Locality Granularity", Sec. 5.4): Eq. 3 and the
+ *     "Adaptivity Efficacy and Locality Granularity" of the "Ablation Study", Sec. 5.6): Eq. 3 and the
  *     warm-up branch applied to the global norm with a single gamma
  *   - AdamW moments, bias correction, update ..... Alg. 1 (last four statements)
  * What the paper does not print and is taken from its citation:
@@ -64,7 +64,7 @@ uint16_t oracle_float_to_bf16_rne(float f)
     return (uint16_t)kept;
 }
 
-/* ---- Sec. 4.1 / Eq. 3: l2 norm of one tensor ------------------------------ */
+/* ---- l2 norm of one tensor (notation of Sec. 4.1; used by Eq. 3, Sec. 4.2) -- */
 
 /* grad_dtype: 0 = float32, 1 = bf16.  Sum of squares in index order. */
 double oracle_sum_squares(const void *g, int64_t numel, int grad_dtype)

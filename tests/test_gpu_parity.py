@@ -539,7 +539,7 @@ def test_list_of_one_tensor_of_one_element():
 
 @pytest.mark.parametrize("quiet_warmup", [False, True])
 def test_paper_default_schedule_warmup_100_then_adagc(quiet_warmup):
-    """Alg. 1 with the defaults of Sec. 4.2 / 5.1 (lambda_rel 1.04, beta 0.99, T_start 100, lambda_abs 1.0) run
+    """Alg. 1 with the defaults of Sec. 4.2 / 5.2 (lambda_rel 1.04, beta 0.99, T_start 100, lambda_abs 1.0) run
     free for 150 steps on the tiny transformer list: 100 GlobalGC warm-up steps with the running minimum, then
     per-tensor AdaGC with spikes.  The oracle is never re-seeded from the device.
     quiet_warmup=False: the model's norm is far above lambda_abs and one warm-up step spikes, so every step of the

@@ -542,7 +542,7 @@ def test_enumerate_chunks_covers_every_element_once():
             assert all(c[0] == i for c in own) and len(own) == -(-numels[i] // chunk)
 
 
-# ------------------------------------------------------------------ global-statistic modes (Eq. 2; Sec. 5.4 ablation)
+# ------------------------------------------------------------------ global-statistic modes (Eq. 2; ablation study, Sec. 5.6)
 
 def test_globalgc_mode_hand_worked_and_equals_endless_warmup():
     """Mode GlobalGC applies Eq. 2 on every step and keeps no per-tensor state.  Tensors [3,4] and

@@ -75,40 +75,76 @@ class Hyper:
                           int(self.grad_dtype), int(self.clip_mode), 0)
 
 
+def _declare(L):
+    vp, i64, dbl, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double, ctypes.c_int
+    L.oracle_num_threads.restype = i32
+    L.oracle_num_threads.argtypes = []
+    L.oracle_bf16_to_float.restype = ctypes.c_float
+    L.oracle_bf16_to_float.argtypes = [ctypes.c_uint16]
+    L.oracle_float_to_bf16_rne.restype = ctypes.c_uint16
+    L.oracle_float_to_bf16_rne.argtypes = [ctypes.c_float]
+    L.oracle_sum_squares.restype = dbl
+    L.oracle_sum_squares.argtypes = [vp, i64, i32]
+    L.oracle_l2_norm.restype = dbl
+    L.oracle_l2_norm.argtypes = [vp, i64, i32]
+    L.oracle_adagc_rule.restype = None
+    L.oracle_adagc_rule.argtypes = [dbl, dbl, dbl, dbl, ctypes.POINTER(dbl),
+                                    ctypes.POINTER(dbl), ctypes.POINTER(i32)]
+    L.oracle_globalgc_coef.restype = dbl
+    L.oracle_globalgc_coef.argtypes = [dbl, dbl]
+    L.oracle_warmup_gamma.restype = dbl
+    L.oracle_warmup_gamma.argtypes = [dbl, dbl, i32]
+    L.oracle_adamw_update.restype = None
+    L.oracle_adamw_update.argtypes = [vp, vp, vp, vp, i32, i64, dbl,
+                                      ctypes.POINTER(_OptHyper), i64, vp]
+    L.oracle_lion_update.restype = None
+    L.oracle_lion_update.argtypes = [vp, vp, vp, i32, i64, dbl, ctypes.POINTER(_OptHyper), vp]
+    L.oracle_state_norms.restype = None
+    L.oracle_state_norms.argtypes = [vp, vp, vp, vp, i64, ctypes.POINTER(dbl), ctypes.POINTER(dbl),
+                                     ctypes.POINTER(dbl)]
+    L.oracle_adagc_step.restype = i32
+    L.oracle_adagc_step.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp,
+                                    ctypes.POINTER(_StepHyper), i64, vp, vp, vp]
+    return L
+
+
+_lib_all_cores = None
+_use_all_cores = False
+
+
 def lib():
-    global _lib
+    """The oracle library in use: the one-thread build (the definition) unless all_cores() switched."""
+    global _lib, _lib_all_cores
+    if _use_all_cores:
+        if _lib_all_cores is None:
+            _lib_all_cores = _declare(ctypes.CDLL(_build.build(all_cores=True)))
+        return _lib_all_cores
     if _lib is None:
         # ADAGC_ORACLE_LIB: a test may point at a deliberately broken build to show that the pins notice
-        L = ctypes.CDLL(os.environ.get("ADAGC_ORACLE_LIB") or _build.build())
-        vp, i64, dbl, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double, ctypes.c_int
-        L.oracle_bf16_to_float.restype = ctypes.c_float
-        L.oracle_bf16_to_float.argtypes = [ctypes.c_uint16]
-        L.oracle_float_to_bf16_rne.restype = ctypes.c_uint16
-        L.oracle_float_to_bf16_rne.argtypes = [ctypes.c_float]
-        L.oracle_sum_squares.restype = dbl
-        L.oracle_sum_squares.argtypes = [vp, i64, i32]
-        L.oracle_l2_norm.restype = dbl
-        L.oracle_l2_norm.argtypes = [vp, i64, i32]
-        L.oracle_adagc_rule.restype = None
-        L.oracle_adagc_rule.argtypes = [dbl, dbl, dbl, dbl, ctypes.POINTER(dbl),
-                                        ctypes.POINTER(dbl), ctypes.POINTER(i32)]
-        L.oracle_globalgc_coef.restype = dbl
-        L.oracle_globalgc_coef.argtypes = [dbl, dbl]
-        L.oracle_warmup_gamma.restype = dbl
-        L.oracle_warmup_gamma.argtypes = [dbl, dbl, i32]
-        L.oracle_adamw_update.restype = None
-        L.oracle_adamw_update.argtypes = [vp, vp, vp, vp, i32, i64, dbl,
-                                          ctypes.POINTER(_OptHyper), i64, vp]
-        L.oracle_lion_update.restype = None
-        L.oracle_lion_update.argtypes = [vp, vp, vp, i32, i64, dbl, ctypes.POINTER(_OptHyper), vp]
-        L.oracle_state_norms.restype = None
-        L.oracle_state_norms.argtypes = [vp, vp, vp, vp, i64, ctypes.POINTER(dbl), ctypes.POINTER(dbl),
-                                         ctypes.POINTER(dbl)]
-        L.oracle_adagc_step.restype = i32
-        L.oracle_adagc_step.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp,
-                                        ctypes.POINTER(_StepHyper), i64, vp, vp, vp]
-        _lib = L
+        _lib = _declare(ctypes.CDLL(os.environ.get("ADAGC_ORACLE_LIB") or _build.build()))
     return _lib
+
+
+class all_cores:
+    """``with oracle.all_cores():`` runs the enclosed calls on the all-cores build of the same source
+    (bit-identical theta / m / v / copies; sums of squares in another rounding order)."""
+
+    def __enter__(self):
+        global _use_all_cores
+        self._saved = _use_all_cores
+        _use_all_cores = True
+        lib()
+        return self
+
+    def __exit__(self, *exc):
+        global _use_all_cores
+        _use_all_cores = self._saved
+        return False
+
+
+def num_threads():
+    """Threads the per-element loops of the library in use run on."""
+    return int(lib().oracle_num_threads())
 
 
 def _grad_dtype(g):

@@ -178,7 +178,12 @@ int adagc_set_param_copies(adagc_ctx* ctx, void* const* params_bf16);
 
 /*
  * One optimizer step (one pass of the loop body of Alg. 1) over the whole list,
- * enqueued on `stream`; returns without waiting for the GPU and allocates nothing.
+ * enqueued on `stream`; allocates nothing and returns without waiting for the GPU.
+ * (One bounded exception: the device pointers of the four arrays are mirrored on the
+ * GPU and re-uploaded, through a ring of four pinned staging tables, only when they
+ * differ from the previous call's.  A caller whose pointers change on every call and
+ * who runs more than four such calls ahead of the GPU waits until the oldest of those
+ * uploads has left its staging table.)
  *   params      HOST array of n_tensors DEVICE pointers, fp32, updated in place      (theta)
  *   grads       HOST array of n_tensors DEVICE pointers, fp32 or bf16 per cfg, read only   (g_t)
  *   exp_avg     HOST array of n_tensors DEVICE pointers, fp32, updated in place      (m)

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cmath>
+
 #include "adagc.h"
 
 namespace adagc {
@@ -77,7 +79,7 @@ struct StepScalars {
 
 struct DeviceTables {
     const ChunkRef*   chunks;     // canonical order: tensor by tensor; slot c of `partials` belongs to chunk c
-    const uint32_t*   schedule;   // order in which the streaming kernels visit the chunks
+    const uint32_t*   schedule;   // order in which the streaming kernels visit the chunks (null: list order)
     const TensorArgs* targs;
     double*           partials;   // one per chunk
     double*           sumsq;      // one per tensor
@@ -92,6 +94,43 @@ struct DeviceTables {
     uint32_t          n_chunks;
     uint32_t          n_tensors;
 };
+
+// What every step entry point accepts as hyper-parameters.
+inline bool hyper_ok(const adagc_hyper& h, int optimizer)
+{
+    auto unit = [](float b) { return b >= 0.0f && b < 1.0f; };   // false for NaN
+    if (!std::isfinite(h.lr) || !std::isfinite(h.weight_decay)) return false;
+    if (!unit(h.beta1) || !unit(h.beta2) || !unit(h.ema_beta)) return false;
+    if (optimizer == ADAGC_OPT_ADAMW && !(h.eps >= 0.0f && std::isfinite(h.eps))) return false;
+    if (!(h.lambda_rel >= 0.0f)) return false;    // +inf allowed, NaN not
+    if (!(h.lambda_abs > 0.0f)) return false;     // +inf allowed, NaN not
+    if (h.t_start < 0) return false;
+    if (h.clip_mode < ADAGC_MODE_ADAGC || h.clip_mode > ADAGC_MODE_GLOBAL_ADAGC) return false;
+    return true;
+}
+
+// Scalars of one step, in double from the caller's fp32 values (host side).
+inline void host_step_scalars(const adagc_hyper& hp, int64_t step, RuleArgs& r, UpdateArgs& u)
+{
+    const double lr = hp.lr, b1 = hp.beta1, b2 = hp.beta2, wd = hp.weight_decay;
+    const double t = (double)step;
+    r.lambda_rel = (double)hp.lambda_rel;
+    r.ema_beta = (double)hp.ema_beta;
+    r.lambda_abs = (double)hp.lambda_abs;
+    r.first_step = (step == 1) ? 1 : 0;
+    r.warmup = ((step - 1) < (int64_t)hp.t_start) ? 1 : 0;   // steps 1..t_start
+    r.mode = hp.clip_mode;
+    u.beta1 = b1;
+    u.one_minus_beta1 = 1.0 - b1;
+    u.beta2 = b2;
+    u.one_minus_beta2 = 1.0 - b2;
+    u.inv_bias2 = 1.0 / (1.0 - std::pow(b2, t));
+    u.step_size = lr / (1.0 - std::pow(b1, t));
+    u.lr_wd = lr * wd;
+    u.eps = (double)hp.eps;
+    u.lr = lr;
+    u.weight_decay = wd;
+}
 
 // Launchers (kernels.hip).  Each only enqueues on `stream`.
 hipError_t launch_sumsq_partials(const DeviceTables& t, int grad_bf16, int nt, int grid, hipStream_t stream);

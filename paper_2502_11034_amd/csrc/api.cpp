@@ -31,9 +31,14 @@ struct adagc_ctx {
     void*        slab = nullptr;              // single device allocation, carved below
     DeviceTables tables{};
     TensorArgs*  d_targs = nullptr;
-    TensorArgs*  staging = nullptr;           // pinned host mirror for the async upload
-    hipEvent_t   upload_done = nullptr;
-    bool         upload_pending = false;
+    // Pinned host mirrors for the asynchronous upload of the pointer table: a ring, so that a caller
+    // who alternates between pointer sets (two gradient buffers, say) does not have to wait for the
+    // previous upload before the next one can be staged.
+    static constexpr int kStagingSlots = 4;
+    TensorArgs*  staging = nullptr;           // kStagingSlots consecutive tables
+    hipEvent_t   upload_done[kStagingSlots] = {nullptr, nullptr, nullptr, nullptr};
+    bool         upload_pending[kStagingSlots] = {false, false, false, false};
+    uint64_t     uploads = 0;                 // tables uploaded so far; slot = uploads % kStagingSlots
     bool         device_scalars_used = false;   // adagc_step_graph was called: its status word is meaningful
 
     std::vector<hipEvent_t> prof_events;      // 4 per step while profiling
@@ -65,24 +70,12 @@ constexpr int64_t kMaxGridBlocks = (int64_t)(0xFFFFFFFFu / (uint32_t)kBlock);
 
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-bool hyper_ok(const adagc_hyper& h, int optimizer)
-{
-    auto unit = [](float b) { return b >= 0.0f && b < 1.0f; };   // false for NaN
-    if (!std::isfinite(h.lr) || !std::isfinite(h.weight_decay)) return false;
-    if (!unit(h.beta1) || !unit(h.beta2) || !unit(h.ema_beta)) return false;
-    if (optimizer == ADAGC_OPT_ADAMW && !(h.eps >= 0.0f && std::isfinite(h.eps))) return false;
-    if (!(h.lambda_rel >= 0.0f)) return false;    // +inf allowed, NaN not
-    if (!(h.lambda_abs > 0.0f)) return false;     // +inf allowed, NaN not
-    if (h.t_start < 0) return false;
-    if (h.clip_mode < ADAGC_MODE_ADAGC || h.clip_mode > ADAGC_MODE_GLOBAL_ADAGC) return false;
-    return true;
-}
-
 void free_ctx(adagc_ctx* c)
 {
     if (!c) return;
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
-    if (c->upload_done) (void)hipEventDestroy(c->upload_done);
+    for (hipEvent_t e : c->upload_done)
+        if (e) (void)hipEventDestroy(e);
     if (c->staging) (void)hipHostFree(c->staging);
     if (c->slab) (void)hipFree(c->slab);
     delete c;
@@ -232,12 +225,16 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
             return ADAGC_ERR_HIP;
         }
     }
-    if (hipHostMalloc(reinterpret_cast<void**>(&c->staging), nt * sizeof(TensorArgs), hipHostMallocDefault) !=
-            hipSuccess ||
-        hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming) != hipSuccess) {
+    if (hipHostMalloc(reinterpret_cast<void**>(&c->staging), adagc_ctx::kStagingSlots * nt * sizeof(TensorArgs),
+                      hipHostMallocDefault) != hipSuccess) {
         free_ctx(c);
         return ADAGC_ERR_HIP;
     }
+    for (hipEvent_t& ev : c->upload_done)
+        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+            free_ctx(c);
+            return ADAGC_ERR_HIP;
+        }
 
     c->d_targs = reinterpret_cast<TensorArgs*>(base + o_targs);
     DeviceTables& t = c->tables;
@@ -319,13 +316,17 @@ int prepare_tables(adagc_ctx* ctx, void* const* params, const void* const* grads
     if (!ctx->args_uploaded ||
         std::memcmp(ctx->scratch_args.data(), ctx->cached_args.data(), args_bytes) != 0) {
         if (capturing) return ADAGC_ERR_STATE;   // a recorded copy would re-read the staging buffer on every replay
-        // The pinned staging buffer may still be the source of an earlier asynchronous upload.
-        if (ctx->upload_pending && hipEventSynchronize(ctx->upload_done) != hipSuccess) return ADAGC_ERR_HIP;
-        std::memcpy(ctx->staging, ctx->scratch_args.data(), args_bytes);
-        if (hipMemcpyAsync(ctx->d_targs, ctx->staging, args_bytes, hipMemcpyHostToDevice, stream) != hipSuccess ||
-            hipEventRecord(ctx->upload_done, stream) != hipSuccess)
+        // Next slot of the staging ring.  It may still be the source of the upload made kStagingSlots
+        // table changes ago; only then (the host that far ahead of the GPU) does this call wait.
+        const int slot = (int)(ctx->uploads % adagc_ctx::kStagingSlots);
+        if (ctx->upload_pending[slot] && hipEventSynchronize(ctx->upload_done[slot]) != hipSuccess) return ADAGC_ERR_HIP;
+        TensorArgs* stage = ctx->staging + (size_t)slot * (size_t)ctx->n_tensors;
+        std::memcpy(stage, ctx->scratch_args.data(), args_bytes);
+        if (hipMemcpyAsync(ctx->d_targs, stage, args_bytes, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipEventRecord(ctx->upload_done[slot], stream) != hipSuccess)
             return ADAGC_ERR_HIP;
-        ctx->upload_pending = true;
+        ctx->upload_pending[slot] = true;
+        ctx->uploads++;
         ctx->cached_args.swap(ctx->scratch_args);
         ctx->args_uploaded = true;
     }
@@ -348,30 +349,10 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
     const int rc = prepare_tables(ctx, params, grads, exp_avg, exp_avg_sq, stream, false);
     if (rc != ADAGC_OK) return rc;
 
-    // Scalars of this step, in double from the caller's fp32 values.
-    const double lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, wd = hp->weight_decay;
-    const double t = (double)step;
     RuleArgs r;
-    r.lambda_rel = (double)hp->lambda_rel;
-    r.ema_beta = (double)hp->ema_beta;
-    r.lambda_abs = (double)hp->lambda_abs;
-    r.first_step = (step == 1) ? 1 : 0;
-    r.mode = hp->clip_mode;
     UpdateArgs u;
-    u.beta1 = b1;
-    u.one_minus_beta1 = 1.0 - b1;
-    u.beta2 = b2;
-    u.one_minus_beta2 = 1.0 - b2;
-    u.inv_bias2 = 1.0 / (1.0 - std::pow(b2, t));
-    u.step_size = lr / (1.0 - std::pow(b1, t));
-    u.lr_wd = lr * wd;
-    u.eps = (double)hp->eps;
-    u.lr = lr;
-    u.weight_decay = wd;
-
-    const bool warmup = (step - 1) < (int64_t)hp->t_start;   // steps 1..t_start
-    r.warmup = warmup ? 1 : 0;
-    const bool global_rule = warmup || hp->clip_mode != ADAGC_MODE_ADAGC;
+    host_step_scalars(*hp, step, r, u);
+    const bool global_rule = r.warmup || hp->clip_mode != ADAGC_MODE_ADAGC;
     ctx->device_scalars_used = false;
     const bool prof = ctx->prof_steps < ctx->prof_capacity;
     hipEvent_t* ev = prof ? &ctx->prof_events[(size_t)ctx->prof_steps * 4] : nullptr;

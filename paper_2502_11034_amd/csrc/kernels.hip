@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kBlock) void sumsq_partials_kernel(DeviceTables t)
     const int tid = threadIdx.x;
 
     for (uint32_t k = blockIdx.x; k < t.n_chunks; k += gridDim.x) {
-        const uint32_t c = t.schedule[k];
+        const uint32_t c = t.schedule ? t.schedule[k] : k;     // no visiting order given: list order
         const ChunkView cv = chunk_view(t, c);
         const TensorArgs& ta = t.targs[cv.tensor];
         const void* g = grad_chunk_ptr<BF16>(ta.grad, cv.first);
@@ -522,7 +522,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
         const uint32_t k = (uint32_t)(item / group) * 8u + (r & 7u);
         const int isub = (int)(r >> 3);
         if (k >= t.n_chunks) continue;
-        const uint32_t c = t.schedule[k];
+        const uint32_t c = t.schedule ? t.schedule[k] : k;     // no visiting order given: list order
         const ChunkView cv = chunk_view(t, c);
         const TensorArgs& ta = t.targs[cv.tensor];
         const double h = t.coef64[cv.tensor];     // the tensor's coefficient as computed, in double

@@ -57,6 +57,22 @@ def assert_close(name, gpu, ref, rtol=RTOL, exempt=None):
     return int((gpu.view(np.uint32) != ref.view(np.uint32)).sum())
 
 
+def assert_close_streamed(name, gpu, ref, exempt_fn=None):
+    """assert_close for arrays of 1e8..1e9 elements: a bit comparison first, the relative test only on
+    the values that are not bit-identical (the two tests are equivalent: identical bits pass any
+    tolerance).  exempt_fn(indices) -> bool array, evaluated only for those values.
+    Returns the number of values that are not bit-identical."""
+    diff = gpu.view(np.uint32) != ref.view(np.uint32)
+    k = int(np.count_nonzero(diff))
+    if k == 0:
+        return 0
+    idx = np.nonzero(diff)[0]
+    del diff
+    assert_close(name, np.ascontiguousarray(gpu[idx]), np.ascontiguousarray(ref[idx]),
+                 exempt=exempt_fn(idx) if exempt_fn is not None else None)
+    return k
+
+
 def bf16_ordered(bits):
     """Map bf16 bit patterns to integers that increase with the represented value."""
     b = bits.astype(np.int32)
@@ -119,9 +135,11 @@ class Run:
                                 self.h_copies)
         return res + (thr,)
 
-    def lion_exempt(self, i, grad_np, m_before, coef, hp):
-        """Elements whose Lion interpolation is within 1e-6 relative of zero."""
+    def lion_exempt(self, i, grad_np, m_before, coef, hp, idx=None):
+        """Elements (all, or those at `idx`) whose Lion interpolation is within 1e-6 relative of zero."""
         b1 = float(np.float32(hp.beta1))
+        if idx is not None:
+            grad_np, m_before = grad_np[idx], m_before[idx]
         g = widen_grad(grad_np).astype(np.float64)
         a = b1 * m_before.astype(np.float64)
         b = (1.0 - b1) * coef * g

@@ -1,12 +1,25 @@
 """Full-size GPU parity, in the launch configuration the benchmark times: the whole
 Llama-3-8B-shaped list (AdamW + bf16 copy; Lion + bf16 gradients) and the 20 001-tensor ragged
-list, resident on one GPU.  The oracle cannot replay 8e9 parameters in seconds, so:
-  - per-tensor scalars (norm, coefficient, clip flag, gamma) are checked for EVERY tensor on the
-    spike step, from a streamed download of the gradients;
-  - the elementwise update is checked in lockstep (oracle starts from the device's pre-step
-    state) on a subset that contains the largest tensor, the smallest, tensors of every shape
-    class, and spiked tensors.
-Tensors are independent under the per-tensor rule, so a subset loses nothing but coverage."""
+list, resident on one GPU, for the number of steps each workload states (5, 5 and 10).
+
+  - EVERY step: norm, coefficient, clip flag and gamma of EVERY tensor against the oracle, from a
+    streamed download of the gradients.
+  - The elementwise update is checked in lockstep (the oracle starts from the device's pre-step
+    state, so the comparison is a strict one-step one):
+      * on every step for a subset of small tensors of every shape class;
+      * on the spike step for EVERY spiked tensor (multi-chunk tensors with h < 1) plus the largest,
+        the smallest and one of each large shape;
+      * on one later step of the Llama-shaped AdamW list for ALL 291 tensors, streamed tensor by
+        tensor (the pre-step state is kept as a second copy in device memory).
+Tensors are independent under the per-tensor rule, which is what makes a per-tensor replay valid.
+Tensors above 4 Mi elements are replayed by the all-cores build of the oracle (the same source with
+OpenMP, held bit-identical to the one-thread build by tests/test_oracle_all_cores.py); the sums of
+squares of the all-tensor scalar check use it as well."""
+import contextlib
+import math
+import os
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -14,111 +27,205 @@ import torch
 import oracle
 from paper_2502_11034_amd import binding as B
 from paper_2502_11034_amd import workloads as W
-from paper_2502_11034_amd.workloads import to_numpy
 import parity as P
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PROGRESS = os.path.join(ROOT, "gpurun_out", "fullsize_parity_progress.log")
+ALL_CORES_ABOVE = 1 << 22
+T0 = time.time()
 
 
 def say(msg):
-    print(msg, flush=True)
+    """Progress line: printed, and appended to a log file so that a long test is visibly alive."""
+    line = "[%7.1f s] %s" % (time.time() - T0, msg)
+    print(line, flush=True)
+    try:
+        os.makedirs(os.path.dirname(PROGRESS), exist_ok=True)
+        with open(PROGRESS, "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
 
 
 def f32(x):
     return float(np.float32(x))
 
 
-def run_fullsize(w, optimizer, hp, steps, subset, scalar_step, name, early_subset=None):
-    """early_subset: the (smaller) subset checked on the steps before scalar_step; the full subset,
-    which holds the largest tensor, is replayed by the oracle on scalar_step only (time)."""
-    lion = optimizer == "lion"
+def host(t):
+    """The values of a tensor as a host numpy array that nothing else writes to (bf16 as uint16 bits)."""
+    t = t.detach()
+    t = t.cpu() if t.is_cuda else t.clone()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def cores_for(numel):
+    return oracle.all_cores() if numel > ALL_CORES_ABOVE else contextlib.nullcontext()
+
+
+def reference_scalars(w, grads, gamma_prev, ohp, step):
+    """Norm, coefficient, flag, new gamma and threshold of every tensor, composed from the oracle's
+    functions the way its own step composes them (sums of squares by the all-cores build)."""
+    sh = ohp._step()
+    n = w.n_tensors
+    ss = np.zeros(n)
+    with oracle.all_cores():
+        for i in range(n):
+            ss[i] = oracle.sum_squares(host(grads[i]))
+    norms = np.sqrt(ss)
+    coefs = np.ones(n)
+    flags = np.zeros(n, np.uint8)
+    gamma = np.zeros(n, np.float32)
+    thr = sh.lambda_rel * gamma_prev.astype(np.float64)
+    if (step - 1) < sh.t_start:
+        total = 0.0
+        for x in ss:                                    # list order
+            total += float(x)
+        h = oracle.globalgc_coef(math.sqrt(total), sh.lambda_abs)
+        coefs[:] = h
+        flags[:] = 1 if h < 1.0 else 0
+        for i in range(n):
+            gamma[i] = np.float32(oracle.warmup_gamma(float(gamma_prev[i]), h * norms[i], step == 1))
+        thr = None
+    else:
+        for i in range(n):
+            h, g_new, c = oracle.adagc_rule(norms[i], float(gamma_prev[i]), sh.lambda_rel, sh.ema_beta)
+            coefs[i], flags[i], gamma[i] = h, c, np.float32(g_new)
+    return norms, coefs, flags, gamma, thr
+
+
+def lockstep_tensor(run, hp, ohp, step, i, pre, g_np, gamma_prev_i, gpu_scalars, tag):
+    """Replay tensor i's step on the oracle from the device's pre-step state and compare every stored
+    value.  Returns the number of values that are not bit-identical."""
+    norms, coefs, flags, gamma_new = gpu_scalars
+    lion = run.optimizer == B.ADAGC_OPT_LION
+    assert math.isinf(hp.lambda_abs) and hp.clip_mode == B.ADAGC_MODE_ADAGC    # a one-tensor replay is the list's step
+    th, mm, vv = pre
+    copy = np.zeros(th.size, np.uint16) if run.copies is not None else None
+    m_before = mm.copy() if lion else None
+    gam = np.array([gamma_prev_i], np.float32)
+    with cores_for(th.size):
+        rn, rc, rf = oracle.adagc_step([th], [g_np], [mm], [vv] if vv is not None else None, gam, ohp, step,
+                                       [copy] if copy is not None else None)
+    np.testing.assert_allclose(norms[i], rn[0], rtol=P.RTOL, err_msg=tag)
+    np.testing.assert_allclose(coefs[i], rc[0], rtol=P.RTOL, err_msg=tag)
+    np.testing.assert_allclose(gamma_new[i], gam[0], rtol=P.RTOL, err_msg=tag)
+    warm = (step - 1) < hp.t_start
+    if warm or abs(rn[0] / (f32(hp.lambda_rel) * float(gamma_prev_i)) - 1.0) > P.BAND:
+        assert flags[i] == rf[0], tag
+    ex = (lambda idx: run.lion_exempt(i, g_np, m_before, rc[0], hp, idx)) if lion else None
+    gpu_theta = host(run.params[i])
+    d_theta = P.assert_close_streamed(tag + " theta", gpu_theta, th, ex)
+    differ = d_theta
+    differ += P.assert_close_streamed(tag + " m", host(run.m[i]), mm)
+    if vv is not None:
+        differ += P.assert_close_streamed(tag + " v", host(run.v[i]), vv)
+    if copy is not None:
+        gpu_copy = host(run.copies[i])
+        if d_theta == 0:
+            # same fp32 theta on both sides: the copy must be the oracle's own conversion, bit for bit
+            assert np.array_equal(gpu_copy, copy), tag + ": bf16 copy differs from the oracle's"
+        else:
+            exempt = ex(np.arange(th.size)) if ex is not None else None
+            P.assert_bf16_copy(tag, gpu_copy, gpu_theta, th, exempt)
+    return differ
+
+
+def pre_state(run, i, src=None):
+    p, m, v = src if src is not None else (run.params, run.m, run.v)
+    return (host(p[i]), host(m[i]), host(v[i]) if v is not None else None)
+
+
+def snapshot_all(run):
+    """A second copy of theta, m, v: in device memory if it fits beside the workload, else on the host."""
+    arrays = [run.params, run.m] + ([run.v] if run.v is not None else [])
+    need = sum(t.numel() * 4 for lst in arrays for t in lst)
+    free, _ = torch.cuda.mem_get_info()
+    where = DEV if free > need + (8 << 30) else "cpu"
+    say("second copy of the state (%.1f GB) goes to %s" % (need / 1e9, where))
+    snap = [[t.to(where, copy=True) for t in lst] for lst in arrays]
+    if run.v is None:
+        snap.append(None)
+    return snap
+
+
+def run_fullsize(w, optimizer, hp, steps, name, elementwise, all_tensors_step=None):
+    """elementwise: {step: tensor indices replayed element by element}; key 0 = every other step."""
     run = P.Run(w, optimizer=optimizer, mirror=False)
     ohp = P.oracle_hyper(hp, run.optimizer, run.grad_dtype)
     say("%s: %d tensors, %d params resident" % (name, w.n_tensors, w.total_params))
-    full_subset = subset
+    clipped_total = 0
     for step in range(1, steps + 1):
-        subset = full_subset if (step == scalar_step or early_subset is None) else early_subset
-        pre = {}
-        for i in subset:
-            pre[i] = (to_numpy(run.params[i]), to_numpy(run.m[i]),
-                      to_numpy(run.v[i]) if run.v is not None else None)
-        gamma_prev = to_numpy(run.gamma)
+        subset = list(range(w.n_tensors)) if step == all_tensors_step else elementwise.get(step, elementwise[0])
+        snap = snapshot_all(run) if step == all_tensors_step else None
+        pre = {} if snap is not None else {i: pre_state(run, i) for i in subset}
+        gamma_prev = host(run.gamma)
         grads = w.make_grads(step, DEV)
-        norms, coefs, flags = run.gpu_step(grads, hp, step)
-        gamma_new = to_numpy(run.gamma)
-        warm = (step - 1) < hp.t_start
+        gpu_scalars = run.gpu_step(grads, hp, step) + (host(run.gamma),)
+        norms, coefs, flags, gamma_new = gpu_scalars
 
-        if step == scalar_step:
-            lam, beta = f32(hp.lambda_rel), f32(hp.ema_beta)
-            rn = np.zeros(w.n_tensors)
-            rc = np.zeros(w.n_tensors)
-            rf = np.zeros(w.n_tensors, np.uint8)
-            rg = np.zeros(w.n_tensors, np.float32)
-            for i in range(w.n_tensors):
-                rn[i] = oracle.l2_norm(to_numpy(grads[i]))
-                h, g_new, c = oracle.adagc_rule(rn[i], float(gamma_prev[i]), lam, beta)
-                rc[i], rf[i], rg[i] = h, c, np.float32(g_new)
-            thr = lam * gamma_prev.astype(np.float64)
-            P.check_scalars("%s step %d all tensors" % (name, step), norms, coefs, flags, gamma_new,
-                            rn, rc, rf, rg, thr)
-            say("%s step %d: scalars of all %d tensors ok, %d clipped" % (name, step, w.n_tensors, int(rf.sum())))
-            if step in w.spikes:
-                assert rf[w.spikes[step][0]].all(), "spiked tensors must clip"
+        rn, rc, rf, rg, thr = reference_scalars(w, grads, gamma_prev, ohp, step)
+        P.check_scalars("%s step %d all tensors" % (name, step), norms, coefs, flags, gamma_new, rn, rc, rf, rg, thr)
+        say("%s step %d: norm, coefficient, flag, gamma of all %d tensors ok, %d clipped"
+            % (name, step, w.n_tensors, int(rf.sum())))
+        clipped_total += int(rf.sum())
+        if step in w.spikes:
+            assert rf[w.spikes[step][0]].all(), "spiked tensors must clip"
 
-        strict = 0
-        for i in subset:
-            th, mm, vv = pre[i]
-            g_np = to_numpy(grads[i])
-            gam = gamma_prev[i:i + 1].copy()
-            copy = np.zeros(th.size, np.uint16) if run.copies is not None else None
-            m_before = mm.copy()
-            rn1, rc1, rf1 = oracle.adagc_step([th], [g_np], [mm], [vv] if vv is not None else None, gam, ohp,
-                                              step, [copy] if copy is not None else None)
+        differ, values = 0, 0
+        for k, i in enumerate(subset):
             tag = "%s step %d tensor %d (%s)" % (name, step, i, w.specs[i].name)
-            np.testing.assert_allclose(norms[i], rn1[0], rtol=P.RTOL, err_msg=tag)
-            np.testing.assert_allclose(coefs[i], rc1[0], rtol=P.RTOL, err_msg=tag)
-            np.testing.assert_allclose(gamma_new[i], gam[0], rtol=P.RTOL, err_msg=tag)
-            if warm or abs(rn1[0] / (f32(hp.lambda_rel) * float(gamma_prev[i])) - 1.0) > P.BAND:
-                assert flags[i] == rf1[0], tag
-            ex = run.lion_exempt(i, g_np, m_before, rc1[0], hp) if lion else None
-            gpu_theta = to_numpy(run.params[i])
-            strict += P.assert_close(tag + " theta", gpu_theta, th, exempt=ex)
-            strict += P.assert_close(tag + " m", to_numpy(run.m[i]), mm)
-            if vv is not None:
-                strict += P.assert_close(tag + " v", to_numpy(run.v[i]), vv)
-            if copy is not None:
-                P.assert_bf16_copy(tag, to_numpy(run.copies[i]), gpu_theta, th, ex)
-            del th, mm, vv, g_np, copy
-        say("%s step %d: update within relative 1e-5 on every element of %d tensors (%d values not bit-identical)"
-            % (name, step, len(subset), strict))
-        del grads, pre
+            if snap is not None:
+                p_i = pre_state(run, i, snap)
+                for lst in snap:
+                    if lst is not None:
+                        lst[i] = None                       # release the second copy as we go
+            else:
+                p_i = pre.pop(i)
+            differ += lockstep_tensor(run, hp, ohp, step, i, p_i, host(grads[i]), gamma_prev[i], gpu_scalars, tag)
+            values += w.numels[i] * (3 if run.v is not None else 2)
+            if snap is not None and (k % 29 == 28 or k + 1 == len(subset)):
+                say("%s step %d: %d of %d tensors replayed" % (name, step, k + 1, len(subset)))
+        say("%s step %d: %d of %d tensors, update within relative 1e-5 on every element, %d values not bit-identical"
+            % (name, step, len(subset), w.n_tensors, differ))
+        # both sides round a double result once: all but a vanishing fraction is bit-identical
+        assert differ <= max(4, values // 100000)
+        del grads, pre, snap
     run.ctx.close()
     del run
     torch.cuda.empty_cache()
+    return clipped_total
 
 
 def llama_subsets(w, spike_step):
+    """{step: indices}: small tensors of every class on every step; on the spike step every spiked
+    tensor, the largest and smallest tensors and one of each large shape."""
     names = {s.name: i for i, s in enumerate(w.specs)}
-    early = [names["l0.attn_norm"], names["l0.k"], names["final_norm"]]
-    subset = early + [names["embed"], names["l7.q"], names["l31.down"]]
+    small = [names["l0.attn_norm"], names["l0.k"], names["final_norm"], names["l31.ffn_norm"], names["l16.v"]]
+    large = [names["embed"], names["lm_head"], names["l7.q"], names["l31.down"], names["l0.gate"]]
     spiked = [int(i) for i in w.spikes[spike_step][0]]
-    small_spiked = sorted(spiked, key=lambda i: w.numels[i])[:2]
-    return sorted(set(subset + small_spiked)), sorted(set(early + small_spiked))
+    return {0: sorted(small), spike_step: sorted(set(small + large + spiked))}, spiked
 
 
 def test_config3_full_size_llama3_8b_adamw():
     w = W.config3()
     assert w.n_tensors == 291 and w.total_params == 8030261248
-    full, early = llama_subsets(w, 3)
-    run_fullsize(w, "adamw", B.make_hyper(), 3, full, 3, "config3-full", early)
+    elementwise, spiked = llama_subsets(w, 3)
+    assert len(spiked) == 15 and max(w.numels[i] for i in spiked) > 16 * B.adagc_chunk_elems()
+    clipped = run_fullsize(w, "adamw", B.make_hyper(), 5, "config3-full", elementwise, all_tensors_step=4)
+    assert clipped >= 15
 
 
 def test_config4_full_size_llama3_8b_lion_bf16_grads():
     w = W.config4()
     hp = B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1)
-    full, early = llama_subsets(w, 3)
-    run_fullsize(w, "lion", hp, 3, full, 3, "config4-full", early)
+    elementwise, spiked = llama_subsets(w, 3)
+    assert len(spiked) == 15
+    clipped = run_fullsize(w, "lion", hp, 5, "config4-full", elementwise)
+    assert clipped >= 15
 
 
 def test_config5_full_size_ragged_stress():
@@ -130,8 +237,8 @@ def test_config5_full_size_ragged_stress():
     subset = sorted(set([int(order[0]), int(order[1]), int(order[-2])] +          # smallest two, largest ragged
                         [int(i) for i in rng.choice(20000, 150, replace=False)] +
                         [20000]))                                                  # the 128256x4096 tensor
-    early = [i for i in subset if w.numels[i] <= (1 << 20)]
-    run_fullsize(w, "adamw", B.make_hyper(), 2, subset, 2, "config5-full", early)
+    small = [i for i in subset if w.numels[i] <= (1 << 20)]
+    run_fullsize(w, "adamw", B.make_hyper(), 10, "config5-full", {0: small, 2: subset, 6: subset, 10: subset})
 
 
 def test_one_tensor_beyond_2_to_31_elements():
@@ -148,28 +255,28 @@ def test_one_tensor_beyond_2_to_31_elements():
     copy = torch.empty(n, dtype=torch.bfloat16, device=dev)
     gamma = torch.tensor([1.0], dtype=torch.float32, device=dev)
     slices = [(0, 1 << 20), ((1 << 31) - (1 << 19), (1 << 31) + 4096), (n - 70001, n)]
-    pre = [(to_numpy(p[a:b]), to_numpy(m[a:b]), to_numpy(v[a:b]), to_numpy(g[a:b])) for a, b in slices]
+    pre = [(host(p[a:b]), host(m[a:b]), host(v[a:b]), host(g[a:b])) for a, b in slices]
     hp = B.make_hyper(t_start=0)
     ctx = B.AdaGC([n], has_bf16_param_copy=True)
     assert ctx.num_chunks() == -(-n // B.adagc_chunk_elems())
     ctx.set_param_copies([copy])
     ctx.step([p], [g], [m], [v], gamma, hp, 3)
     norms, coefs, flags = ctx.get_norms()
-    ref_norm = oracle.l2_norm(to_numpy(g))
+    ref_norm = oracle.l2_norm(host(g))
     h, gamma_new, clipped = oracle.adagc_rule(ref_norm, 1.0, f32(hp.lambda_rel), f32(hp.ema_beta))
     say("2^31+ tensor: norm %.6f (ref %.6f), h %.6f, clipped %d" % (norms[0], ref_norm, coefs[0], clipped))
     assert clipped and flags[0] == 1
     np.testing.assert_allclose(norms[0], ref_norm, rtol=P.RTOL)
     np.testing.assert_allclose(coefs[0], h, rtol=P.RTOL)
-    np.testing.assert_allclose(to_numpy(gamma)[0], np.float32(gamma_new), rtol=P.RTOL)
+    np.testing.assert_allclose(host(gamma)[0], np.float32(gamma_new), rtol=P.RTOL)
     ohp = P.oracle_hyper(hp, 0, 0)
     for (a, b), (th, mm, vv, gg) in zip(slices, pre):
         ref_copy = np.zeros(b - a, np.uint16)
         oracle.adamw_update(th, mm, vv, gg, h, ohp, 3, ref_copy)
         tag = "2^31+ tensor slice [%d, %d)" % (a, b)
-        gpu_theta = to_numpy(p[a:b])
+        gpu_theta = host(p[a:b])
         P.assert_close(tag + " theta", gpu_theta, th)
-        P.assert_close(tag + " m", to_numpy(m[a:b]), mm)
-        P.assert_close(tag + " v", to_numpy(v[a:b]), vv)
-        P.assert_bf16_copy(tag, to_numpy(copy[a:b]), gpu_theta, th)
+        P.assert_close(tag + " m", host(m[a:b]), mm)
+        P.assert_close(tag + " v", host(v[a:b]), vv)
+        P.assert_bf16_copy(tag, host(copy[a:b]), gpu_theta, th)
     ctx.close()

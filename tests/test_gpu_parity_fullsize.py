@@ -9,8 +9,12 @@ list, resident on one GPU, for the number of steps each workload states (5, 5 an
       * on every step for a subset of small tensors of every shape class;
       * on the spike step for EVERY spiked tensor (multi-chunk tensors with h < 1) plus the largest,
         the smallest and one of each large shape;
-      * on one later step of the Llama-shaped AdamW list for ALL 291 tensors, streamed tensor by
+      * on one later step of both Llama-shaped lists for ALL 291 tensors, streamed tensor by
         tensor (the pre-step state is kept as a second copy in device memory).
+A value that is not bit-identical to the oracle's must be within relative 1e-5 of it; for a clipped
+tensor it may instead lie between the oracle's results for the two ends of the interval in which the
+tensor's coefficient is defined (parity.coefficient_interval: the paper fixes no summation order for
+the norm), which matters only where the two terms of the first moment cancel.
 Tensors are independent under the per-tensor rule, which is what makes a per-tensor replay valid.
 Tensors above 4 Mi elements are replayed by the all-cores build of the oracle (the same source with
 OpenMP, held bit-identical to the one-thread build by tests/test_oracle_all_cores.py); the sums of
@@ -106,6 +110,9 @@ def lockstep_tensor(run, hp, ohp, step, i, pre, g_np, gamma_prev_i, gpu_scalars,
     th, mm, vv = pre
     copy = np.zeros(th.size, np.uint16) if run.copies is not None else None
     m_before = mm.copy() if lion else None
+    # a clipped tensor: keep the pre-step values, for the oracle's results at the two ends of the
+    # interval in which its coefficient is defined (only evaluated where a value misses the plain test)
+    kept = (th.copy(), mm.copy(), vv.copy() if vv is not None else None) if flags[i] else None
     gam = np.array([gamma_prev_i], np.float32)
     with cores_for(th.size):
         rn, rc, rf = oracle.adagc_step([th], [g_np], [mm], [vv] if vv is not None else None, gam, ohp, step,
@@ -116,21 +123,45 @@ def lockstep_tensor(run, hp, ohp, step, i, pre, g_np, gamma_prev_i, gpu_scalars,
     warm = (step - 1) < hp.t_start
     if warm or abs(rn[0] / (f32(hp.lambda_rel) * float(gamma_prev_i)) - 1.0) > P.BAND:
         assert flags[i] == rf[0], tag
+
+    def envelope(which):
+        if kept is None:
+            return None
+
+        def at(idx):
+            ends = []
+            for h_end in P.coefficient_interval(rc[0], th.size):
+                a_th, a_m = kept[0][idx].copy(), kept[1][idx].copy()
+                a_v = kept[2][idx].copy() if kept[2] is not None else None
+                g_idx = np.ascontiguousarray(g_np[idx])
+                if lion:
+                    oracle.lion_update(a_th, a_m, g_idx, h_end, ohp)
+                else:
+                    oracle.adamw_update(a_th, a_m, a_v, g_idx, h_end, ohp, step)
+                ends.append({"theta": a_th, "m": a_m, "v": a_v}[which])
+            return ends[0], ends[1]
+        return at
+
     ex = (lambda idx: run.lion_exempt(i, g_np, m_before, rc[0], hp, idx)) if lion else None
     gpu_theta = host(run.params[i])
-    d_theta = P.assert_close_streamed(tag + " theta", gpu_theta, th, ex)
+    d_theta = P.assert_close_streamed(tag + " theta", gpu_theta, th, ex, envelope("theta"))
     differ = d_theta
-    differ += P.assert_close_streamed(tag + " m", host(run.m[i]), mm)
+    differ += P.assert_close_streamed(tag + " m", host(run.m[i]), mm, None, envelope("m"))
     if vv is not None:
-        differ += P.assert_close_streamed(tag + " v", host(run.v[i]), vv)
+        differ += P.assert_close_streamed(tag + " v", host(run.v[i]), vv, None, envelope("v"))
     if copy is not None:
         gpu_copy = host(run.copies[i])
-        if d_theta == 0:
-            # same fp32 theta on both sides: the copy must be the oracle's own conversion, bit for bit
-            assert np.array_equal(gpu_copy, copy), tag + ": bf16 copy differs from the oracle's"
-        else:
-            exempt = ex(np.arange(th.size)) if ex is not None else None
-            P.assert_bf16_copy(tag, gpu_copy, gpu_theta, th, exempt)
+        exact = torch.from_numpy(gpu_theta).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(gpu_copy, exact), tag + ": bf16 copy is not RNE of the stored fp32 value"
+        # against the oracle's own conversion: identical wherever theta is, at most 1 bf16 ulp elsewhere
+        mism = np.nonzero(gpu_copy != copy)[0]
+        if mism.size:
+            theta_differs = gpu_theta.view(np.uint32)[mism] != th.view(np.uint32)[mism]
+            assert theta_differs.all(), tag + ": bf16 copy differs from the oracle's where theta does not"
+            d = np.abs(P.bf16_ordered(gpu_copy[mism]) - P.bf16_ordered(copy[mism]))
+            if ex is not None:
+                d = np.where(ex(mism), 0, d)
+            assert int(d.max(initial=0)) <= 1, tag + ": bf16 copy more than 1 ulp from the oracle's"
     return differ
 
 
@@ -224,7 +255,7 @@ def test_config4_full_size_llama3_8b_lion_bf16_grads():
     hp = B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1)
     elementwise, spiked = llama_subsets(w, 3)
     assert len(spiked) == 15
-    clipped = run_fullsize(w, "lion", hp, 5, "config4-full", elementwise)
+    clipped = run_fullsize(w, "lion", hp, 5, "config4-full", elementwise, all_tensors_step=4)
     assert clipped >= 15
 
 

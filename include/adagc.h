@@ -228,6 +228,38 @@ int adagc_step_graph(adagc_ctx* ctx, void* const* params, const void* const* gra
                      const adagc_step_params* step_params, void* stream);
 
 /*
+ * For callers that cannot allocate device memory: code running under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The same step as adagc_step, without a context:
+ * this call allocates nothing (no hipMalloc / hipFree, no copy, no memset, no event), it only
+ * launches kernels on `stream`.  The segment table, the per-chunk partial sums and the per-tensor
+ * results live in a fixed array inside the library's device code, ADAGC_STATIC_MAX_* in size
+ * (about 11 MB per GPU, held from the library's load until the process ends).
+ *   descs, n_tensors, cfg   HOST  as for adagc_create; cfg->telemetry and the launch-tuning fields
+ *                                 must be 0 (library defaults, chunks visited in list order)
+ *   params, grads, exp_avg, exp_avg_sq, ema_norms, hp, step, stream   as for adagc_step
+ *   params_bf16   HOST array of n_tensors DEVICE pointers (cfg->has_bf16_param_copy = 1), else NULL
+ *   out_norms     DEVICE fp32[n_tensors]  ||g_i|| before clipping        (may be NULL)
+ *   out_coefs     DEVICE fp32[n_tensors]  h_i                            (may be NULL)
+ *   out_clipped   DEVICE u8[n_tensors]    1 where the clip was active    (may be NULL)
+ * The tensors belong to the current GPU.  Results are those of adagc_step bit for bit (the same
+ * kernels; the visiting order never changes a result).
+ * Limits: n_tensors <= ADAGC_STATIC_MAX_TENSORS and at most ADAGC_STATIC_MAX_CHUNKS chunks of
+ * adagc_chunk_elems() elements (each tensor takes ceil(numel / chunk) of them); beyond that the call
+ * returns ADAGC_ERR_TOO_LARGE and enqueues nothing.
+ * Every call on a GPU uses that GPU's one array, whose contents are those of the last call: calls
+ * that overlap on one GPU (two streams, two threads) race and must be ordered by the caller.  Nothing
+ * in the array has to start at zero: each call overwrites every slot it reads.
+ * Errors: INVALID_ARG, TOO_LARGE, HIP; arguments are validated before anything is enqueued.
+ */
+#define ADAGC_STATIC_MAX_TENSORS 32768
+#define ADAGC_STATIC_MAX_CHUNKS  524288
+int adagc_step_static(const adagc_tensor_desc* descs, int64_t n_tensors, const adagc_config* cfg,
+                      void* const* params, const void* const* grads, void* const* exp_avg,
+                      void* const* exp_avg_sq, void* const* params_bf16, float* ema_norms,
+                      const adagc_hyper* hp, int64_t step, float* out_norms, float* out_coefs,
+                      uint8_t* out_clipped, void* stream);
+
+/*
  * Per-tensor results of the most recently enqueued step: copies them to the host
  * and waits for `stream`.  Any of the three output arrays may be NULL.
  *   host_norms    HOST fp32[n_tensors]   ||g_i|| before clipping

@@ -25,7 +25,7 @@ ADAGC_MODE_ADAGC, ADAGC_MODE_GLOBALGC, ADAGC_MODE_GLOBAL_ADAGC = 0, 1, 2
 
 EXPORTS = [
     "adagc_chunk_elems", "adagc_build_segment_table", "adagc_build_visiting_order", "adagc_create", "adagc_destroy",
-    "adagc_set_param_copies", "adagc_step", "adagc_step_graph", "adagc_get_norms", "adagc_get_state_norms", "adagc_num_tensors",
+    "adagc_set_param_copies", "adagc_step", "adagc_step_graph", "adagc_step_static", "adagc_get_norms", "adagc_get_state_norms", "adagc_num_tensors",
     "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end",
     "adagc_strerror",
 ]
@@ -90,6 +90,9 @@ def lib():
     L.adagc_step.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(adagc_hyper), i64, vp]
     L.adagc_step_graph.restype = ctypes.c_int
     L.adagc_step_graph.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.adagc_step_static.restype = ctypes.c_int
+    L.adagc_step_static.argtypes = [vp, i64, ctypes.POINTER(adagc_config), vp, vp, vp, vp, vp, vp,
+                                    ctypes.POINTER(adagc_hyper), i64, vp, vp, vp, vp]
     L.adagc_get_norms.restype = ctypes.c_int
     L.adagc_get_norms.argtypes = [vp, vp, vp, vp, i64, vp]
     L.adagc_get_state_norms.restype = ctypes.c_int
@@ -173,6 +176,27 @@ def adagc_build_visiting_order(n_chunks, parts=2, run=8):
                                             order.ctypes.data if order.size else None),
            "adagc_build_visiting_order")
     return order
+
+
+ADAGC_STATIC_MAX_TENSORS = 32768
+ADAGC_STATIC_MAX_CHUNKS = 524288
+
+
+def adagc_step_static(numels, params, grads, exp_avg, exp_avg_sq, ema_norms, hyper, step, optimizer=ADAGC_OPT_ADAMW,
+                      grad_dtype=ADAGC_GRAD_F32, params_bf16=None, out_norms=None, out_coefs=None, out_clipped=None,
+                      stream=None):
+    """adagc_step_static: the step without a context and without any allocation on the GPU side.
+    out_*: device tensors (or None).  Raises AdagcError on a non-zero return code."""
+    cfg = adagc_config(int(optimizer), int(grad_dtype), int(params_bf16 is not None), 0, 0, 0, 0, 0, 0, 0)
+    descs = _descs([int(n) for n in numels])
+    p, g, m = (ptr_array(x) for x in (params, grads, exp_avg))
+    v = ptr_array(exp_avg_sq) if exp_avg_sq is not None else None
+    c = ptr_array(params_bf16) if params_bf16 is not None else None
+    dp = lambda t: t.data_ptr() if t is not None else None
+    _check(lib().adagc_step_static(ctypes.cast(descs, ctypes.c_void_p), len(numels), ctypes.byref(cfg), p, g, m, v, c,
+                                   ema_norms.data_ptr(), ctypes.byref(hyper), int(step), dp(out_norms),
+                                   dp(out_coefs), dp(out_clipped), ctypes.c_void_p(stream) if stream else None),
+           "adagc_step_static")
 
 
 class AdaGC:

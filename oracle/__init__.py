@@ -25,6 +25,7 @@ GRAD_BF16 = 1
 MODE_ADAGC = 0          # Alg. 1
 MODE_GLOBALGC = 1       # Eq. 2 on every step
 MODE_GLOBAL_ADAGC = 2   # one adaptive threshold for the whole model ("Ablation Study", Sec. 5.6)
+MODE_ZCLIP = 3          # z-score clipping of the global norm (Table 2; appendix "Clipping Hyper-Parameters")
 
 
 class _OptHyper(ctypes.Structure):
@@ -38,7 +39,7 @@ class _StepHyper(ctypes.Structure):
                 ("lambda_rel", ctypes.c_double), ("ema_beta", ctypes.c_double),
                 ("lambda_abs", ctypes.c_double), ("t_start", ctypes.c_int64),
                 ("optimizer", ctypes.c_int32), ("grad_dtype", ctypes.c_int32),
-                ("clip_mode", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("clip_mode", ctypes.c_int32), ("reserved", ctypes.c_int32), ("z_thres", ctypes.c_double)]
 
 
 def _f32(x):
@@ -63,6 +64,7 @@ class Hyper:
     optimizer: int = ADAMW
     grad_dtype: int = GRAD_F32
     clip_mode: int = MODE_ADAGC
+    z_thres: float = 2.0          # ZClip only; appendix "Clipping Hyper-Parameters" (with alpha = ema_beta = 0.97)
 
     def _opt(self):
         return _OptHyper(_f32(self.lr), _f32(self.beta1), _f32(self.beta2), _f32(self.eps),
@@ -72,7 +74,7 @@ class Hyper:
         return _StepHyper(_f32(self.lr), _f32(self.beta1), _f32(self.beta2), _f32(self.eps),
                           _f32(self.weight_decay), _f32(self.lambda_rel), _f32(self.ema_beta),
                           _f32(self.lambda_abs), int(self.t_start), int(self.optimizer),
-                          int(self.grad_dtype), int(self.clip_mode), 0)
+                          int(self.grad_dtype), int(self.clip_mode), 0, _f32(self.z_thres))
 
 
 def _declare(L):
@@ -94,6 +96,11 @@ def _declare(L):
     L.oracle_globalgc_coef.argtypes = [dbl, dbl]
     L.oracle_warmup_gamma.restype = dbl
     L.oracle_warmup_gamma.argtypes = [dbl, dbl, i32]
+    L.oracle_zclip_rule.restype = None
+    L.oracle_zclip_rule.argtypes = [dbl, dbl, dbl, dbl, dbl, ctypes.POINTER(dbl), ctypes.POINTER(dbl),
+                                    ctypes.POINTER(dbl), ctypes.POINTER(i32)]
+    L.oracle_zclip_gather.restype = None
+    L.oracle_zclip_gather.argtypes = [dbl, dbl, dbl, dbl, i32, ctypes.POINTER(dbl), ctypes.POINTER(dbl)]
     L.oracle_adamw_update.restype = None
     L.oracle_adamw_update.argtypes = [vp, vp, vp, vp, i32, i64, dbl,
                                       ctypes.POINTER(_OptHyper), i64, vp]
@@ -198,6 +205,22 @@ def warmup_gamma(gamma_prev, clipped_norm, first_step):
     return lib().oracle_warmup_gamma(gamma_prev, clipped_norm, int(bool(first_step)))
 
 
+def zclip_rule(norm, mu_prev, var_prev, alpha, z_thres):
+    """(h, mu_new, var_new, clipped) of ZClip's z-score rule on one global norm."""
+    h, mu, var, c = ctypes.c_double(), ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
+    lib().oracle_zclip_rule(norm, mu_prev, var_prev, alpha, z_thres, ctypes.byref(h), ctypes.byref(mu),
+                            ctypes.byref(var), ctypes.byref(c))
+    return h.value, mu.value, var.value, bool(c.value)
+
+
+def zclip_gather(clipped_norm, mu_prev, var_prev, alpha, first_step):
+    """(mu_new, var_new) on a step that only gathers ZClip's statistics."""
+    mu, var = ctypes.c_double(), ctypes.c_double()
+    lib().oracle_zclip_gather(clipped_norm, mu_prev, var_prev, alpha, int(bool(first_step)), ctypes.byref(mu),
+                              ctypes.byref(var))
+    return mu.value, var.value
+
+
 def adamw_update(theta, m, v, g, h, hyper, t, theta_bf16=None):
     n = theta.size
     oh = hyper._opt()
@@ -230,7 +253,8 @@ def adagc_step(theta, grad, m, v, gamma, hyper, step, theta_bf16=None):
     """One pass of the body of Alg. 1 over a list of tensors.
 
     theta, grad, m, v (None for Lion), theta_bf16 (or None): lists of 1-D arrays.
-    gamma: float32 array, one entry per tensor, updated in place.
+    gamma: float32 array, one entry per tensor, updated in place (MODE_ZCLIP: entries 0 and 1 hold the
+    mean and the variance of the global norm, so a one-tensor list needs two entries).
     Returns (norms float64[n], coefs float64[n], clipped uint8[n]).
     """
     n = len(theta)
@@ -255,7 +279,8 @@ def adagc_step(theta, grad, m, v, gamma, hyper, step, theta_bf16=None):
     clipped = np.zeros(n, dtype=np.uint8)
     sh = hyper._step()
     rc = lib().oracle_adagc_step(n, numel.ctypes.data, p_theta, p_grad, p_m, p_v, p_c,
-                                 _check(gamma, np.float32, n), ctypes.byref(sh), int(step),
+                                 _check(gamma, np.float32, max(n, 2) if hyper.clip_mode == MODE_ZCLIP else n),
+                                 ctypes.byref(sh), int(step),
                                  norms.ctypes.data, coefs.ctypes.data, clipped.ctypes.data)
     if rc != 0:
         raise ValueError("oracle_adagc_step rejected its arguments")

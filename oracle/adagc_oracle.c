@@ -14,6 +14,12 @@
  *   - "Global AdaGC" (one adaptive threshold for the whole model; ablation
  *     "Adaptivity Efficacy and Locality Granularity" of the "Ablation Study", Sec. 5.6): Eq. 3 and the
  *     warm-up branch applied to the global norm with a single gamma
+ *   - ZClip (a baseline of the paper's comparison): Table 2 prints the
+ *     coefficient min{1, tau_t/||g_t||}, tau_t = mu_t + xi(z_t) sigma_t and
+ *     z_t = (||g_t|| - mu_t)/sigma_t over the GLOBAL norm; the appendix
+ *     "Clipping Hyper-Parameters" gives alpha = 0.97 and z_thres = 2.0.  The
+ *     adjustment function xi and the update of mu, sigma are not printed: see
+ *     oracle_zclip_rule for the reading taken ("parity unpinned by the paper").
  *   - AdamW moments, bias correction, update ..... Alg. 1 (last four statements)
  * What the paper does not print and is taken from its citation:
  *   - Lion update rule (Chen et al., "Symbolic discovery of optimization
@@ -201,6 +207,55 @@ double oracle_warmup_gamma(double gamma_prev, double clipped_norm, int first_ste
     return clipped_norm < gamma_prev ? clipped_norm : gamma_prev;
 }
 
+/* ---- ZClip (Table 2 "Comparison of major gradient/update clipping methods") ---
+ *
+ * Printed: h = min{1, tau/||g||}, tau = mu + xi(z) sigma, z = (||g|| - mu)/sigma, with mu and
+ * sigma the EMA mean and standard deviation of the global gradient norm; alpha = 0.97 and
+ * z_thres = 2.0 (appendix "Clipping Hyper-Parameters").
+ * Not printed, reading taken here:
+ *   - the clip is active only for z > z_thres (strict);
+ *   - xi(z) = z_thres^2 / z, the reciprocal adjustment: the further out the norm lies, the lower
+ *     the threshold; at z = z_thres it gives tau = ||g||, so h is continuous there;
+ *   - the statistics take the CLIPPED norm nhat (tau when active, ||g|| otherwise), as AdaGC's
+ *     own EMA does: mu' = alpha mu + (1-alpha) nhat, var' = alpha var + (1-alpha)(nhat - mu')^2,
+ *     sigma = sqrt(var); mu and var are kept as two 32-bit floats.
+ * sigma = 0 needs no special case: z is +inf, -inf or NaN, and IEEE arithmetic gives tau = mu
+ * for a norm above mu and no clip otherwise. */
+void oracle_zclip_rule(double norm, double mu_prev, double var_prev, double alpha, double z_thres,
+                       double *h, double *mu_new, double *var_new, int *clipped)
+{
+    double sigma = sqrt(var_prev);
+    double z = (norm - mu_prev) / sigma;
+    int active = (z > z_thres);            /* false for NaN */
+    double xi = z_thres * z_thres / z;
+    double tau = mu_prev + xi * sigma;
+    double coef = active ? tau / norm : 1.0;
+    double clipped_norm = active ? tau : norm;
+    double mu = alpha * mu_prev + (1.0 - alpha) * clipped_norm;
+    double dev = clipped_norm - mu;
+    *h = coef;
+    *mu_new = mu;
+    *var_new = alpha * var_prev + (1.0 - alpha) * dev * dev;
+    *clipped = active;
+}
+
+/* Statistics of the steps before the z-score rule applies (the first t_start steps, on which the
+ * gradient only passes through GlobalGC): the first step sets mu to its clipped norm with zero
+ * variance, later ones update both as above. */
+void oracle_zclip_gather(double clipped_norm, double mu_prev, double var_prev, double alpha,
+                         int first_step, double *mu_new, double *var_new)
+{
+    if (first_step) {
+        *mu_new = clipped_norm;
+        *var_new = 0.0;
+        return;
+    }
+    double mu = alpha * mu_prev + (1.0 - alpha) * clipped_norm;
+    double dev = clipped_norm - mu;
+    *mu_new = mu;
+    *var_new = alpha * var_prev + (1.0 - alpha) * dev * dev;
+}
+
 /* ---- Alg. 1, last four statements: AdamW on the clipped gradient ----------- */
 
 typedef struct {
@@ -268,8 +323,11 @@ typedef struct {
     int32_t optimizer;                          /* 0 = AdamW, 1 = Lion                      */
     int32_t grad_dtype;                         /* 0 = float32, 1 = bf16                    */
     int32_t clip_mode;                          /* 0 = AdaGC (Alg. 1), 1 = GlobalGC on every step (Eq. 2),
-                                                   2 = Global AdaGC (single gamma, kept in gamma[0]) */
+                                                   2 = Global AdaGC (single gamma, kept in gamma[0]),
+                                                   3 = ZClip (mu in gamma[0], variance in gamma[1];
+                                                       ema_beta is its alpha) */
     int32_t reserved;
+    double z_thres;                             /* ZClip's z-score threshold */
 } oracle_step_hyper;
 
 /* Arrays of per-tensor pointers; state is updated in place.  v may be NULL for
@@ -290,7 +348,7 @@ int oracle_adagc_step(int64_t n_tensors, const int64_t *numel, float *const *the
     int warmup = (step - 1) < hp->t_start; /* steps 1..T_start */
 
     const int mode = hp->clip_mode;
-    if (mode < 0 || mode > 2)
+    if (mode < 0 || mode > 3)
         return -1;
 
     /* ||g_t|| over the whole model: tensors in list order, elements in index order */
@@ -307,11 +365,24 @@ int oracle_adagc_step(int64_t n_tensors, const int64_t *numel, float *const *the
             oracle_adagc_rule(global_norm, (double)gamma[0], hp->lambda_rel, hp->ema_beta, &h_global,
                               &gamma_new, &clipped_global);
             gamma[0] = (float)gamma_new;
+        } else if (mode == 3 && !warmup) {
+            double mu_new, var_new;
+            oracle_zclip_rule(global_norm, (double)gamma[0], (double)gamma[1], hp->ema_beta, hp->z_thres,
+                              &h_global, &mu_new, &var_new, &clipped_global);
+            gamma[0] = (float)mu_new;
+            gamma[1] = (float)var_new;
         } else {
             h_global = oracle_globalgc_coef(global_norm, hp->lambda_abs);
             clipped_global = (h_global < 1.0);
             if (mode == 2)
                 gamma[0] = (float)oracle_warmup_gamma((double)gamma[0], h_global * global_norm, step == 1);
+            if (mode == 3) {
+                double mu_new, var_new;
+                oracle_zclip_gather(h_global * global_norm, (double)gamma[0], (double)gamma[1],
+                                    hp->ema_beta, step == 1, &mu_new, &var_new);
+                gamma[0] = (float)mu_new;
+                gamma[1] = (float)var_new;
+            }
         }
     }
 

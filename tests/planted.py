@@ -50,6 +50,20 @@ MISTAKES = [
     ("updates read bf16 bits as integers", "return (double)oracle_bf16_to_float(((const uint16_t *)g)[j]);",
      "return (double)(((const uint16_t *)g)[j]);"),
     ("weight decay dropped from Lion", "th = th - hp->lr * (sgn + hp->weight_decay * th);", "th = th - hp->lr * sgn;"),
+    ("ZClip: clip on >= instead of >", "int active = (z > z_thres);", "int active = (z >= z_thres);"),
+    ("ZClip: threshold without the reciprocal adjustment", "double xi = z_thres * z_thres / z;", "double xi = z_thres;"),
+    ("ZClip: z-score from the variance, not the deviation", "double sigma = sqrt(var_prev);", "double sigma = var_prev;"),
+    ("ZClip: statistics fed the unclipped norm", "double clipped_norm = active ? tau : norm;\n    double mu = alpha",
+     "double clipped_norm = norm;\n    double mu = alpha"),
+    ("ZClip: variance around the old mean", "double dev = clipped_norm - mu;\n    *h = coef;", "double dev = clipped_norm - mu_prev;\n    *h = coef;"),
+    ("ZClip: variance without the square", "*var_new = alpha * var_prev + (1.0 - alpha) * dev * dev;\n    *clipped = active;",
+     "*var_new = alpha * var_prev + (1.0 - alpha) * dev;\n    *clipped = active;"),
+    ("ZClip: EMA weights swapped", "double mu = alpha * mu_prev + (1.0 - alpha) * clipped_norm;\n    double dev = clipped_norm - mu;\n    *h = coef;",
+     "double mu = (1.0 - alpha) * mu_prev + alpha * clipped_norm;\n    double dev = clipped_norm - mu;\n    *h = coef;"),
+    ("ZClip: coefficient inverted", "double coef = active ? tau / norm : 1.0;", "double coef = active ? norm / tau : 1.0;"),
+    ("ZClip: first step averages instead of setting", "    if (first_step) {\n        *mu_new = clipped_norm;\n        *var_new = 0.0;\n        return;\n    }\n", ""),
+    ("ZClip: statistics gathered from the raw norm during the first steps", "oracle_zclip_gather(h_global * global_norm,", "oracle_zclip_gather(global_norm,"),
+    ("ZClip: z-score rule already during the first steps", "} else if (mode == 3 && !warmup) {", "} else if (mode == 3) {"),
 ]
 
 

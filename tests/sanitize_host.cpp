@@ -13,6 +13,7 @@ typedef struct {
     double lr, beta1, beta2, eps, weight_decay, lambda_rel, ema_beta, lambda_abs;
     int64_t t_start;
     int32_t optimizer, grad_dtype, clip_mode, reserved;
+    double z_thres;
 } oracle_step_hyper;
 int oracle_adagc_step(int64_t n_tensors, const int64_t* numel, float* const* theta, const void* const* grad,
                       float* const* m, float* const* v, uint16_t* const* theta_bf16, float* gamma,
@@ -72,7 +73,7 @@ int main()
     // ---- oracle: several steps through warm-up, AdaGC, the global modes, AdamW and Lion, fp32 and bf16
     for (int optimizer = 0; optimizer < 2; ++optimizer)
         for (int dtype = 0; dtype < 2; ++dtype)
-            for (int mode = 0; mode < 3; ++mode) {
+            for (int mode = 0; mode < 4; ++mode) {
                 std::vector<std::vector<float>> theta, m, v, gf;
                 std::vector<std::vector<uint16_t>> gb, copy;
                 std::vector<float*> p_theta, p_m, p_v;
@@ -94,7 +95,7 @@ int main()
                 std::vector<float> gamma(n, 0.f);
                 std::vector<double> norm(n), coef(n);
                 std::vector<uint8_t> clipped(n);
-                oracle_step_hyper hp = {3e-4, 0.9, 0.95, 1e-8, 0.1, 1.04, 0.99, 0.05, 2, optimizer, dtype, mode, 0};
+                oracle_step_hyper hp = {3e-4, 0.9, 0.95, 1e-8, 0.1, 1.04, 0.99, 0.05, 2, optimizer, dtype, mode, 0, 2.0};
                 for (int64_t step = 1; step <= 6; ++step) {
                     const float scale = (step == 4) ? 30.f : 1.f;
                     for (int64_t i = 0; i < n; ++i)

@@ -677,3 +677,149 @@ def test_state_norms_after_first_adamw_step_closed_form():
     assert mn == pytest.approx((1 - f32(0.9)) * np.linalg.norm(gd), rel=1e-6)
     assert vn == pytest.approx((1 - f32(0.95)) * np.linalg.norm(gd * gd), rel=1e-6)
     assert un == pytest.approx(f32(3e-4) * math.sqrt(n), rel=1e-4)
+
+
+# ------------------------------------------------------------------ ZClip (Table 2; appendix "Clipping Hyper-Parameters")
+# The paper prints the coefficient, tau and z; the adjustment function xi and the statistics' update are a
+# reading (see oracle_zclip_rule): "parity unpinned by the paper" for those, pinned here by hand values,
+# invariants and closed forms.
+
+def test_zclip_paper_hyper_parameters():
+    paper = golden()
+    assert paper["zclip_alpha"] == 0.97 and paper["zclip_z_thres"] == 2.0
+    assert oracle.Hyper().z_thres == paper["zclip_z_thres"]
+
+
+def test_zclip_rule_hand_values_dyadic():
+    # mu 4, sigma 1, norm 8: z = 4 > 2, xi = 2^2/4 = 1, tau = 5, h = 5/8; alpha 1/2: mu' = 4.5, var' = .5 + .5*(.5)^2
+    assert oracle.zclip_rule(8.0, 4.0, 1.0, 0.5, 2.0) == (0.625, 4.5, 0.625, True)
+    # norm 6: z = 2 is not above the threshold: no clip, the statistics take the raw norm
+    assert oracle.zclip_rule(6.0, 4.0, 1.0, 0.5, 2.0) == (1.0, 5.0, 1.0, False)
+    # sigma = 2 (var 4), mu 1, norm 17: z = 8, xi = 9/8 with z_thres 3, tau = 1 + 9/4 = 3.25, h = 3.25/17
+    h, mu, var, c = oracle.zclip_rule(17.0, 1.0, 4.0, 0.75, 3.0)
+    assert c and h == 3.25 / 17.0 and mu == 0.75 + 0.25 * 3.25 and var == 0.75 * 4.0 + 0.25 * (3.25 - mu) ** 2
+    # a norm below the mean is never clipped
+    assert oracle.zclip_rule(1.0, 4.0, 1.0, 0.5, 2.0)[::3] == (1.0, False)
+
+
+def test_zclip_threshold_as_table_2_prints_it():
+    """tau = mu + xi(z) sigma with z = (norm - mu)/sigma and h = min{1, tau/norm}; with the reciprocal xi,
+    tau lies strictly between the mean and the activation boundary mu + z_thres sigma, falls as the norm
+    grows, and meets the norm at the boundary (h continuous)."""
+    rng = np.random.default_rng(21)
+    for _ in range(300):
+        mu, sigma, zt = rng.uniform(0.1, 10), rng.uniform(0.01, 3), rng.uniform(0.5, 4)
+        norm = mu + sigma * zt * rng.uniform(1.0001, 30)
+        h, mu_new, var_new, c = oracle.zclip_rule(norm, mu, sigma * sigma, 0.97, zt)
+        assert c and 0.0 < h < 1.0
+        tau = h * norm
+        z = (norm - mu) / sigma
+        assert abs(tau - (mu + zt * zt / z * sigma)) <= 1e-12 * tau
+        assert mu < tau < mu + zt * sigma < norm
+        h2 = oracle.zclip_rule(norm * 1.5, mu, sigma * sigma, 0.97, zt)[0]
+        assert h2 * norm * 1.5 < tau                       # further out, lower threshold
+        assert abs(mu_new - (0.97 * mu + 0.03 * tau)) <= 1e-12 * mu_new          # statistics take the clipped norm
+    # continuity at the boundary, from above
+    h = oracle.zclip_rule(4.0 + 2.0 * (1 + 1e-9), 4.0, 1.0, 0.97, 2.0)[0]
+    assert 1.0 - 1e-8 < h < 1.0
+
+
+def test_zclip_scale_invariance():
+    for c in (0.125, 8.0, 1024.0):
+        a = oracle.zclip_rule(9.0, 3.0, 2.25, 0.75, 2.0)
+        b = oracle.zclip_rule(9.0 * c, 3.0 * c, 2.25 * c * c, 0.75, 2.0)
+        assert a[0] == b[0] and a[3] == b[3] and b[1] == a[1] * c and b[2] == a[2] * c * c
+
+
+def test_zclip_zero_variance_needs_no_special_case():
+    assert oracle.zclip_rule(6.0, 4.0, 0.0, 0.5, 2.0) == (4.0 / 6.0, 4.0, 0.0, True)      # tau = mu
+    assert oracle.zclip_rule(4.0, 4.0, 0.0, 0.5, 2.0) == (1.0, 4.0, 0.0, False)            # z = 0/0
+    assert oracle.zclip_rule(3.0, 4.0, 0.0, 0.5, 2.0) == (1.0, 3.5, 0.125, False)
+    h, mu, var, c = oracle.zclip_rule(float("nan"), 4.0, 1.0, 0.5, 2.0)
+    assert h == 1.0 and not c and math.isnan(mu)
+
+
+def test_zclip_statistics_are_exponential_moving_mean_and_variance():
+    """Never clipped (z_thres = inf): mu_k = a^k mu_0 + (1-a) sum a^(k-j) n_j, and the variance follows
+    var_k = a var_{k-1} + (1-a)(n_k - mu_k)^2, in exact rationals on dyadic inputs."""
+    from fractions import Fraction as F
+    a = F(3, 4)
+    norms = [F(5), F(3, 2), F(9, 4), F(7), F(1, 8), F(33, 16)]
+    mu, var = F(2), F(1, 4)
+    fmu, fvar = float(mu), float(var)
+    for k, n in enumerate(norms):
+        mu = a * mu + (1 - a) * n
+        var = a * var + (1 - a) * (n - mu) ** 2
+        h, fmu, fvar, c = oracle.zclip_rule(float(n), fmu, fvar, float(a), float("inf"))
+        assert h == 1.0 and not c
+        assert fmu == float(mu) and fvar == float(var)
+    closed = a ** len(norms) * F(2) + (1 - a) * sum(a ** (len(norms) - 1 - j) * n for j, n in enumerate(norms))
+    assert mu == closed
+    # the mean is the library's exponentially weighted mean (adjust=False) of the same sequence
+    import pandas as pd
+    ew = pd.Series([2.0] + [float(n) for n in norms]).ewm(alpha=float(1 - a), adjust=False).mean().iloc[-1]
+    assert abs(ew - fmu) <= 1e-15 * fmu
+    # a constant norm: the mean converges to it geometrically and the variance decays
+    mu_c, var_c = 1.0, 1.0
+    for k in range(1, 60):
+        _, mu_c, var_c, _ = oracle.zclip_rule(3.0, mu_c, var_c, 0.5, float("inf"))
+        assert abs(mu_c - (3.0 - 2.0 * 0.5 ** k)) <= 1e-15
+    assert var_c < 1e-15
+
+
+def test_zclip_gather():
+    assert oracle.zclip_gather(5.0, 123.0, 456.0, 0.5, True) == (5.0, 0.0)             # first step: set
+    assert oracle.zclip_gather(7.0, 5.0, 0.0, 0.5, False) == (6.0, 0.5)                # then the same EMA
+    assert oracle.zclip_gather(7.0, 5.0, 0.0, 0.5, False) == oracle.zclip_rule(7.0, 5.0, 0.0, 0.5, float("inf"))[1:3]
+
+
+def test_zclip_step_hand_worked():
+    """[3,4] and [12]: global norm 13.  mu 5, var 4 (sigma 2), z_thres 2: z = 4, xi = 1, tau = 7, h = 7/13 for
+    every tensor; alpha 1/2: mu' = 6, var' = 2 + .5*1 = 2.5.  The update is plain AdamW on h*g."""
+    theta = [np.array([1.0, -1.0], np.float32), np.array([0.5], np.float32)]
+    g = [np.array([3.0, 4.0], np.float32), np.array([12.0], np.float32)]
+    hp = oracle.Hyper(clip_mode=oracle.MODE_ZCLIP, ema_beta=0.5, z_thres=2.0, t_start=0)
+    m, v = _lists([np.zeros(2), np.zeros(1)]), _lists([np.zeros(2), np.zeros(1)])
+    state = np.array([5.0, 4.0], np.float32)
+    th = [x.copy() for x in theta]
+    norms, coefs, clipped = oracle.adagc_step(th, g, m, v, state, hp, 3)
+    assert norms.tolist() == [5.0, 12.0] and clipped.tolist() == [1, 1]
+    assert coefs.tolist() == [7.0 / 13.0, 7.0 / 13.0]
+    assert state.tolist() == [6.0, 2.5]
+    for i in range(2):
+        t2, m2, v2 = theta[i].copy(), np.zeros_like(theta[i]), np.zeros_like(theta[i])
+        oracle.adamw_update(t2, m2, v2, g[i], 7.0 / 13.0, hp, 3)
+        assert np.array_equal(t2, th[i]) and np.array_equal(m2, m[i]) and np.array_equal(v2, v[i])
+    # an ordinary step (z = 0.5): nothing clipped, statistics move
+    state = np.array([12.0, 4.0], np.float32)
+    norms, coefs, clipped = oracle.adagc_step(th, g, m, v, state, hp, 4)
+    assert coefs.tolist() == [1.0, 1.0] and clipped.tolist() == [0, 0]
+    assert state.tolist() == [12.5, 2.0 + 0.5 * 0.25]
+
+
+def test_zclip_step_gathers_statistics_under_globalgc_first():
+    """Steps 1..t_start: Eq. 2's coefficient, and the statistics gathered from the globally clipped norm
+    (set on step 1, moving averages afterwards); the z-score rule starts on step t_start + 1."""
+    g = [np.array([3.0, 4.0], np.float32), np.array([12.0], np.float32)]
+    hp = oracle.Hyper(clip_mode=oracle.MODE_ZCLIP, ema_beta=0.5, z_thres=2.0, t_start=2, lambda_abs=6.5)
+    th, m, v = _lists([np.ones(2), np.ones(1)]), _lists([np.zeros(2), np.zeros(1)]), _lists([np.zeros(2), np.zeros(1)])
+    state = np.array([99.0, 99.0], np.float32)
+    _, coefs, clipped = oracle.adagc_step(th, g, m, v, state, hp, 1)
+    assert coefs.tolist() == [0.5, 0.5] and clipped.tolist() == [1, 1] and state.tolist() == [6.5, 0.0]
+    g2 = [x * np.float32(0.5) for x in g]                 # norm 6.5: not clipped by lambda_abs = 6.5
+    _, coefs, clipped = oracle.adagc_step(th, g2, m, v, state, hp, 2)
+    assert coefs.tolist() == [1.0, 1.0] and state.tolist() == [6.5, 0.0]
+    _, coefs, clipped = oracle.adagc_step(th, g, m, v, state, hp, 3)   # z = +inf: tau = mu
+    assert coefs.tolist() == [0.5, 0.5] and clipped.tolist() == [1, 1] and state.tolist() == [6.5, 0.0]
+
+
+def test_zclip_on_a_list_sees_only_the_global_norm():
+    rng = np.random.default_rng(8)
+    parts = [rng.standard_normal(n).astype(np.float32) for n in (5, 1, 9)]
+    whole = [np.concatenate(parts)]
+    hp = oracle.Hyper(clip_mode=oracle.MODE_ZCLIP, t_start=0, ema_beta=0.97)
+    s1, s2 = np.array([1.0, 0.04], np.float32), np.array([1.0, 0.04], np.float32)
+    a = oracle.adagc_step(_lists([np.zeros(5), np.zeros(1), np.zeros(9)]), parts, _lists([np.zeros(5), np.zeros(1), np.zeros(9)]),
+                          _lists([np.zeros(5), np.zeros(1), np.zeros(9)]), np.concatenate([s1, [0]]).astype(np.float32), hp, 2)
+    b = oracle.adagc_step(_lists([np.zeros(15)]), whole, _lists([np.zeros(15)]), _lists([np.zeros(15)]), s2, hp, 2)
+    assert a[1][0] == a[1][1] == a[1][2] == b[1][0] and b[2][0] == 1

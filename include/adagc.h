@@ -61,6 +61,16 @@ extern "C" {
 #define ADAGC_MODE_GLOBAL_ADAGC  2  /* one adaptive threshold for the whole model (ablation "adaptive but
                                        non-local", "Ablation Study", Sec. 5.6): Eq. 3 and the warm-up branch applied to the
                                        model's norm; its single gamma lives in ema_norms[0] */
+#define ADAGC_MODE_ZCLIP         3  /* ZClip, a baseline of the paper's comparison (Table 2: h = min{1, tau/||g||},
+                                       tau = mu + xi(z) sigma, z = (||g|| - mu)/sigma on the model's norm; appendix
+                                       "Clipping Hyper-Parameters": alpha 0.97, z_thres 2.0).  The paper leaves xi and
+                                       the statistics' update undefined; this library takes xi(z) = z_thres^2 / z,
+                                       active for z > z_thres, and feeds the clipped norm nhat to
+                                       mu' = alpha mu + (1-alpha) nhat, var' = alpha var + (1-alpha)(nhat - mu')^2.
+                                       alpha is ema_beta; mu lives in ema_norms[0], var in ema_norms[1] (so
+                                       ema_norms needs at least 2 entries).  Steps 1..t_start only gather the
+                                       statistics under GlobalGC (Eq. 2 with lambda_abs): step 1 sets mu to its
+                                       clipped norm and var to 0 */
 
 typedef struct adagc_ctx adagc_ctx; /* opaque; created by adagc_create, freed by adagc_destroy */
 
@@ -112,6 +122,7 @@ typedef struct {
     int32_t t_start;       /* number of warm-up steps: steps 1..t_start take the warm-up branch.
                               0 = never (ema_norms must then be pre-filled by the caller) */
     int32_t clip_mode;     /* ADAGC_MODE_*; 0 = the paper's method */
+    float   z_thres;       /* ADAGC_MODE_ZCLIP only: z-score threshold, > 0 (+inf: never clip); ignored otherwise */
 } adagc_hyper;
 
 /* Device-resident inputs of adagc_step_graph: the hyper-parameters and the step number are read by the
@@ -189,7 +200,8 @@ int adagc_set_param_copies(adagc_ctx* ctx, void* const* params_bf16);
  *   exp_avg     HOST array of n_tensors DEVICE pointers, fp32, updated in place      (m)
  *   exp_avg_sq  HOST array of n_tensors DEVICE pointers, fp32, updated in place      (v); NULL for Lion
  *   ema_norms   DEVICE fp32[n_tensors], updated in place                              (gamma_i);
- *               ADAGC_MODE_GLOBAL_ADAGC uses element 0 only, ADAGC_MODE_GLOBALGC none
+ *               ADAGC_MODE_GLOBAL_ADAGC uses element 0 only, ADAGC_MODE_GLOBALGC none,
+ *               ADAGC_MODE_ZCLIP elements 0 and 1 (fp32[max(n_tensors, 2)])
  *   hp          HOST hyper-parameters of this step
  *   step        1-based t of Alg. 1: drives the bias correction and the warm-up test
  *   stream      hipStream_t (NULL = the default stream)

@@ -21,7 +21,7 @@ ADAGC_ERR_STATE = -5
 
 ADAGC_OPT_ADAMW, ADAGC_OPT_LION = 0, 1
 ADAGC_GRAD_F32, ADAGC_GRAD_BF16 = 0, 1
-ADAGC_MODE_ADAGC, ADAGC_MODE_GLOBALGC, ADAGC_MODE_GLOBAL_ADAGC = 0, 1, 2
+ADAGC_MODE_ADAGC, ADAGC_MODE_GLOBALGC, ADAGC_MODE_GLOBAL_ADAGC, ADAGC_MODE_ZCLIP = 0, 1, 2, 3
 
 EXPORTS = [
     "adagc_chunk_elems", "adagc_build_segment_table", "adagc_build_visiting_order", "adagc_create", "adagc_destroy",
@@ -47,7 +47,8 @@ class adagc_hyper(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
                 ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
                 ("lambda_rel", ctypes.c_float), ("ema_beta", ctypes.c_float),
-                ("lambda_abs", ctypes.c_float), ("t_start", ctypes.c_int32), ("clip_mode", ctypes.c_int32)]
+                ("lambda_abs", ctypes.c_float), ("t_start", ctypes.c_int32), ("clip_mode", ctypes.c_int32),
+                ("z_thres", ctypes.c_float)]
 
 
 class adagc_step_params(ctypes.Structure):
@@ -165,7 +166,7 @@ def adagc_build_segment_table(numels, chunk_elems=None):
 
 
 def step_params_bytes(hyper, step):
-    """The 48 bytes of an adagc_step_params, ready to be copied into device memory."""
+    """The bytes of an adagc_step_params, ready to be copied into device memory."""
     return bytes(adagc_step_params(hyper, int(step)))
 
 
@@ -242,7 +243,7 @@ class AdaGC:
     # -- adagc_step_graph
     def step_graph(self, params, grads, exp_avg, exp_avg_sq, ema_norms, step_params, stream=None):
         """As step(), with hyper-parameters and step number read on the GPU from `step_params`: a device
-        tensor of 48 bytes holding an adagc_step_params (see step_params_bytes)."""
+        tensor of sizeof(adagc_step_params) = 56 bytes holding an adagc_step_params (see step_params_bytes)."""
         p, g, m = (ptr_array(x) for x in (params, grads, exp_avg))
         v = ptr_array(exp_avg_sq) if exp_avg_sq is not None else None
         _check(lib().adagc_step_graph(self._ctx, p, g, m, v, ema_norms.data_ptr(), step_params.data_ptr(),
@@ -292,6 +293,6 @@ class AdaGC:
 
 
 def make_hyper(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, lambda_rel=1.04,
-               ema_beta=0.99, lambda_abs=float("inf"), t_start=1, clip_mode=ADAGC_MODE_ADAGC):
+               ema_beta=0.99, lambda_abs=float("inf"), t_start=1, clip_mode=ADAGC_MODE_ADAGC, z_thres=2.0):
     return adagc_hyper(lr, beta1, beta2, eps, weight_decay, lambda_rel, ema_beta, lambda_abs, int(t_start),
-                       int(clip_mode))
+                       int(clip_mode), z_thres)

@@ -49,9 +49,11 @@ struct RuleArgs {
     double lambda_rel;
     double ema_beta;
     double lambda_abs;
+    double z_thres;      // ZClip
     int    first_step;   // step == 1: gamma is set, not min-ed
     int    warmup;       // step <= t_start
     int    mode;         // ADAGC_MODE_*
+    int    pad;
 };
 
 // Scalars of the elementwise update, precomputed on the host in double from the caller's fp32
@@ -105,7 +107,8 @@ inline bool hyper_ok(const adagc_hyper& h, int optimizer)
     if (!(h.lambda_rel >= 0.0f)) return false;    // +inf allowed, NaN not
     if (!(h.lambda_abs > 0.0f)) return false;     // +inf allowed, NaN not
     if (h.t_start < 0) return false;
-    if (h.clip_mode < ADAGC_MODE_ADAGC || h.clip_mode > ADAGC_MODE_GLOBAL_ADAGC) return false;
+    if (h.clip_mode < ADAGC_MODE_ADAGC || h.clip_mode > ADAGC_MODE_ZCLIP) return false;
+    if (h.clip_mode == ADAGC_MODE_ZCLIP && !(h.z_thres > 0.0f)) return false;   // +inf allowed, NaN not
     return true;
 }
 
@@ -117,6 +120,8 @@ inline void host_step_scalars(const adagc_hyper& hp, int64_t step, RuleArgs& r, 
     r.lambda_rel = (double)hp.lambda_rel;
     r.ema_beta = (double)hp.ema_beta;
     r.lambda_abs = (double)hp.lambda_abs;
+    r.z_thres = (double)hp.z_thres;
+    r.pad = 0;
     r.first_step = (step == 1) ? 1 : 0;
     r.warmup = ((step - 1) < (int64_t)hp.t_start) ? 1 : 0;   // steps 1..t_start
     r.mode = hp.clip_mode;

@@ -277,7 +277,8 @@ __global__ __launch_bounds__(kBlock) void tensor_sumsq_kernel(DeviceTables t)
 // Global stage 2: the model's norm over all tensors (fixed order) and one coefficient for the
 // whole model.  Warm-up steps and the GlobalGC mode use Eq. 2; the Global AdaGC mode applies Eq. 3
 // (and, during warm-up, the running minimum of Alg. 1) to the model's norm with the single gamma
-// kept in ema[0].
+// kept in ema[0]; the ZClip mode applies Table 2's z-score rule with its mean in ema[0] and its
+// variance in ema[1].
 __device__ __forceinline__ void global_rule(const DeviceTables& t, float* ema, const RuleArgs& r, double* wave_sums)
 {
     const int tid = threadIdx.x;
@@ -302,6 +303,23 @@ __device__ __forceinline__ void global_rule(const DeviceTables& t, float* ema, c
         ema[0] = (float)__dadd_rn(__dmul_rn(r.ema_beta, gamma_prev),
                                   __dmul_rn(__dsub_rn(1.0, r.ema_beta), clipped_norm));
         clipped = active;
+    } else if (r.mode == ADAGC_MODE_ZCLIP && !r.warmup) {
+        // Table 2's ZClip row on the model's norm: z-score against the moving mean and deviation,
+        // threshold mu + (z_thres^2 / z) sigma, statistics fed the clipped norm.
+        const double mu_prev = (double)ema[0], var_prev = (double)ema[1];
+        const double sigma = sqrt(var_prev);
+        const double z = __ddiv_rn(__dsub_rn(gnorm, mu_prev), sigma);
+        active = z > r.z_thres;                                   // false for NaN (sigma = 0 and norm = mu)
+        const double xi = __ddiv_rn(__dmul_rn(r.z_thres, r.z_thres), z);
+        const double tau = __dadd_rn(mu_prev, __dmul_rn(xi, sigma));
+        h = active ? __ddiv_rn(tau, gnorm) : 1.0;
+        const double clipped_norm = active ? tau : gnorm;
+        const double mu = __dadd_rn(__dmul_rn(r.ema_beta, mu_prev), __dmul_rn(__dsub_rn(1.0, r.ema_beta), clipped_norm));
+        const double dev = __dsub_rn(clipped_norm, mu);
+        ema[0] = (float)mu;
+        ema[1] = (float)__dadd_rn(__dmul_rn(r.ema_beta, var_prev),
+                                  __dmul_rn(__dmul_rn(__dsub_rn(1.0, r.ema_beta), dev), dev));
+        clipped = active;
     } else {
         active = gnorm > r.lambda_abs;
         h = active ? __ddiv_rn(r.lambda_abs, gnorm) : 1.0;
@@ -312,6 +330,19 @@ __device__ __forceinline__ void global_rule(const DeviceTables& t, float* ema, c
             double gamma_new = clipped_norm;
             if (!r.first_step) gamma_new = clipped_norm < gamma_prev ? clipped_norm : gamma_prev;
             ema[0] = (float)gamma_new;
+        }
+        if (r.mode == ADAGC_MODE_ZCLIP) {
+            // steps that only gather the statistics: set on the first step, moving averages afterwards
+            const double clipped_norm = __dmul_rn(h, gnorm);
+            double mu = clipped_norm, var = 0.0;
+            if (!r.first_step) {
+                const double mu_prev = (double)ema[0], var_prev = (double)ema[1];
+                mu = __dadd_rn(__dmul_rn(r.ema_beta, mu_prev), __dmul_rn(__dsub_rn(1.0, r.ema_beta), clipped_norm));
+                const double dev = __dsub_rn(clipped_norm, mu);
+                var = __dadd_rn(__dmul_rn(r.ema_beta, var_prev), __dmul_rn(__dmul_rn(__dsub_rn(1.0, r.ema_beta), dev), dev));
+            }
+            ema[0] = (float)mu;
+            ema[1] = (float)var;
         }
     }
     t.global[0] = total;
@@ -366,13 +397,16 @@ __global__ void prepare_step_kernel(DeviceTables t, const adagc_step_params* par
     auto finite = [](float x) { return fabsf(x) <= 3.402823466e+38f; };
     bool ok = step >= 1 && finite(hp.lr) && finite(hp.weight_decay) && unit(hp.beta1) && unit(hp.beta2) &&
               unit(hp.ema_beta) && hp.lambda_rel >= 0.0f && hp.lambda_abs > 0.0f && hp.t_start >= 0 &&
-              hp.clip_mode >= ADAGC_MODE_ADAGC && hp.clip_mode <= ADAGC_MODE_GLOBAL_ADAGC;
+              hp.clip_mode >= ADAGC_MODE_ADAGC && hp.clip_mode <= ADAGC_MODE_ZCLIP &&
+              (hp.clip_mode != ADAGC_MODE_ZCLIP || hp.z_thres > 0.0f);
     if (optimizer == ADAGC_OPT_ADAMW) ok = ok && hp.eps >= 0.0f && finite(hp.eps);
     StepScalars sc;
     const double lr = hp.lr, b1 = hp.beta1, b2 = hp.beta2, wd = hp.weight_decay, tt = (double)step;
     sc.r.lambda_rel = (double)hp.lambda_rel;
     sc.r.ema_beta = (double)hp.ema_beta;
     sc.r.lambda_abs = (double)hp.lambda_abs;
+    sc.r.z_thres = (double)hp.z_thres;
+    sc.r.pad = 0;
     sc.r.first_step = (step == 1) ? 1 : 0;
     sc.r.warmup = ((step - 1) < (int64_t)hp.t_start) ? 1 : 0;
     sc.r.mode = hp.clip_mode;

@@ -29,7 +29,8 @@ BAND = 1e-6
 def oracle_hyper(hp, optimizer, grad_dtype):
     return oracle.Hyper(lr=hp.lr, beta1=hp.beta1, beta2=hp.beta2, eps=hp.eps, weight_decay=hp.weight_decay,
                         lambda_rel=hp.lambda_rel, ema_beta=hp.ema_beta, lambda_abs=hp.lambda_abs,
-                        t_start=hp.t_start, optimizer=optimizer, grad_dtype=grad_dtype, clip_mode=hp.clip_mode)
+                        t_start=hp.t_start, optimizer=optimizer, grad_dtype=grad_dtype, clip_mode=hp.clip_mode,
+                        z_thres=hp.z_thres)
 
 
 def rms(x):

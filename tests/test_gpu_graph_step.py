@@ -1,5 +1,6 @@
 """GPU parity of adagc_step_graph: the step whose hyper-parameters and step number are read on the device,
 eagerly and as a HIP graph recorded once and replayed for later steps, against the CPU oracle."""
+import ctypes
 import math
 
 import numpy as np
@@ -53,7 +54,7 @@ def test_device_scalars_step_matches_oracle_eagerly(optimizer):
     run = P.Run(w, optimizer=optimizer)
     model_norm = math.sqrt(sum(float(s) ** 2 * k for s, k in zip(w.sigma, w.numels)))
     hp = B.make_hyper(lr=1e-4 if lion else 3e-4, beta2=0.99 if lion else 0.95, t_start=2, lambda_abs=0.5 * model_norm)
-    sp = torch.zeros(48, dtype=torch.uint8, device=DEV)
+    sp = torch.zeros(ctypes.sizeof(B.adagc_step_params), dtype=torch.uint8, device=DEV)
     for step in range(1, 8):
         grads = w.make_grads(step, DEV)
         _mirror(run)
@@ -71,7 +72,7 @@ def test_device_scalars_step_matches_oracle_eagerly(optimizer):
         assert differ <= 4
 
 
-@pytest.mark.parametrize("mode", [B.ADAGC_MODE_ADAGC, B.ADAGC_MODE_GLOBAL_ADAGC])
+@pytest.mark.parametrize("mode", [B.ADAGC_MODE_ADAGC, B.ADAGC_MODE_GLOBAL_ADAGC, B.ADAGC_MODE_ZCLIP])
 def test_graph_recorded_once_replays_for_later_steps(mode):
     """One eager step, then the step is captured into a graph ONCE (at a warm-up step) and replayed for steps
     3..9 with new gradients, a changing learning rate and the step number all updated in device memory between
@@ -82,8 +83,9 @@ def test_graph_recorded_once_replays_for_later_steps(mode):
     run = P.Run(w)
     model_norm = math.sqrt(sum(float(s) ** 2 * k for s, k in zip(w.sigma, w.numels)))
     def hyper(step):
-        return B.make_hyper(lr=3e-4 * (1.0 - 0.05 * step), t_start=3, lambda_abs=2.0 * model_norm, clip_mode=mode)
-    sp = torch.zeros(48, dtype=torch.uint8, device=DEV)
+        return B.make_hyper(lr=3e-4 * (1.0 - 0.05 * step), t_start=3, lambda_abs=2.0 * model_norm, clip_mode=mode,
+                            ema_beta=0.97 if mode == B.ADAGC_MODE_ZCLIP else 0.99)
+    sp = torch.zeros(ctypes.sizeof(B.adagc_step_params), dtype=torch.uint8, device=DEV)
     grads = w.make_grads(1, DEV)                       # static buffers: refilled in place before every step
     name = "graph-mode%d" % mode
 
@@ -132,7 +134,7 @@ def test_device_side_validation_and_capture_rules():
     w = _workload()
     run = P.Run(w, mirror=False)
     hp = B.make_hyper()
-    sp = torch.zeros(48, dtype=torch.uint8, device=DEV)
+    sp = torch.zeros(ctypes.sizeof(B.adagc_step_params), dtype=torch.uint8, device=DEV)
     grads = w.make_grads(1, DEV)
     _set(sp, hp, 1)
     run.ctx.step_graph(run.params, grads, run.m, run.v, run.gamma, sp)

@@ -301,6 +301,39 @@ def test_global_adagc_mode_single_adaptive_threshold():
     run.compare_state("global-adagc")
 
 
+def test_zclip_mode_z_score_of_the_global_norm():
+    """Table 2's ZClip row: three steps that gather the mean and variance of the model's norm under Eq. 2,
+    then the z-score rule.  The model's gradient scale wanders by a few per cent and jumps on steps 6 and 11,
+    so that clipped and unclipped steps both occur; the state is (mu, var) in ema_norms[0:2]."""
+    specs = W.gpt2_like_list(2, 128, 512, 1024, 0)
+    every = np.arange(len(specs))
+    scale = {1: 1.3, 2: 1.0, 3: 0.9, 4: 1.05, 5: 0.97, 6: 4.0, 7: 1.0, 8: 0.8, 9: 1.02, 10: 0.99, 11: 1.6, 12: 1.0}
+    w = W.Workload(specs, sigma_lo=1e-2, sigma_hi=1e-1, spikes={t: (every, f) for t, f in scale.items()})
+    run = P.Run(w)
+    g2 = w.make_grads(2, DEV)
+    total = math.sqrt(sum(float((g.double() ** 2).sum()) for g in g2))
+    hp = B.make_hyper(lambda_abs=1.2 * total, t_start=3, clip_mode=B.ADAGC_MODE_ZCLIP, ema_beta=0.97, z_thres=2.0)
+    run.gamma[2:].fill_(7.0)
+    run.h_gamma[2:] = 7.0
+    seen = []
+    for step in range(1, 13):
+        grads = w.make_grads(step, DEV)
+        norms, coefs, flags = run.gpu_step(grads, hp, step)
+        rn, rc, rf, _ = run.oracle_step([to_numpy(g) for g in grads], hp, step)
+        P.check_scalars("zclip step %d" % step, norms, coefs, flags, to_numpy(run.gamma), rn, rc, rf, run.h_gamma)
+        assert len(set(coefs.tolist())) == 1 and len(set(flags.tolist())) == 1
+        seen.append(int(rf[0]))
+        say("zclip step %2d: h %.6f clipped %d mu %.6f var %.3e" % (step, rc[0], rf[0], run.h_gamma[0], run.h_gamma[1]))
+    assert seen[0] == 1 and seen[1] == 0 and seen[5] == 1 and seen[10] == 1 and 0 in seen[3:]
+    assert (to_numpy(run.gamma)[2:] == 7.0).all()
+    run.compare_state("zclip")
+    # the threshold must be positive (NaN and zero rejected before anything is enqueued)
+    for bad in (0.0, -1.0, float("nan")):
+        with pytest.raises(B.AdagcError) as e:
+            run.ctx.step(run.params, grads, run.m, run.v, run.gamma, B.make_hyper(clip_mode=B.ADAGC_MODE_ZCLIP, z_thres=bad), 13)
+        assert e.value.code == B.ADAGC_ERR_INVALID_ARG
+
+
 def _telemetry_case(optimizer, w, hp, name, **knobs):
     run = P.Run(w, optimizer=optimizer, telemetry=True, **knobs)
     plain = P.Run(w, optimizer=optimizer, mirror=False)
@@ -427,7 +460,7 @@ def test_step_errors_leave_state_untouched():
     assert code(lambda: run.ctx.step(run.params, grads, run.m, None, run.gamma, hp, 1)) == B.ADAGC_ERR_INVALID_ARG
     bad = B.make_hyper(beta1=1.0)
     assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, bad, 1)) == B.ADAGC_ERR_INVALID_ARG
-    bad = B.make_hyper(clip_mode=3)
+    bad = B.make_hyper(clip_mode=99)
     assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, bad, 1)) == B.ADAGC_ERR_INVALID_ARG
     bad = B.make_hyper(lambda_rel=float("nan"))
     assert code(lambda: run.ctx.step(run.params, grads, run.m, run.v, run.gamma, bad, 1)) == B.ADAGC_ERR_INVALID_ARG
@@ -638,16 +671,22 @@ def _teeth_scenarios():
     trajectory(P.Run(w), B.make_hyper(t_start=2, lambda_abs=0.5 * model_norm, eps=1e-3), 6, "teeth-adamw", lockstep=True)
     w = _ZeroHead(specs, spikes=spikes, grad_dtype=torch.bfloat16)
     trajectory(P.Run(w, optimizer="lion"), B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99), 5, "teeth-lion", lockstep=True)
+    # ZClip: two gathering steps (the first globally clipped), then clipped and unclipped z-score steps
+    every = np.arange(len(specs))
+    scale = {1: 1.5, 2: 1.0, 3: 0.9, 4: 3.0, 5: 1.0, 6: 0.8, 7: 1.1}
+    w = W.Workload(specs, spikes={t: (every, f) for t, f in scale.items()})
+    hp = B.make_hyper(t_start=2, lambda_abs=1.2 * model_norm, clip_mode=B.ADAGC_MODE_ZCLIP, ema_beta=0.75, z_thres=2.0)
+    trajectory(P.Run(w), hp, 7, "teeth-zclip", lockstep=True)
 
 
 def test_parity_comparisons_notice_a_wrong_oracle(tmp_path):
     """Plant each mistake of tests/planted.py in a copy of the CPU oracle (the GPU library is untouched) and run
     the scenarios: the comparison must fail for every mistake that changes what a step computes.  Two entries
     are left to the CPU pins: ties of the bf16 rounding (the copy is compared to within one bf16 ulp) and
-    '>=' for '>' (differs only at exact equality of norm and threshold)."""
+    '>=' for '>' in Eq. 3 and in ZClip (differs only at exact equality)."""
     import planted
     _teeth_scenarios()                                  # the real oracle agrees
-    cpu_only = {"bf16 ties always round up", "clip on >= instead of >"}
+    cpu_only = {"bf16 ties always round up", "clip on >= instead of >", "ZClip: clip on >= instead of >"}
     unnoticed = []
     for k, (what, _, _) in enumerate(planted.MISTAKES):
         if what in cpu_only:

@@ -640,7 +640,7 @@ def test_global_adagc_warmup_sets_then_minimises_the_single_gamma():
 def test_step_rejects_unknown_mode():
     theta, m, v = _lists([[1]]), _lists([[0]]), _lists([[0]])
     with pytest.raises(ValueError):
-        oracle.adagc_step(theta, _lists([[1]]), m, v, np.zeros(1, np.float32), Hyper(clip_mode=3), 1)
+        oracle.adagc_step(theta, _lists([[1]]), m, v, np.zeros(1, np.float32), Hyper(clip_mode=99), 1)
 
 
 # ------------------------------------------------------------------ state norms (Fig. 2 quantities)

@@ -26,6 +26,8 @@ MODE_ADAGC = 0          # Alg. 1
 MODE_GLOBALGC = 1       # Eq. 2 on every step
 MODE_GLOBAL_ADAGC = 2   # one adaptive threshold for the whole model ("Ablation Study", Sec. 5.6)
 MODE_ZCLIP = 3          # z-score clipping of the global norm (Table 2; appendix "Clipping Hyper-Parameters")
+MODE_AGC = 4            # update clipping by the weights' l2 norm (Table 2)
+MODE_CLIPPY = 5         # update clipping by the weights' l-infinity norm (Table 2)
 
 
 class _OptHyper(ctypes.Structure):
@@ -101,6 +103,18 @@ def _declare(L):
                                     ctypes.POINTER(dbl), ctypes.POINTER(i32)]
     L.oracle_zclip_gather.restype = None
     L.oracle_zclip_gather.argtypes = [dbl, dbl, dbl, dbl, i32, ctypes.POINTER(dbl), ctypes.POINTER(dbl)]
+    L.oracle_agc_coef.restype = dbl
+    L.oracle_agc_coef.argtypes = [dbl, dbl, dbl, ctypes.POINTER(i32)]
+    L.oracle_clippy_coef.restype = dbl
+    L.oracle_clippy_coef.argtypes = [dbl, dbl, dbl, dbl, dbl, ctypes.POINTER(i32)]
+    L.oracle_direction_norms.restype = None
+    L.oracle_direction_norms.argtypes = [vp, vp, vp, vp, i32, i64, ctypes.POINTER(_OptHyper), i32, i64,
+                                         ctypes.POINTER(dbl), ctypes.POINTER(dbl), ctypes.POINTER(dbl),
+                                         ctypes.POINTER(dbl)]
+    L.oracle_adamw_update_clipped.restype = None
+    L.oracle_adamw_update_clipped.argtypes = [vp, vp, vp, vp, i32, i64, dbl, ctypes.POINTER(_OptHyper), i64, vp]
+    L.oracle_lion_update_clipped.restype = None
+    L.oracle_lion_update_clipped.argtypes = [vp, vp, vp, i32, i64, dbl, ctypes.POINTER(_OptHyper), vp]
     L.oracle_adamw_update.restype = None
     L.oracle_adamw_update.argtypes = [vp, vp, vp, vp, i32, i64, dbl,
                                       ctypes.POINTER(_OptHyper), i64, vp]
@@ -237,6 +251,49 @@ def lion_update(theta, m, g, h, hyper, theta_bf16=None):
                              _check(g, g.dtype, n), _grad_dtype(g), n, float(h),
                              ctypes.byref(oh),
                              None if theta_bf16 is None else _check(theta_bf16, np.uint16, n))
+
+
+def agc_coef(theta_norm, delta_norm, lambda_rel):
+    """(coefficient, clipped) of Table 2's AGC row."""
+    c = ctypes.c_int()
+    return lib().oracle_agc_coef(theta_norm, delta_norm, lambda_rel, ctypes.byref(c)), bool(c.value)
+
+
+def clippy_coef(theta_inf, delta_inf, lambda_rel, lambda_abs, lr):
+    """(coefficient, clipped) of Table 2's Clippy row."""
+    c = ctypes.c_int()
+    return lib().oracle_clippy_coef(theta_inf, delta_inf, lambda_rel, lambda_abs, lr, ctypes.byref(c)), bool(c.value)
+
+
+def direction_norms(theta, m, v, g, hyper, t):
+    """(||theta||_2, ||Delta||_2, ||theta||_inf, ||Delta||_inf) for the direction this step's unclipped
+    gradient produces (AdamW: mhat/(sqrt(vhat)+eps); Lion, v=None: the sign of the interpolation)."""
+    n = theta.size
+    oh = hyper._opt()
+    out = [ctypes.c_double() for _ in range(4)]
+    lib().oracle_direction_norms(_check(theta, np.float32), _check(m, np.float32, n),
+                                 None if v is None else _check(v, np.float32, n), _check(g, g.dtype, n),
+                                 _grad_dtype(g), n, ctypes.byref(oh), int(hyper.optimizer), int(t),
+                                 *[ctypes.byref(x) for x in out])
+    return tuple(x.value for x in out)
+
+
+def adamw_update_clipped(theta, m, v, g, update_coef, hyper, t, theta_bf16=None):
+    n = theta.size
+    oh = hyper._opt()
+    lib().oracle_adamw_update_clipped(_check(theta, np.float32), _check(m, np.float32, n),
+                                      _check(v, np.float32, n), _check(g, g.dtype, n), _grad_dtype(g),
+                                      n, float(update_coef), ctypes.byref(oh), int(t),
+                                      None if theta_bf16 is None else _check(theta_bf16, np.uint16, n))
+
+
+def lion_update_clipped(theta, m, g, update_coef, hyper, theta_bf16=None):
+    n = theta.size
+    oh = hyper._opt()
+    lib().oracle_lion_update_clipped(_check(theta, np.float32), _check(m, np.float32, n),
+                                     _check(g, g.dtype, n), _grad_dtype(g), n, float(update_coef),
+                                     ctypes.byref(oh),
+                                     None if theta_bf16 is None else _check(theta_bf16, np.uint16, n))
 
 
 def state_norms(theta_before, theta_after, m, v=None):

@@ -20,6 +20,10 @@
  *     "Clipping Hyper-Parameters" gives alpha = 0.97 and z_thres = 2.0.  The
  *     adjustment function xi and the update of mu, sigma are not printed: see
  *     oracle_zclip_rule for the reading taken ("parity unpinned by the paper").
+ *   - AGC and Clippy (update-clipping baselines of the paper's comparison):
+ *     Table 2 prints min{1, lambda_rel ||theta||/||Delta||} (l2) and
+ *     min{1, (lambda_rel ||theta||_inf + lambda_abs)/(eta ||Delta||_inf)};
+ *     see oracle_agc_coef / oracle_clippy_coef for the readings taken
  *   - AdamW moments, bias correction, update ..... Alg. 1 (last four statements)
  * What the paper does not print and is taken from its citation:
  *   - Lion update rule (Chen et al., "Symbolic discovery of optimization
@@ -269,9 +273,11 @@ static double grad_at(const void *g, int64_t j, int grad_dtype)
     return (double)oracle_bf16_to_float(((const uint16_t *)g)[j]);
 }
 
-void oracle_adamw_update(float *theta, float *m, float *v, const void *g, int grad_dtype,
-                         int64_t numel, double h, const oracle_opt_hyper *hp, int64_t t,
-                         uint16_t *theta_bf16 /* may be NULL */)
+/* update_coef scales the optimizer's direction Delta = mhat/(sqrt(vhat)+eps) (update clipping, AGC and
+ * Clippy rows of Table 2); 1.0, an exact factor, everywhere else. */
+static void adamw_update_scaled(float *theta, float *m, float *v, const void *g, int grad_dtype,
+                                int64_t numel, double h, double update_coef, const oracle_opt_hyper *hp,
+                                int64_t t, uint16_t *theta_bf16 /* may be NULL */)
 {
     double bias1 = 1.0 - pow(hp->beta1, (double)t);
     double bias2 = 1.0 - pow(hp->beta2, (double)t);
@@ -283,7 +289,7 @@ void oracle_adamw_update(float *theta, float *m, float *v, const void *g, int gr
         double mhat = mj / bias1;
         double vhat = vj / bias2;
         double th = (double)theta[j];
-        th = th - hp->lr * hp->weight_decay * th - hp->lr * mhat / (sqrt(vhat) + hp->eps);
+        th = th - hp->lr * hp->weight_decay * th - update_coef * (hp->lr * mhat / (sqrt(vhat) + hp->eps));
         m[j] = (float)mj;
         v[j] = (float)vj;
         theta[j] = (float)th;
@@ -292,10 +298,25 @@ void oracle_adamw_update(float *theta, float *m, float *v, const void *g, int gr
     }
 }
 
+void oracle_adamw_update(float *theta, float *m, float *v, const void *g, int grad_dtype,
+                         int64_t numel, double h, const oracle_opt_hyper *hp, int64_t t,
+                         uint16_t *theta_bf16 /* may be NULL */)
+{
+    adamw_update_scaled(theta, m, v, g, grad_dtype, numel, h, 1.0, hp, t, theta_bf16);
+}
+
+/* The same step with the gradient unclipped and the direction scaled by update_coef. */
+void oracle_adamw_update_clipped(float *theta, float *m, float *v, const void *g, int grad_dtype,
+                                 int64_t numel, double update_coef, const oracle_opt_hyper *hp, int64_t t,
+                                 uint16_t *theta_bf16 /* may be NULL */)
+{
+    adamw_update_scaled(theta, m, v, g, grad_dtype, numel, 1.0, update_coef, hp, t, theta_bf16);
+}
+
 /* ---- Lion on the clipped gradient (rule imported from its own paper) ------- */
 
-void oracle_lion_update(float *theta, float *m, const void *g, int grad_dtype, int64_t numel,
-                        double h, const oracle_opt_hyper *hp, uint16_t *theta_bf16)
+static void lion_update_scaled(float *theta, float *m, const void *g, int grad_dtype, int64_t numel,
+                               double h, double update_coef, const oracle_opt_hyper *hp, uint16_t *theta_bf16)
 {
     ORACLE_PARALLEL_FOR
     for (int64_t j = 0; j < numel; ++j) {
@@ -304,13 +325,92 @@ void oracle_lion_update(float *theta, float *m, const void *g, int grad_dtype, i
         double c = hp->beta1 * mprev + (1.0 - hp->beta1) * ghat;
         double sgn = (c > 0.0) ? 1.0 : ((c < 0.0) ? -1.0 : 0.0);
         double th = (double)theta[j];
-        th = th - hp->lr * (sgn + hp->weight_decay * th);
+        th = th - hp->lr * (update_coef * sgn + hp->weight_decay * th);
         double mj = hp->beta2 * mprev + (1.0 - hp->beta2) * ghat;
         theta[j] = (float)th;
         m[j] = (float)mj;
         if (theta_bf16)
             theta_bf16[j] = oracle_float_to_bf16_rne(theta[j]);
     }
+}
+
+void oracle_lion_update(float *theta, float *m, const void *g, int grad_dtype, int64_t numel,
+                        double h, const oracle_opt_hyper *hp, uint16_t *theta_bf16)
+{
+    lion_update_scaled(theta, m, g, grad_dtype, numel, h, 1.0, hp, theta_bf16);
+}
+
+void oracle_lion_update_clipped(float *theta, float *m, const void *g, int grad_dtype, int64_t numel,
+                                double update_coef, const oracle_opt_hyper *hp, uint16_t *theta_bf16)
+{
+    lion_update_scaled(theta, m, g, grad_dtype, numel, 1.0, update_coef, hp, theta_bf16);
+}
+
+/* ---- AGC and Clippy (Table 2): clipping of the optimizer's update -------------------------------
+ *
+ * Printed: AGC    min{1, lambda_rel ||theta_t|| / ||Delta_t||}                      (l2 norms, per unit)
+ *          Clippy min{1, min((lambda_rel ||theta_t||_inf + lambda_abs)/(eta_t ||Delta_t||_inf))}  (per tensor)
+ * with Delta_t "the optimizer update"; hyper-parameters in the appendix "Clipping Hyper-Parameters"
+ * (AGC lambda_rel 1e-3; Clippy lambda_abs 0.5, lambda_rel 1e-2).  Both leave the gradient alone
+ * (Table 2, column "Gradient") and scale the update.
+ * Readings taken:
+ *   - Delta_t is the optimizer's direction before the learning rate (Clippy's row multiplies it by
+ *     eta_t itself): mhat/(sqrt(vhat)+eps) for AdamW, sign(c) for Lion, from this step's moments;
+ *     decoupled weight decay is not part of it and is applied unscaled;
+ *   - theta_t is the parameter tensor before this step's update;
+ *   - a "unit" is one tensor of the list (a caller who wants rows as units lists the rows);
+ *   - with norms of the whole tensor the inner min of Clippy's row has one argument;
+ *   - the clip is active only when the ratio is below 1 (strict), so 0/0 and x/0 leave the update
+ *     alone; a tensor of zeros has ratio 0 under AGC and its update is scaled to nothing: the
+ *     printed rule has no floor on ||theta|| and none is invented. */
+double oracle_agc_coef(double theta_norm, double delta_norm, double lambda_rel, int *clipped)
+{
+    double ratio = lambda_rel * theta_norm / delta_norm;
+    int active = (ratio < 1.0);            /* false for NaN */
+    *clipped = active;
+    return active ? ratio : 1.0;
+}
+
+double oracle_clippy_coef(double theta_inf, double delta_inf, double lambda_rel, double lambda_abs,
+                          double lr, int *clipped)
+{
+    double ratio = (lambda_rel * theta_inf + lambda_abs) / (lr * delta_inf);
+    int active = (ratio < 1.0);
+    *clipped = active;
+    return active ? ratio : 1.0;
+}
+
+/* l2 and l-infinity norms of theta (before the step) and of the direction Delta this step's
+ * unclipped gradient produces; m, v are read, not written.  v is unused for Lion. */
+void oracle_direction_norms(const float *theta, const float *m, const float *v, const void *g,
+                            int grad_dtype, int64_t numel, const oracle_opt_hyper *hp, int optimizer,
+                            int64_t t, double *theta_l2, double *delta_l2, double *theta_inf,
+                            double *delta_inf)
+{
+    double bias1 = 1.0 - pow(hp->beta1, (double)t);
+    double bias2 = 1.0 - pow(hp->beta2, (double)t);
+    double s_theta = 0.0, s_delta = 0.0, max_theta = 0.0, max_delta = 0.0;
+    for (int64_t j = 0; j < numel; ++j) {
+        double gj = grad_at(g, j, grad_dtype);
+        double delta;
+        if (optimizer == 0) {
+            double mj = hp->beta1 * (double)m[j] + (1.0 - hp->beta1) * gj;
+            double vj = hp->beta2 * (double)v[j] + (1.0 - hp->beta2) * gj * gj;
+            delta = (mj / bias1) / (sqrt(vj / bias2) + hp->eps);
+        } else {
+            double c = hp->beta1 * (double)m[j] + (1.0 - hp->beta1) * gj;
+            delta = (c > 0.0) ? 1.0 : ((c < 0.0) ? -1.0 : 0.0);
+        }
+        double th = (double)theta[j];
+        s_theta += th * th;
+        s_delta += delta * delta;
+        if (fabs(th) > max_theta) max_theta = fabs(th);
+        if (fabs(delta) > max_delta) max_delta = fabs(delta);
+    }
+    *theta_l2 = sqrt(s_theta);
+    *delta_l2 = sqrt(s_delta);
+    *theta_inf = max_theta;
+    *delta_inf = max_delta;
 }
 
 /* ---- Alg. 1, one pass of the repeat-loop body over a list of tensors ------- */
@@ -325,7 +425,10 @@ typedef struct {
     int32_t clip_mode;                          /* 0 = AdaGC (Alg. 1), 1 = GlobalGC on every step (Eq. 2),
                                                    2 = Global AdaGC (single gamma, kept in gamma[0]),
                                                    3 = ZClip (mu in gamma[0], variance in gamma[1];
-                                                       ema_beta is its alpha) */
+                                                       ema_beta is its alpha),
+                                                   4 = AGC, 5 = Clippy: the update is clipped, the
+                                                       gradient is not; no state; lambda_rel (and, for
+                                                       Clippy, lambda_abs) are Table 2's */
     int32_t reserved;
     double z_thres;                             /* ZClip's z-score threshold */
 } oracle_step_hyper;
@@ -348,8 +451,32 @@ int oracle_adagc_step(int64_t n_tensors, const int64_t *numel, float *const *the
     int warmup = (step - 1) < hp->t_start; /* steps 1..T_start */
 
     const int mode = hp->clip_mode;
-    if (mode < 0 || mode > 3)
+    if (mode < 0 || mode > 5)
         return -1;
+
+    if (mode == 4 || mode == 5) {
+        /* update clipping: out_norm reports the norm of the direction the rule acts on */
+        for (int64_t i = 0; i < n_tensors; ++i) {
+            double th2, d2, thinf, dinf, c;
+            int clipped;
+            oracle_direction_norms(theta[i], m[i], v ? v[i] : NULL, grad[i], hp->grad_dtype, numel[i], &oh,
+                                   hp->optimizer, step, &th2, &d2, &thinf, &dinf);
+            if (mode == 4)
+                c = oracle_agc_coef(th2, d2, hp->lambda_rel, &clipped);
+            else
+                c = oracle_clippy_coef(thinf, dinf, hp->lambda_rel, hp->lambda_abs, hp->lr, &clipped);
+            if (out_norm) out_norm[i] = (mode == 4) ? d2 : dinf;
+            if (out_coef) out_coef[i] = c;
+            if (out_clipped) out_clipped[i] = (uint8_t)clipped;
+            uint16_t *copy = theta_bf16 ? theta_bf16[i] : NULL;
+            if (hp->optimizer == 0)
+                oracle_adamw_update_clipped(theta[i], m[i], v[i], grad[i], hp->grad_dtype, numel[i], c, &oh,
+                                            step, copy);
+            else
+                oracle_lion_update_clipped(theta[i], m[i], grad[i], hp->grad_dtype, numel[i], c, &oh, copy);
+        }
+        return 0;
+    }
 
     /* ||g_t|| over the whole model: tensors in list order, elements in index order */
     double h_global = 1.0;

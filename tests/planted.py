@@ -49,7 +49,7 @@ MISTAKES = [
      "return lambda_abs / global_norm;"),
     ("updates read bf16 bits as integers", "return (double)oracle_bf16_to_float(((const uint16_t *)g)[j]);",
      "return (double)(((const uint16_t *)g)[j]);"),
-    ("weight decay dropped from Lion", "th = th - hp->lr * (sgn + hp->weight_decay * th);", "th = th - hp->lr * sgn;"),
+    ("weight decay dropped from Lion", "th = th - hp->lr * (update_coef * sgn + hp->weight_decay * th);", "th = th - hp->lr * update_coef * sgn;"),
     ("ZClip: clip on >= instead of >", "int active = (z > z_thres);", "int active = (z >= z_thres);"),
     ("ZClip: threshold without the reciprocal adjustment", "double xi = z_thres * z_thres / z;", "double xi = z_thres;"),
     ("ZClip: z-score from the variance, not the deviation", "double sigma = sqrt(var_prev);", "double sigma = var_prev;"),
@@ -64,6 +64,21 @@ MISTAKES = [
     ("ZClip: first step averages instead of setting", "    if (first_step) {\n        *mu_new = clipped_norm;\n        *var_new = 0.0;\n        return;\n    }\n", ""),
     ("ZClip: statistics gathered from the raw norm during the first steps", "oracle_zclip_gather(h_global * global_norm,", "oracle_zclip_gather(global_norm,"),
     ("ZClip: z-score rule already during the first steps", "} else if (mode == 3 && !warmup) {", "} else if (mode == 3) {"),
+    ("AGC: ratio inverted", "double ratio = lambda_rel * theta_norm / delta_norm;", "double ratio = lambda_rel * delta_norm / theta_norm;"),
+    ("AGC: relative threshold dropped", "double ratio = lambda_rel * theta_norm / delta_norm;", "double ratio = theta_norm / delta_norm;"),
+    ("Clippy: learning rate left out", "/ (lr * delta_inf);", "/ delta_inf;"),
+    ("Clippy: absolute term dropped", "(lambda_rel * theta_inf + lambda_abs)", "(lambda_rel * theta_inf)"),
+    ("update clipping: coefficient not capped at 1", "    int active = (ratio < 1.0);            /* false for NaN */", "    int active = 1;"),
+    ("update clipping: coefficient applied to the gradient", "adamw_update_scaled(theta, m, v, g, grad_dtype, numel, 1.0, update_coef, hp, t, theta_bf16);",
+     "adamw_update_scaled(theta, m, v, g, grad_dtype, numel, update_coef, 1.0, hp, t, theta_bf16);"),
+    ("update clipping: weight decay scaled too", "th - hp->lr * hp->weight_decay * th - update_coef * (", "th - update_coef * (hp->lr * hp->weight_decay * th) - update_coef * ("),
+    ("update clipping: direction from the old moments", "double mj = hp->beta1 * (double)m[j] + (1.0 - hp->beta1) * gj;", "double mj = (double)m[j];"),
+    ("update clipping: direction without bias correction", "delta = (mj / bias1) / (sqrt(vj / bias2) + hp->eps);", "delta = mj / (sqrt(vj) + hp->eps);"),
+    ("Clippy given the l2 norms", "c = oracle_clippy_coef(thinf, dinf,", "c = oracle_clippy_coef(th2, d2,"),
+    ("AGC given the l-infinity norms", "c = oracle_agc_coef(th2, d2,", "c = oracle_agc_coef(thinf, dinf,"),
+    ("update clipping: Lion coefficient on the decay instead of the sign", "th = th - hp->lr * (update_coef * sgn + hp->weight_decay * th);",
+     "th = th - hp->lr * (sgn + update_coef * hp->weight_decay * th);"),
+    ("update clipping: squared norms compared", "    *theta_l2 = sqrt(s_theta);\n    *delta_l2 = sqrt(s_delta);", "    *theta_l2 = s_theta;\n    *delta_l2 = s_delta;"),
 ]
 
 

@@ -823,3 +823,146 @@ def test_zclip_on_a_list_sees_only_the_global_norm():
                           _lists([np.zeros(5), np.zeros(1), np.zeros(9)]), np.concatenate([s1, [0]]).astype(np.float32), hp, 2)
     b = oracle.adagc_step(_lists([np.zeros(15)]), whole, _lists([np.zeros(15)]), _lists([np.zeros(15)]), s2, hp, 2)
     assert a[1][0] == a[1][1] == a[1][2] == b[1][0] and b[2][0] == 1
+
+
+# ------------------------------------------------------------------ AGC and Clippy (Table 2; update clipping)
+# Table 2 prints both coefficients; what Delta is, which theta enters and what a unit is are readings
+# (see oracle_agc_coef): pinned here by hand values, invariants and a cross-check of the direction's norms
+# against the update routine.
+
+def test_update_clipping_paper_hyper_parameters():
+    paper = golden()
+    assert paper["agc_lambda_rel"] == 1e-3 and paper["clippy_lambda_abs"] == 0.5 and paper["clippy_lambda_rel"] == 1e-2
+
+
+def test_agc_coef_hand_values_and_invariant():
+    assert oracle.agc_coef(10.0, 5.0, 0.25) == (0.5, True)        # 0.25*10/5
+    assert oracle.agc_coef(10.0, 2.0, 0.25) == (1.0, False)       # ratio 1.25
+    assert oracle.agc_coef(8.0, 2.0, 0.25) == (1.0, False)        # ratio exactly 1: not clipped
+    assert oracle.agc_coef(10.0, 0.0, 0.25) == (1.0, False)       # no update to clip
+    assert oracle.agc_coef(0.0, 0.0, 0.25) == (1.0, False)        # 0/0
+    assert oracle.agc_coef(0.0, 3.0, 0.25) == (0.0, True)         # no floor on ||theta||: literal
+    rng = np.random.default_rng(4)
+    for _ in range(200):
+        th, d, lam = rng.uniform(0.01, 50), rng.uniform(0.01, 50), rng.uniform(1e-4, 2)
+        c, clipped = oracle.agc_coef(th, d, lam)
+        assert 0.0 < c <= 1.0 and clipped == (lam * th < d)
+        assert c * d <= lam * th * (1 + 1e-15) or not clipped     # ||c Delta|| <= lambda ||theta||
+        if clipped:
+            assert abs(c * d - lam * th) <= 1e-15 * lam * th
+        assert oracle.agc_coef(th * 8, d * 8, lam) == (c, clipped)    # scale invariant
+
+
+def test_clippy_coef_hand_values_and_invariant():
+    assert oracle.clippy_coef(2.0, 8.0, 0.5, 1.0, 0.5) == (0.5, True)        # (0.5*2+1)/(0.5*8)
+    assert oracle.clippy_coef(2.0, 4.0, 0.5, 1.0, 0.5) == (1.0, False)       # ratio exactly 1
+    assert oracle.clippy_coef(2.0, 1.0, 0.5, 1.0, 0.5) == (1.0, False)
+    assert oracle.clippy_coef(0.0, 8.0, 0.5, 1.0, 0.5) == (0.25, True)       # the absolute term keeps zeros moving
+    assert oracle.clippy_coef(2.0, 0.0, 0.5, 1.0, 0.5) == (1.0, False)
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        th, d = rng.uniform(0, 5), rng.uniform(0.01, 50)
+        lr, lam, ab = rng.uniform(1e-4, 1), rng.uniform(1e-4, 1), rng.uniform(0.01, 1)
+        c, clipped = oracle.clippy_coef(th, d, lam, ab, lr)
+        assert 0.0 < c <= 1.0
+        assert lr * c * d <= (lam * th + ab) * (1 + 1e-15)          # the largest step stays within the budget
+        if clipped:
+            assert abs(lr * c * d - (lam * th + ab)) <= 1e-15 * (lam * th + ab)
+
+
+def test_direction_norms_hand_worked_and_against_the_update_routine():
+    # step 1 from zero moments with eps = 0: Delta = g/|g| = sign(g)
+    hp = Hyper(lr=0.25, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.0)
+    theta = np.array([3.0, -4.0, 0.0, 0.0], np.float32)
+    g = np.array([1.0, -2.0, 0.5, 8.0], np.float32)
+    z = np.zeros(4, np.float32)
+    assert oracle.direction_norms(theta, z, z, g, hp, 1) == (5.0, 2.0, 4.0, 1.0)
+    # general case: the direction is what the update routine applies; recover it with lr = 1, wd = 0, theta = 0
+    rng = np.random.default_rng(17)
+    n = 4000
+    m = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    v = ((rng.standard_normal(n) * 1e-2) ** 2).astype(np.float32)
+    g = (rng.standard_normal(n) * 3e-2).astype(np.float32)
+    theta = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    hp = Hyper(lr=1.0, weight_decay=0.0, eps=1e-8)
+    t0, m2, v2 = np.zeros(n, np.float32), m.copy(), v.copy()
+    oracle.adamw_update(t0, m2, v2, g, 1.0, hp, 7)
+    delta = -t0.astype(np.float64)                                  # fp32-rounded direction
+    th2, d2, thinf, dinf = oracle.direction_norms(theta, m, v, g, hp, 7)
+    assert abs(d2 - np.linalg.norm(delta)) <= 1e-6 * d2 and abs(dinf - np.abs(delta).max()) <= 1e-6 * dinf
+    assert abs(th2 - np.linalg.norm(theta.astype(np.float64))) <= 1e-14 * th2
+    assert thinf == float(np.abs(theta).max())
+    # Lion: the direction is the sign of the interpolation
+    hpl = Hyper(beta1=0.5, beta2=0.75, optimizer=oracle.LION)
+    m = np.array([1.0, -1.0, 2.0, 0.0, 0.0], np.float32)
+    g = np.array([1.0, 1.0, -1.0, 0.0, -3.0], np.float32)          # c = 1, 0, .5, 0, -1.5
+    th = np.array([0.5, 0.5, 0.5, 0.5, -2.0], np.float32)
+    assert oracle.direction_norms(th, m, None, g, hpl, 3) == (math.sqrt(5.0), math.sqrt(3.0), 2.0, 1.0)
+
+
+def test_update_clipped_scales_the_direction_only():
+    """lr 1/4, beta1 1/2, beta2 3/4, eps 0, step 1: Delta = sign(g).  With coefficient 1/2 the parameter
+    moves by lr/2; the moments are those of the unclipped gradient; weight decay is applied in full."""
+    hp = Hyper(lr=0.25, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.0)
+    theta = np.array([3.0, -4.0, 1.0], np.float32)
+    g = np.array([2.0, -6.0, 0.5], np.float32)
+    th, m, v = theta.copy(), np.zeros(3, np.float32), np.zeros(3, np.float32)
+    oracle.adamw_update_clipped(th, m, v, g, 0.5, hp, 1)
+    assert th.tolist() == [3.0 - 0.125, -4.0 + 0.125, 1.0 - 0.125]
+    assert m.tolist() == [1.0, -3.0, 0.25] and v.tolist() == [1.0, 9.0, 0.0625]
+    hpw = Hyper(lr=0.25, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.5)
+    th = theta.copy()
+    oracle.adamw_update_clipped(th, np.zeros(3, np.float32), np.zeros(3, np.float32), g, 0.5, hpw, 1)
+    assert th.tolist() == [3.0 - 0.375 - 0.125, -4.0 + 0.5 + 0.125, 1.0 - 0.125 - 0.125]
+    # coefficient 1 is the plain step, bit for bit
+    rng = np.random.default_rng(2)
+    a = [(rng.standard_normal(500) * s).astype(np.float32) for s in (0.02, 1e-3, 1e-3, 1e-2)]
+    a[2] = a[2] ** 2
+    p1, m1, v1 = a[0].copy(), a[1].copy(), a[2].copy()
+    p2, m2, v2 = a[0].copy(), a[1].copy(), a[2].copy()
+    oracle.adamw_update(p1, m1, v1, a[3], 1.0, Hyper(), 9)
+    oracle.adamw_update_clipped(p2, m2, v2, a[3], 1.0, Hyper(), 9)
+    assert np.array_equal(p1, p2) and np.array_equal(m1, m2) and np.array_equal(v1, v2)
+    # Lion: theta -= lr (coef*sign(c) + wd*theta); momentum from the unclipped gradient
+    hpl = Hyper(lr=0.25, beta1=0.5, beta2=0.75, weight_decay=0.5, optimizer=oracle.LION)
+    th, m = np.array([8.0, -2.0], np.float32), np.array([1.0, 1.0], np.float32)
+    oracle.lion_update_clipped(th, m, np.array([1.0, -3.0], np.float32), 0.5, hpl)
+    assert th.tolist() == [8.0 - 0.25 * (0.5 + 4.0), -2.0 - 0.25 * (-0.5 - 1.0)]
+    assert m.tolist() == [0.75 + 0.25, 0.75 - 0.75]
+
+
+def test_agc_and_clippy_steps_hand_worked():
+    """theta [3,4,0,0] (l2 5, l-inf 4) and [0,0]; first step, eps 0: Delta is the sign of g.
+    AGC, lambda_rel 0.2: ratios 0.2*5/2 = 0.5 and 0 -> the first tensor moves by lr/2, the second not at all.
+    Clippy, lambda_rel 1/16, lambda_abs 1/4, lr 1: ratios (0.25+0.25)/1 = 0.5 and 0.25."""
+    def fresh():
+        return (_lists([[3, 4, 0, 0], [0, 0]]), _lists([[0] * 4, [0] * 2]), _lists([[0] * 4, [0] * 2]))
+    g = _lists([[1, -2, 0.5, 8], [4, -4]])
+    gamma = np.array([7.0, 9.0], np.float32)
+    th, m, v = fresh()
+    hp = Hyper(lr=0.25, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.0, lambda_rel=0.2, clip_mode=oracle.MODE_AGC)
+    norms, coefs, clipped = oracle.adagc_step(th, g, m, v, gamma, hp, 1)
+    assert norms.tolist() == [2.0, math.sqrt(2.0)]                  # reported: the direction's l2 norm
+    assert coefs.tolist() == [f32(0.2) * 5.0 / 2.0, 0.0] and clipped.tolist() == [1, 1]
+    c = f32(0.2) * 5.0 / 2.0
+    np.testing.assert_array_equal(th[0], np.array([3 - 0.25 * c, 4 + 0.25 * c, -0.25 * c, -0.25 * c], np.float32))
+    assert th[1].tolist() == [0.0, 0.0]
+    assert m[0].tolist() == [0.5, -1.0, 0.25, 4.0] and m[1].tolist() == [2.0, -2.0]      # unclipped gradient
+    assert gamma.tolist() == [7.0, 9.0]                              # no state
+    th, m, v = fresh()
+    hp = Hyper(lr=1.0, beta1=0.5, beta2=0.75, eps=0.0, weight_decay=0.0, lambda_rel=0.0625, lambda_abs=0.25,
+               clip_mode=oracle.MODE_CLIPPY)
+    norms, coefs, clipped = oracle.adagc_step(th, g, m, v, gamma, hp, 1)
+    assert norms.tolist() == [1.0, 1.0] and coefs.tolist() == [0.5, 0.25] and clipped.tolist() == [1, 1]
+    assert th[0].tolist() == [2.5, 4.5, -0.5, -0.5] and th[1].tolist() == [-0.25, 0.25]
+    # generous thresholds: nothing is clipped and the step is plain AdamW
+    th, m, v = fresh()
+    th2, m2, v2 = fresh()
+    hp = Hyper(lambda_rel=1e6, clip_mode=oracle.MODE_AGC, t_start=0)
+    th[1][:] = 1.0
+    th2[1][:] = 1.0
+    _, coefs, clipped = oracle.adagc_step(th, g, m, v, gamma, hp, 4)
+    oracle.adagc_step(th2, g, m2, v2, gamma.copy(), Hyper(lambda_rel=float("inf"), t_start=0), 4)
+    assert coefs.tolist() == [1.0, 1.0] and clipped.tolist() == [0, 0]
+    for x, y in zip(th + m + v, th2 + m2 + v2):
+        assert np.array_equal(x, y)

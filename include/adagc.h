@@ -72,6 +72,16 @@ extern "C" {
                                        statistics under GlobalGC (Eq. 2 with lambda_abs): step 1 sets mu to its
                                        clipped norm and var to 0 */
 
+#define ADAGC_MODE_AGC           4  /* update clipping, Table 2's AGC row: the gradient is left alone and each tensor's
+                                       update direction Delta (AdamW: mhat/(sqrt(vhat)+eps); Lion: sign(c)) is scaled by
+                                       min{1, lambda_rel ||theta|| / ||Delta||} (l2 norms, theta before the step; the paper's
+                                       setting: lambda_rel 1e-3).  One tensor of the list is one unit; weight decay is
+                                       applied unscaled.  Needs adagc_config.update_clipping = 1; keeps no state;
+                                       adagc_get_norms then reports ||Delta_i|| and the update's coefficient */
+#define ADAGC_MODE_CLIPPY        5  /* update clipping, Table 2's Clippy row: the same with
+                                       min{1, (lambda_rel ||theta||_inf + lambda_abs) / (lr ||Delta||_inf)}
+                                       (the paper's setting: lambda_abs 0.5, lambda_rel 1e-2) */
+
 typedef struct adagc_ctx adagc_ctx; /* opaque; created by adagc_create, freed by adagc_destroy */
 
 /* One parameter tensor = one clipping unit (Sec. 4.2: "each parameter tensor";
@@ -105,6 +115,9 @@ typedef struct {
                                      (small items shorten the tail of the launch and give short lists more
                                      workgroups; whole chunks cost the fewest dispatches) */
     int32_t schedule_run;         /* visiting order: chunks an XCD takes in a row (default 8) */
+    int32_t update_clipping;      /* 1: reserve the scratch the update-clipping modes need (ADAGC_MODE_AGC and
+                                     ADAGC_MODE_CLIPPY: two extra partial results per work item of the update
+                                     kernel); those modes return ADAGC_ERR_STATE without it */
 } adagc_config;
 
 /* Hyper-parameters of Alg. 1, passed by the caller on every step (the learning
@@ -211,7 +224,9 @@ int adagc_set_param_copies(adagc_ctx* ctx, void* const* params_bf16);
  * Non-finite gradients get no special treatment: a NaN norm compares false
  * against the threshold, so the tensor is not clipped and the NaN propagates as
  * it would in plain AdamW.
- * Errors: INVALID_ARG, STATE (bf16 copies expected but not set), HIP.
+ * The update-clipping modes read g, theta, m, v once more instead of the norm pass (the direction's norms
+ * must be complete before any element is updated): 16 + 30 bytes per parameter instead of 4 + 30.
+ * Errors: INVALID_ARG, STATE (bf16 copies expected but not set; update clipping not reserved), HIP.
  */
 int adagc_step(adagc_ctx* ctx, void* const* params, const void* const* grads,
                void* const* exp_avg, void* const* exp_avg_sq, float* ema_norms,
@@ -228,7 +243,8 @@ int adagc_step(adagc_ctx* ctx, void* const* params, const void* const* grads,
  *   other arguments as for adagc_step
  * The parameters cannot be validated on the host: a step whose parameters adagc_step would reject
  * leaves all state untouched, and the next adagc_get_norms / adagc_get_state_norms returns
- * INVALID_ARG.  The bias corrections use the device's pow(), which may differ from the host's in
+ * INVALID_ARG (this includes the update-clipping modes, which this entry point does not offer).
+ * The bias corrections use the device's pow(), which may differ from the host's in
  * the last bit of a double (invisible after rounding to fp32 in all but about one value in 10^8).
  * While `stream` is capturing, the call records kernels only: the tensor pointers must be the ones
  * of the previous call on this context (make one uncaptured call first; otherwise STATE), and
@@ -246,8 +262,9 @@ int adagc_step_graph(adagc_ctx* ctx, void* const* params, const void* const* gra
  * launches kernels on `stream`.  The segment table, the per-chunk partial sums and the per-tensor
  * results live in a fixed array inside the library's device code, ADAGC_STATIC_MAX_* in size
  * (about 11 MB per GPU, held from the library's load until the process ends).
- *   descs, n_tensors, cfg   HOST  as for adagc_create; cfg->telemetry and the launch-tuning fields
- *                                 must be 0 (library defaults, chunks visited in list order)
+ *   descs, n_tensors, cfg   HOST  as for adagc_create; cfg->telemetry, cfg->update_clipping and the
+ *                                 launch-tuning fields must be 0 (library defaults, chunks visited in
+ *                                 list order; clip modes 0 to 3)
  *   params, grads, exp_avg, exp_avg_sq, ema_norms, hp, step, stream   as for adagc_step
  *   params_bf16   HOST array of n_tensors DEVICE pointers (cfg->has_bf16_param_copy = 1), else NULL
  *   out_norms     DEVICE fp32[n_tensors]  ||g_i|| before clipping        (may be NULL)

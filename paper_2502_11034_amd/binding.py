@@ -22,6 +22,7 @@ ADAGC_ERR_STATE = -5
 ADAGC_OPT_ADAMW, ADAGC_OPT_LION = 0, 1
 ADAGC_GRAD_F32, ADAGC_GRAD_BF16 = 0, 1
 ADAGC_MODE_ADAGC, ADAGC_MODE_GLOBALGC, ADAGC_MODE_GLOBAL_ADAGC, ADAGC_MODE_ZCLIP = 0, 1, 2, 3
+ADAGC_MODE_AGC, ADAGC_MODE_CLIPPY = 4, 5
 
 EXPORTS = [
     "adagc_chunk_elems", "adagc_build_segment_table", "adagc_build_visiting_order", "adagc_create", "adagc_destroy",
@@ -40,7 +41,8 @@ class adagc_config(ctypes.Structure):
                 ("has_bf16_param_copy", ctypes.c_int32), ("telemetry", ctypes.c_int32),
                 ("grid_blocks", ctypes.c_int32),
                 ("unroll", ctypes.c_int32), ("nontemporal", ctypes.c_int32), ("schedule", ctypes.c_int32),
-                ("update_split", ctypes.c_int32), ("schedule_run", ctypes.c_int32)]
+                ("update_split", ctypes.c_int32), ("schedule_run", ctypes.c_int32),
+                ("update_clipping", ctypes.c_int32)]
 
 
 class adagc_hyper(ctypes.Structure):
@@ -188,7 +190,7 @@ def adagc_step_static(numels, params, grads, exp_avg, exp_avg_sq, ema_norms, hyp
                       stream=None):
     """adagc_step_static: the step without a context and without any allocation on the GPU side.
     out_*: device tensors (or None).  Raises AdagcError on a non-zero return code."""
-    cfg = adagc_config(int(optimizer), int(grad_dtype), int(params_bf16 is not None), 0, 0, 0, 0, 0, 0, 0)
+    cfg = adagc_config(int(optimizer), int(grad_dtype), int(params_bf16 is not None), 0, 0, 0, 0, 0, 0, 0, 0)
     descs = _descs([int(n) for n in numels])
     p, g, m = (ptr_array(x) for x in (params, grads, exp_avg))
     v = ptr_array(exp_avg_sq) if exp_avg_sq is not None else None
@@ -205,13 +207,14 @@ class AdaGC:
 
     def __init__(self, numels, optimizer=ADAGC_OPT_ADAMW, grad_dtype=ADAGC_GRAD_F32,
                  has_bf16_param_copy=False, grid_blocks=0, unroll=0, nontemporal=0, schedule=0, telemetry=False,
-                 update_split=0, schedule_run=0):
+                 update_split=0, schedule_run=0, update_clipping=False):
         L = lib()
         self._ctx = ctypes.c_void_p(None)
         self.n_tensors = len(numels)
         self.numels = [int(n) for n in numels]
         cfg = adagc_config(int(optimizer), int(grad_dtype), int(bool(has_bf16_param_copy)), int(bool(telemetry)),
-                           int(grid_blocks), int(unroll), int(nontemporal), int(schedule), int(update_split), int(schedule_run))
+                           int(grid_blocks), int(unroll), int(nontemporal), int(schedule), int(update_split), int(schedule_run),
+                           int(bool(update_clipping)))
         descs = _descs(self.numels)
         _check(L.adagc_create(ctypes.byref(self._ctx), ctypes.cast(descs, ctypes.c_void_p), self.n_tensors,
                               ctypes.byref(cfg)), "adagc_create")

@@ -50,6 +50,7 @@ struct RuleArgs {
     double ema_beta;
     double lambda_abs;
     double z_thres;      // ZClip
+    double lr;           // Clippy's ratio divides by the learning rate
     int    first_step;   // step == 1: gamma is set, not min-ed
     int    warmup;       // step <= t_start
     int    mode;         // ADAGC_MODE_*
@@ -67,6 +68,9 @@ struct UpdateArgs {
     double eps;
     double lr;             // Lion
     double weight_decay;   // Lion
+    double bias1;          // 1 - beta1^t (the direction's norms of the update-clipping modes)
+    int    update_clip;    // 1: the direction is scaled by the tensor's update coefficient
+    int    pad;
 };
 
 // Scalars of one step kept in device memory: written by a small kernel from the caller's
@@ -93,6 +97,9 @@ struct DeviceTables {
     double*           tele_partials;  // telemetry: [3][n_chunks][items per chunk] sums of m^2, v^2, (dtheta)^2 (or null)
     float*            tele_norm;      // telemetry: [3][n_tensors] norms
     StepScalars*      scalars;        // used by adagc_step_graph only
+    double*           ustat_partials; // update clipping: [2][n_chunks][items per chunk] partial norms of theta and of
+                                      // the direction (sums of squares for AGC, maxima for Clippy), or null
+    double*           ucoef64;        // update clipping: per-tensor coefficient of the direction, or null
     uint32_t          n_chunks;
     uint32_t          n_tensors;
 };
@@ -107,7 +114,7 @@ inline bool hyper_ok(const adagc_hyper& h, int optimizer)
     if (!(h.lambda_rel >= 0.0f)) return false;    // +inf allowed, NaN not
     if (!(h.lambda_abs > 0.0f)) return false;     // +inf allowed, NaN not
     if (h.t_start < 0) return false;
-    if (h.clip_mode < ADAGC_MODE_ADAGC || h.clip_mode > ADAGC_MODE_ZCLIP) return false;
+    if (h.clip_mode < ADAGC_MODE_ADAGC || h.clip_mode > ADAGC_MODE_CLIPPY) return false;
     if (h.clip_mode == ADAGC_MODE_ZCLIP && !(h.z_thres > 0.0f)) return false;   // +inf allowed, NaN not
     return true;
 }
@@ -121,6 +128,7 @@ inline void host_step_scalars(const adagc_hyper& hp, int64_t step, RuleArgs& r, 
     r.ema_beta = (double)hp.ema_beta;
     r.lambda_abs = (double)hp.lambda_abs;
     r.z_thres = (double)hp.z_thres;
+    r.lr = lr;
     r.pad = 0;
     r.first_step = (step == 1) ? 1 : 0;
     r.warmup = ((step - 1) < (int64_t)hp.t_start) ? 1 : 0;   // steps 1..t_start
@@ -135,6 +143,9 @@ inline void host_step_scalars(const adagc_hyper& hp, int64_t step, RuleArgs& r, 
     u.eps = (double)hp.eps;
     u.lr = lr;
     u.weight_decay = wd;
+    u.bias1 = 1.0 - std::pow(b1, t);
+    u.update_clip = (hp.clip_mode == ADAGC_MODE_AGC || hp.clip_mode == ADAGC_MODE_CLIPPY) ? 1 : 0;
+    u.pad = 0;
 }
 
 // Launchers (kernels.hip).  Each only enqueues on `stream`.
@@ -144,6 +155,10 @@ hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleA
 hipError_t launch_update(const DeviceTables& t, const UpdateArgs& u, int optimizer, int grad_bf16,
                          int with_copy, int unroll, int items_per_chunk, int nt, int tele, int grid,
                          hipStream_t stream, bool device_scalars = false);
+// Update-clipping modes (AGC, Clippy): norms of theta and of the direction per work item, then one workgroup
+// per tensor turns them into the tensor's update coefficient.
+hipError_t launch_update_clip_rule(const DeviceTables& t, const UpdateArgs& u, const RuleArgs& r, int optimizer,
+                                   int grad_bf16, int items_per_chunk, int nt, int grid, hipStream_t stream);
 // Rule stage of adagc_step_graph: scalars from device-resident step parameters, then the per-tensor
 // sums, the model-wide rule (a no-op outside warm-up and the global modes) and the per-tensor rule.
 hipError_t launch_rules_from_device(const DeviceTables& t, float* ema, const adagc_step_params* params,

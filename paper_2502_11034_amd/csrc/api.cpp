@@ -106,7 +106,8 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     if (cfg->grad_dtype != ADAGC_GRAD_F32 && cfg->grad_dtype != ADAGC_GRAD_BF16) return ADAGC_ERR_INVALID_ARG;
     if (cfg->has_bf16_param_copy != 0 && cfg->has_bf16_param_copy != 1) return ADAGC_ERR_INVALID_ARG;
     if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 2 || cfg->schedule < 0 ||
-        cfg->schedule_run < 0 || cfg->telemetry < 0 || cfg->telemetry > 1)
+        cfg->schedule_run < 0 || cfg->telemetry < 0 || cfg->telemetry > 1 || cfg->update_clipping < 0 ||
+        cfg->update_clipping > 1)
         return ADAGC_ERR_INVALID_ARG;
     if (cfg->unroll != 0 && cfg->unroll != 1 && cfg->unroll != 2 && cfg->unroll != 4) return ADAGC_ERR_INVALID_ARG;
     {
@@ -195,6 +196,8 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     const size_t tiles_per_chunk = (size_t)c->items_per_chunk;
     const size_t o_tele_partials = carve(cfg->telemetry ? 3 * nc * tiles_per_chunk * sizeof(double) : 0);
     const size_t o_tele_norm = carve(cfg->telemetry ? 3 * nt * sizeof(float) : 0);
+    const size_t o_ustat = carve(cfg->update_clipping ? 2 * nc * tiles_per_chunk * sizeof(double) : 0);
+    const size_t o_ucoef64 = carve(cfg->update_clipping ? nt * sizeof(double) : 0);
     const size_t slab_bytes = off;
 
     hipError_t e = hipMalloc(&c->slab, slab_bytes);
@@ -251,6 +254,8 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
     t.flag = reinterpret_cast<uint8_t*>(base + o_flag);
     t.tele_partials = cfg->telemetry ? reinterpret_cast<double*>(base + o_tele_partials) : nullptr;
     t.tele_norm = cfg->telemetry ? reinterpret_cast<float*>(base + o_tele_norm) : nullptr;
+    t.ustat_partials = cfg->update_clipping ? reinterpret_cast<double*>(base + o_ustat) : nullptr;
+    t.ucoef64 = cfg->update_clipping ? reinterpret_cast<double*>(base + o_ucoef64) : nullptr;
     t.n_chunks = (uint32_t)c->n_chunks;
     t.n_tensors = (uint32_t)c->n_tensors;
 
@@ -341,6 +346,8 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
 {
     if (!ctx || !params || !grads || !exp_avg || !ema_norms || !hp || step < 1) return ADAGC_ERR_INVALID_ARG;
     if (!hyper_ok(*hp, ctx->cfg.optimizer)) return ADAGC_ERR_INVALID_ARG;
+    const bool update_clip = hp->clip_mode == ADAGC_MODE_AGC || hp->clip_mode == ADAGC_MODE_CLIPPY;
+    if (update_clip && !ctx->cfg.update_clipping) return ADAGC_ERR_STATE;
     const bool bf16g = ctx->cfg.grad_dtype == ADAGC_GRAD_BF16;
     const bool copy = ctx->cfg.has_bf16_param_copy != 0;
     DeviceGuard guard(ctx->device);
@@ -358,12 +365,22 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
     hipEvent_t* ev = prof ? &ctx->prof_events[(size_t)ctx->prof_steps * 4] : nullptr;
 
     if (prof && hipEventRecord(ev[0], stream) != hipSuccess) return ADAGC_ERR_HIP;
-    if (launch_sumsq_partials(ctx->tables, bf16g, ctx->nontemporal, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
-    if (prof && hipEventRecord(ev[1], stream) != hipSuccess) return ADAGC_ERR_HIP;
-    hipError_t e = global_rule ? launch_finalize_global(ctx->tables, ema_norms, r, stream)
-                               : launch_finalize_adagc(ctx->tables, ema_norms, r, stream);
-    if (e != hipSuccess) return ADAGC_ERR_HIP;
-    if (prof && hipEventRecord(ev[2], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (update_clip) {
+        // AGC / Clippy: no gradient norms; the direction's norms (timed in the norm slot together with their
+        // per-tensor rule), then the update scales the direction
+        if (launch_update_clip_rule(ctx->tables, u, r, ctx->cfg.optimizer, bf16g, ctx->items_per_chunk, ctx->nontemporal,
+                                    ctx->grid_update, stream) != hipSuccess)
+            return ADAGC_ERR_HIP;
+        if (prof && (hipEventRecord(ev[1], stream) != hipSuccess || hipEventRecord(ev[2], stream) != hipSuccess))
+            return ADAGC_ERR_HIP;
+    } else {
+        if (launch_sumsq_partials(ctx->tables, bf16g, ctx->nontemporal, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
+        if (prof && hipEventRecord(ev[1], stream) != hipSuccess) return ADAGC_ERR_HIP;
+        const hipError_t e = global_rule ? launch_finalize_global(ctx->tables, ema_norms, r, stream)
+                                         : launch_finalize_adagc(ctx->tables, ema_norms, r, stream);
+        if (e != hipSuccess) return ADAGC_ERR_HIP;
+        if (prof && hipEventRecord(ev[2], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    }
     if (launch_update(ctx->tables, u, ctx->cfg.optimizer, bf16g, copy, ctx->unroll, ctx->items_per_chunk,
                       ctx->nontemporal, ctx->cfg.telemetry, ctx->grid_update, stream) != hipSuccess)
         return ADAGC_ERR_HIP;

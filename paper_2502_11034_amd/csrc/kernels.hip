@@ -7,6 +7,9 @@
 //                           (GlobalGC + running minimum), GlobalGC on every step (Eq. 2),
 //                           Global AdaGC (Eq. 3 on the model's norm; "Ablation Study", Sec. 5.6)
 //   update_kernel           per quarter chunk: clipped gradient into AdamW / Lion  (Alg. 1)
+//   direction_stats_kernel / finalize_update_clip_kernel
+//                           update clipping (AGC and Clippy rows of Table 2): norms of theta and of the
+//                           optimizer's direction per tensor, and the coefficient that scales the direction
 //   prepare_step_kernel / global_rule_device_kernel / finalize_device_kernel
 //                           the same rules with the step's scalars read from device memory, for a
 //                           launch sequence that is recorded once and replayed for later steps
@@ -420,6 +423,10 @@ __global__ void prepare_step_kernel(DeviceTables t, const adagc_step_params* par
     sc.u.eps = (double)hp.eps;
     sc.u.lr = lr;
     sc.u.weight_decay = wd;
+    sc.u.bias1 = 1.0 - pow(b1, tt);
+    sc.u.update_clip = 0;                       // the update-clipping modes are rejected above
+    sc.u.pad = 0;
+    sc.r.lr = lr;
     sc.status = ok ? 0 : 1;
     sc.pad = 0;
     *t.scalars = sc;
@@ -457,14 +464,15 @@ struct ElemState {
 
 // AdamW statements of Alg. 1 on the clipped gradient h*g; the bias corrections are folded into two
 // host-computed scalars (step_size = lr / (1 - beta1^t), inv_bias2 = 1 / (1 - beta2^t)).
-__device__ __forceinline__ void adamw_elem(const UpdateArgs& a, double h, float g, ElemState& s)
+// uc scales the direction m_hat/(sqrt(v_hat)+eps) (update clipping); it is exactly 1.0 in every other mode.
+__device__ __forceinline__ void adamw_elem(const UpdateArgs& a, double h, double uc, float g, ElemState& s)
 {
     const double gh = h * (double)g;
     const double m = a.beta1 * (double)s.m + a.one_minus_beta1 * gh;
     const double v = a.beta2 * (double)s.v + a.one_minus_beta2 * gh * gh;
     const double denom = sqrt(v * a.inv_bias2) + a.eps;
     const double th = (double)s.p;
-    s.p = (float)(th - a.lr_wd * th - a.step_size * m / denom);
+    s.p = (float)(th - a.lr_wd * th - uc * (a.step_size * m / denom));
     s.m = (float)m;
     s.v = (float)v;
 }
@@ -472,31 +480,36 @@ __device__ __forceinline__ void adamw_elem(const UpdateArgs& a, double h, float 
 // Lion (rule of Chen et al.; the paper only cites it).  The sign is a discrete decision: the
 // interpolation c is evaluated with separately rounded operations, the sequence a plain C
 // implementation without contraction produces.
-__device__ __forceinline__ void lion_elem(const UpdateArgs& a, double h, float g, ElemState& s)
+__device__ __forceinline__ double lion_sign(const UpdateArgs& a, double gh, float m)
+{
+    const double c = __dadd_rn(__dmul_rn(a.beta1, (double)m), __dmul_rn(a.one_minus_beta1, gh));
+    return (c > 0.0) ? 1.0 : ((c < 0.0) ? -1.0 : 0.0);
+}
+
+__device__ __forceinline__ void lion_elem(const UpdateArgs& a, double h, double uc, float g, ElemState& s)
 {
     const double gh = __dmul_rn(h, (double)g);
-    const double c = __dadd_rn(__dmul_rn(a.beta1, (double)s.m), __dmul_rn(a.one_minus_beta1, gh));
-    const double sgn = (c > 0.0) ? 1.0 : ((c < 0.0) ? -1.0 : 0.0);
+    const double sgn = lion_sign(a, gh, s.m);
     const double th = (double)s.p;
-    s.p = (float)(th - a.lr * (sgn + a.weight_decay * th));
+    s.p = (float)(th - a.lr * (uc * sgn + a.weight_decay * th));
     s.m = (float)(a.beta2 * (double)s.m + a.one_minus_beta2 * gh);
 }
 
 template <int OPT>
-__device__ __forceinline__ void apply_elem(const UpdateArgs& a, double h, float g, ElemState& s)
+__device__ __forceinline__ void apply_elem(const UpdateArgs& a, double h, double uc, float g, ElemState& s)
 {
-    if constexpr (OPT == ADAGC_OPT_ADAMW) adamw_elem(a, h, g, s);
-    else lion_elem(a, h, g, s);
+    if constexpr (OPT == ADAGC_OPT_ADAMW) adamw_elem(a, h, uc, g, s);
+    else lion_elem(a, h, uc, g, s);
 }
 
 template <int OPT>
-__device__ __forceinline__ void apply_vec(const UpdateArgs& a, double h, f32x4 g, f32x4& p, f32x4& m, f32x4& v)
+__device__ __forceinline__ void apply_vec(const UpdateArgs& a, double h, double uc, f32x4 g, f32x4& p, f32x4& m, f32x4& v)
 {
     ElemState s;
-    s = {p.x, m.x, v.x}; apply_elem<OPT>(a, h, g.x, s); p.x = s.p; m.x = s.m; v.x = s.v;
-    s = {p.y, m.y, v.y}; apply_elem<OPT>(a, h, g.y, s); p.y = s.p; m.y = s.m; v.y = s.v;
-    s = {p.z, m.z, v.z}; apply_elem<OPT>(a, h, g.z, s); p.z = s.p; m.z = s.m; v.z = s.v;
-    s = {p.w, m.w, v.w}; apply_elem<OPT>(a, h, g.w, s); p.w = s.p; m.w = s.m; v.w = s.v;
+    s = {p.x, m.x, v.x}; apply_elem<OPT>(a, h, uc, g.x, s); p.x = s.p; m.x = s.m; v.x = s.v;
+    s = {p.y, m.y, v.y}; apply_elem<OPT>(a, h, uc, g.y, s); p.y = s.p; m.y = s.m; v.y = s.v;
+    s = {p.z, m.z, v.z}; apply_elem<OPT>(a, h, uc, g.z, s); p.z = s.p; m.z = s.m; v.z = s.v;
+    s = {p.w, m.w, v.w}; apply_elem<OPT>(a, h, uc, g.w, s); p.w = s.p; m.w = s.m; v.w = s.v;
 }
 
 // Telemetry: per-lane fp64 sums of m^2, v^2 and (theta_new - theta_old)^2 over the lane's elements,
@@ -560,6 +573,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
         const ChunkView cv = chunk_view(t, c);
         const TensorArgs& ta = t.targs[cv.tensor];
         const double h = t.coef64[cv.tensor];     // the tensor's coefficient as computed, in double
+        const double uc = a.update_clip ? t.ucoef64[cv.tensor] : 1.0;   // update clipping: scales the direction
         const void* g = grad_chunk_ptr<BF16G>(ta.grad, cv.first);
         float* p = reinterpret_cast<float*>(ta.param) + cv.first;
         float* m = reinterpret_cast<float*>(ta.exp_avg) + cv.first;
@@ -595,7 +609,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                     for (int u = 0; u < U; ++u) {
                         const int idx = v0 + u * kBlock + tid;
                         const f32x4 p_old = pp[u];
-                        apply_vec<OPT>(a, h, gg[u], pp[u], mm[u], vv[u]);
+                        apply_vec<OPT>(a, h, uc, gg[u], pp[u], mm[u], vv[u]);
                         if constexpr (TELE) tele_vec<kHasV>(tele, p_old, pp[u], mm[u], vv[u]);
                         st<NTS>(p4 + idx, pp[u]);
                         st<NTS>(m4 + idx, mm[u]);
@@ -612,7 +626,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                         f32x4 vv = f32x4{0.f, 0.f, 0.f, 0.f};
                         if constexpr (kHasV) vv = ld<NTL>(v4 + idx);
                         const f32x4 p_old = pp;
-                        apply_vec<OPT>(a, h, gg, pp, mm, vv);
+                        apply_vec<OPT>(a, h, uc, gg, pp, mm, vv);
                         if constexpr (TELE) tele_vec<kHasV>(tele, p_old, pp, mm, vv);
                         st<NTS>(p4 + idx, pp);
                         st<NTS>(m4 + idx, mm);
@@ -623,7 +637,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                     if (j < cv.len) {
                         ElemState s = {p[j], m[j], kHasV ? v[j] : 0.f};
                         const float p_old = s.p;
-                        apply_elem<OPT>(a, h, load_grad1<BF16G>(g, j), s);
+                        apply_elem<OPT>(a, h, uc, load_grad1<BF16G>(g, j), s);
                         if constexpr (TELE) tele_elem<kHasV>(tele, p_old, s.p, s.m, s.v);
                         p[j] = s.p;
                         m[j] = s.m;
@@ -635,7 +649,7 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
                 for (int j = e0 + tid; j < e1; j += kBlock) {
                     ElemState s = {p[j], m[j], kHasV ? v[j] : 0.f};
                     const float p_old = s.p;
-                    apply_elem<OPT>(a, h, load_grad1<BF16G>(g, j), s);
+                    apply_elem<OPT>(a, h, uc, load_grad1<BF16G>(g, j), s);
                     if constexpr (TELE) tele_elem<kHasV>(tele, p_old, s.p, s.m, s.v);
                     p[j] = s.p;
                     m[j] = s.m;
@@ -662,6 +676,197 @@ __global__ __launch_bounds__(kBlock) void update_kernel(DeviceTables t, UpdateAr
             __syncthreads();
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Update clipping (AGC and Clippy rows of Table 2).  The coefficient of a tensor's update needs the norms
+// of theta and of the whole tensor's direction Delta, so the direction is evaluated twice: here for its
+// norms (nothing is written but two partial results per work item), then by update_kernel, which scales it.
+// Work items are those of update_kernel.  LINF selects maxima of |.| (Clippy) instead of sums of squares (AGC).
+
+// All 64 lanes must be active.  Returns the same value in every lane.  Maxima are exact in any order.
+__device__ __forceinline__ double wave_max_f64(double x)
+{
+    x = fmax(x, dpp_mov<0x128>(x));  // row_ror:8
+    x = fmax(x, dpp_mov<0x124>(x));  // row_ror:4
+    x = fmax(x, dpp_mov<0x122>(x));  // row_ror:2
+    x = fmax(x, dpp_mov<0x121>(x));  // row_ror:1
+    return fmax(fmax(readlane_f64(x, 0), readlane_f64(x, 16)), fmax(readlane_f64(x, 32), readlane_f64(x, 48)));
+}
+
+// The direction of one element for the unclipped gradient: AdamW m_hat/(sqrt(v_hat)+eps) from this step's
+// moments, Lion the sign of the interpolation.
+template <int OPT>
+__device__ __forceinline__ double direction_elem(const UpdateArgs& a, float g, float m_prev, float v_prev)
+{
+    const double gd = (double)g;
+    if constexpr (OPT == ADAGC_OPT_ADAMW) {
+        const double m = a.beta1 * (double)m_prev + a.one_minus_beta1 * gd;
+        const double v = a.beta2 * (double)v_prev + a.one_minus_beta2 * gd * gd;
+        return (m / a.bias1) / (sqrt(v * a.inv_bias2) + a.eps);
+    } else {
+        return lion_sign(a, gd, m_prev);
+    }
+}
+
+template <bool LINF>
+__device__ __forceinline__ void stat_acc(double (&acc)[2], float theta, double delta)
+{
+    const double th = (double)theta;
+    if constexpr (LINF) {
+        acc[0] = fmax(acc[0], fabs(th));       // a NaN never becomes the maximum
+        acc[1] = fmax(acc[1], fabs(delta));
+    } else {
+        acc[0] = fma(th, th, acc[0]);
+        acc[1] = fma(delta, delta, acc[1]);
+    }
+}
+
+template <int OPT, bool BF16G, bool LINF, bool NT>
+__global__ __launch_bounds__(kBlock) void direction_stats_kernel(DeviceTables t, UpdateArgs a, uint32_t items_per_chunk)
+{
+    constexpr int U = 4;
+    constexpr bool kHasV = (OPT == ADAGC_OPT_ADAMW);
+    constexpr int kTiles = kVecPerLane / U;
+    constexpr int kTileVecs = U * kBlock;
+    constexpr int kTileElems = kTileVecs * 4;
+    const int tid = threadIdx.x;
+    __shared__ double wave_part[2][kWavesPerBlock];
+
+    const uint32_t group = 8u * items_per_chunk;
+    const int tiles_per_item = kTiles / (int)items_per_chunk;
+    const uint64_t n_items = (((uint64_t)t.n_chunks + 7u) & ~(uint64_t)7u) * items_per_chunk;
+    for (uint64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const uint32_t r = (uint32_t)(item % group);
+        const uint32_t k = (uint32_t)(item / group) * 8u + (r & 7u);
+        const int isub = (int)(r >> 3);
+        if (k >= t.n_chunks) continue;
+        const uint32_t c = t.schedule ? t.schedule[k] : k;
+        const ChunkView cv = chunk_view(t, c);
+        const TensorArgs& ta = t.targs[cv.tensor];
+        const void* g = grad_chunk_ptr<BF16G>(ta.grad, cv.first);
+        const float* p = reinterpret_cast<const float*>(ta.param) + cv.first;
+        const float* m = reinterpret_cast<const float*>(ta.exp_avg) + cv.first;
+        const float* v = kHasV ? reinterpret_cast<const float*>(ta.exp_avg_sq) + cv.first : nullptr;
+        double acc[2] = {0.0, 0.0};
+
+#pragma unroll 1
+        for (int tt = 0; tt < tiles_per_item; ++tt) {
+            const int sub = isub * tiles_per_item + tt;
+            const int e0 = sub * kTileElems;
+            const int e1 = cv.len < e0 + kTileElems ? cv.len : e0 + kTileElems;
+            if (e0 >= e1) break;
+            if (ta.vec_ok) {
+                const f32x4* p4 = reinterpret_cast<const f32x4*>(p);
+                const f32x4* m4 = reinterpret_cast<const f32x4*>(m);
+                const f32x4* v4 = reinterpret_cast<const f32x4*>(v);
+                const int v0 = sub * kTileVecs;
+                const int vend = (e1 - e0 == kTileElems) ? v0 + kTileVecs : (cv.len >> 2);
+                if (e1 - e0 == kTileElems) {
+                    f32x4 gg[U], pp[U], mm[U], vv[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int idx = v0 + u * kBlock + tid;
+                        gg[u] = load_grad4<BF16G, NT>(g, idx);
+                        pp[u] = ld<NT>(p4 + idx);
+                        mm[u] = ld<NT>(m4 + idx);
+                        if constexpr (kHasV) vv[u] = ld<NT>(v4 + idx);
+                        else vv[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        stat_acc<LINF>(acc, pp[u].x, direction_elem<OPT>(a, gg[u].x, mm[u].x, vv[u].x));
+                        stat_acc<LINF>(acc, pp[u].y, direction_elem<OPT>(a, gg[u].y, mm[u].y, vv[u].y));
+                        stat_acc<LINF>(acc, pp[u].z, direction_elem<OPT>(a, gg[u].z, mm[u].z, vv[u].z));
+                        stat_acc<LINF>(acc, pp[u].w, direction_elem<OPT>(a, gg[u].w, mm[u].w, vv[u].w));
+                    }
+                } else {
+                    for (int idx = v0 + tid; idx < vend; idx += kBlock) {
+                        const f32x4 gg = load_grad4<BF16G, NT>(g, idx);
+                        const f32x4 pp = ld<NT>(p4 + idx);
+                        const f32x4 mm = ld<NT>(m4 + idx);
+                        f32x4 vv = f32x4{0.f, 0.f, 0.f, 0.f};
+                        if constexpr (kHasV) vv = ld<NT>(v4 + idx);
+                        stat_acc<LINF>(acc, pp.x, direction_elem<OPT>(a, gg.x, mm.x, vv.x));
+                        stat_acc<LINF>(acc, pp.y, direction_elem<OPT>(a, gg.y, mm.y, vv.y));
+                        stat_acc<LINF>(acc, pp.z, direction_elem<OPT>(a, gg.z, mm.z, vv.z));
+                        stat_acc<LINF>(acc, pp.w, direction_elem<OPT>(a, gg.w, mm.w, vv.w));
+                    }
+                    const int j = ((cv.len >> 2) << 2) + tid;      // up to three single elements at the ragged end
+                    if (j < cv.len)
+                        stat_acc<LINF>(acc, p[j], direction_elem<OPT>(a, load_grad1<BF16G>(g, j), m[j], kHasV ? v[j] : 0.f));
+                }
+            } else {
+                for (int j = e0 + tid; j < e1; j += kBlock)
+                    stat_acc<LINF>(acc, p[j], direction_elem<OPT>(a, load_grad1<BF16G>(g, j), m[j], kHasV ? v[j] : 0.f));
+            }
+        }
+
+        // every item of every chunk writes its two slots, an empty item writes zeros
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const double w = LINF ? wave_max_f64(acc[q]) : wave_sum_f64(acc[q]);
+            if ((tid & 63) == 0) wave_part[q][tid >> 6] = w;
+        }
+        __syncthreads();
+        if (tid < 2) {
+            double b = wave_part[tid][0];
+#pragma unroll
+            for (int w = 1; w < kWavesPerBlock; ++w) b = LINF ? fmax(b, wave_part[tid][w]) : b + wave_part[tid][w];
+            t.ustat_partials[((size_t)tid * t.n_chunks + c) * items_per_chunk + isub] = b;
+        }
+        __syncthreads();
+    }
+}
+
+// The maximum of a tensor's slots (any order gives the same value).
+__device__ __forceinline__ double tensor_slot_max(const DeviceTables& t, const double* slots, uint32_t i, double* wave_part,
+                                                  uint32_t slots_per_chunk)
+{
+    const uint32_t count = t.targs[i].chunk_count * slots_per_chunk;
+    const double* p = slots + (size_t)t.targs[i].chunk_begin * slots_per_chunk;
+    double a0 = 0.0;
+    for (uint32_t k = threadIdx.x; k < count; k += kBlock) a0 = fmax(a0, p[k]);
+    const double s = wave_max_f64(a0);
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = s;
+    __syncthreads();
+    double total = wave_part[0];
+#pragma unroll
+    for (int w = 1; w < kWavesPerBlock; ++w) total = fmax(total, wave_part[w]);
+    return total;
+}
+
+// One workgroup per tensor: the two norms from the item slots, then Table 2's AGC or Clippy coefficient.
+// The gradient's own coefficient is 1 in these modes.  Reported to the caller: the direction's norm,
+// the update coefficient, and whether it is below 1.
+__global__ __launch_bounds__(kBlock) void finalize_update_clip_kernel(DeviceTables t, RuleArgs r, uint32_t items_per_chunk)
+{
+    __shared__ double wave_part[kWavesPerBlock];
+    const uint32_t i = blockIdx.x;
+    const bool linf = r.mode == ADAGC_MODE_CLIPPY;
+    double stat[2];
+    for (int q = 0; q < 2; ++q) {
+        const double* slots = t.ustat_partials + (size_t)q * t.n_chunks * items_per_chunk;
+        stat[q] = linf ? tensor_slot_max(t, slots, i, wave_part, items_per_chunk)
+                       : tensor_slot_sum(t, slots, i, wave_part, items_per_chunk);
+        __syncthreads();
+    }
+    if (threadIdx.x != 0) return;
+    double ratio, delta_norm;
+    if (linf) {
+        delta_norm = stat[1];
+        ratio = __ddiv_rn(__dadd_rn(__dmul_rn(r.lambda_rel, stat[0]), r.lambda_abs), __dmul_rn(r.lr, delta_norm));
+    } else {
+        delta_norm = sqrt(stat[1]);
+        ratio = __ddiv_rn(__dmul_rn(r.lambda_rel, sqrt(stat[0])), delta_norm);
+    }
+    const bool active = ratio < 1.0;              // false for NaN (0/0): the update is left alone
+    const double c = active ? ratio : 1.0;
+    t.norm[i] = (float)delta_norm;
+    t.coef[i] = (float)c;
+    t.ucoef64[i] = c;
+    t.coef64[i] = 1.0;
+    t.flag[i] = active ? 1 : 0;
 }
 
 // Telemetry finalize: per tensor, the three norms from the item slots (same fixed order as K2).
@@ -740,6 +945,29 @@ hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleA
     if (e != hipSuccess) return e;
     const uint32_t blocks = (t.n_tensors + kBlock - 1) / kBlock;
     finalize_global_kernel<<<dim3(blocks), dim3(kBlock), 0, stream>>>(t, ema, r);
+    return hipGetLastError();
+}
+
+using StatsFn = void (*)(DeviceTables, UpdateArgs, uint32_t);
+
+template <int OPT, bool BF16G>
+static StatsFn select_stats_flags(bool linf, int nt)
+{
+    if (linf) return nt ? direction_stats_kernel<OPT, BF16G, true, true> : direction_stats_kernel<OPT, BF16G, true, false>;
+    return nt ? direction_stats_kernel<OPT, BF16G, false, true> : direction_stats_kernel<OPT, BF16G, false, false>;
+}
+
+hipError_t launch_update_clip_rule(const DeviceTables& t, const UpdateArgs& u, const RuleArgs& r, int optimizer,
+                                   int grad_bf16, int items_per_chunk, int nt, int grid, hipStream_t stream)
+{
+    const bool linf = r.mode == ADAGC_MODE_CLIPPY;
+    StatsFn fn;
+    if (optimizer == ADAGC_OPT_LION) fn = grad_bf16 ? select_stats_flags<ADAGC_OPT_LION, true>(linf, nt) : select_stats_flags<ADAGC_OPT_LION, false>(linf, nt);
+    else fn = grad_bf16 ? select_stats_flags<ADAGC_OPT_ADAMW, true>(linf, nt) : select_stats_flags<ADAGC_OPT_ADAMW, false>(linf, nt);
+    fn<<<dim3(grid), dim3(kBlock), 0, stream>>>(t, u, (uint32_t)items_per_chunk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    finalize_update_clip_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t, r, (uint32_t)items_per_chunk);
     return hipGetLastError();
 }
 

@@ -94,14 +94,14 @@ extern "C" int adagc_step_static(const adagc_tensor_desc* descs, int64_t n_tenso
     if (cfg->has_bf16_param_copy != 0 && cfg->has_bf16_param_copy != 1) return ADAGC_ERR_INVALID_ARG;
     // no telemetry and no launch tuning here: the defaults, chunks in list order
     if (cfg->telemetry != 0 || cfg->grid_blocks != 0 || cfg->unroll != 0 || cfg->nontemporal != 0 ||
-        cfg->schedule != 0 || cfg->update_split != 0 || cfg->schedule_run != 0)
+        cfg->schedule != 0 || cfg->update_split != 0 || cfg->schedule_run != 0 || cfg->update_clipping != 0)
         return ADAGC_ERR_INVALID_ARG;
     const bool adamw = cfg->optimizer == ADAGC_OPT_ADAMW;
     const bool bf16g = cfg->grad_dtype == ADAGC_GRAD_BF16;
     const bool copy = cfg->has_bf16_param_copy != 0;
     if (adamw && !exp_avg_sq) return ADAGC_ERR_INVALID_ARG;
     if (copy && !params_bf16) return ADAGC_ERR_INVALID_ARG;
-    if (!hyper_ok(*hp, cfg->optimizer)) return ADAGC_ERR_INVALID_ARG;
+    if (!hyper_ok(*hp, cfg->optimizer) || hp->clip_mode > ADAGC_MODE_ZCLIP) return ADAGC_ERR_INVALID_ARG;
     if (n_tensors > (int64_t)kMaxT) return ADAGC_ERR_TOO_LARGE;
 
     // Everything is validated before anything is enqueued: one pass over the list.

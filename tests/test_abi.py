@@ -28,7 +28,7 @@ def test_header_symbols_are_exported():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.adagc_tensor_desc) == 16
-    assert ctypes.sizeof(B.adagc_config) == 40
+    assert ctypes.sizeof(B.adagc_config) == 44
     assert ctypes.sizeof(B.adagc_step_params) == 56
     assert ctypes.sizeof(B.adagc_hyper) == 44
 
@@ -137,5 +137,5 @@ int main(void)
                     str(src), "-o", exe, lib, "-Wl,-rpath," + os.path.dirname(lib)], check=True)
     res = subprocess.run([exe], capture_output=True, text=True, timeout=60)
     assert res.returncode == 0, res.stdout + res.stderr
-    assert res.stdout.split()[:3] == ["16", "40", "44"]
+    assert res.stdout.split()[:3] == ["16", "44", "44"]
     assert "wrong state" in res.stdout

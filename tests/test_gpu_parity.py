@@ -44,7 +44,8 @@ def trajectory(run, hp, steps, name, lockstep=False):
                         None if (warm or hp.clip_mode != B.ADAGC_MODE_ADAGC) else thr)
         exempt = None
         if run.optimizer == B.ADAGC_OPT_LION:
-            exempt = [run.lion_exempt(i, grads_np[i], m_before[i], ref_coefs[i], hp)
+            update_clip = hp.clip_mode in (B.ADAGC_MODE_AGC, B.ADAGC_MODE_CLIPPY)     # the gradient is not scaled there
+            exempt = [run.lion_exempt(i, grads_np[i], m_before[i], 1.0 if update_clip else ref_coefs[i], hp)
                       for i in range(run.w.n_tensors)]
         if lockstep or step == steps or step in run.w.spikes:
             differ = run.compare_state("%s step %d" % (name, step), exempt)
@@ -332,6 +333,70 @@ def test_zclip_mode_z_score_of_the_global_norm():
         with pytest.raises(B.AdagcError) as e:
             run.ctx.step(run.params, grads, run.m, run.v, run.gamma, B.make_hyper(clip_mode=B.ADAGC_MODE_ZCLIP, z_thres=bad), 13)
         assert e.value.code == B.ADAGC_ERR_INVALID_ARG
+
+
+def _update_clip_workload(lion=False):
+    """Matrices (theta ~ 0.02), norm weights (theta = 1) and biases (theta = 0), ragged sizes, several chunks."""
+    specs = W.gpt2_like_list(2, 128, 512, 1024, 0) + W.ragged_stress_list(10, 1 << 16, (3 * 16384 + 5,))
+    return W.Workload(specs, sigma_lo=1e-3, sigma_hi=1e-1, bf16_copy=True,
+                      grad_dtype=torch.bfloat16 if lion else torch.float32)
+
+
+@pytest.mark.parametrize("optimizer", ["adamw", "lion"])
+def test_agc_mode_update_clipping_by_weight_norm(optimizer):
+    """Table 2's AGC row: the gradient is left alone, each tensor's direction is scaled by
+    min{1, lambda_rel ||theta|| / ||Delta||}.  lambda_rel 20: matrices are clipped (ratio ~0.4), norm weights
+    are not (ratio ~20), zero-initialised biases get coefficient 0 and stay where they are."""
+    w = _update_clip_workload(optimizer == "lion")
+    run = P.Run(w, optimizer=optimizer, update_clipping=True)
+    hp = (B.make_hyper(lambda_rel=20.0, clip_mode=B.ADAGC_MODE_AGC) if optimizer == "adamw" else
+          B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, lambda_rel=20.0, clip_mode=B.ADAGC_MODE_AGC))
+    run.gamma.fill_(5.0)
+    run.h_gamma[:] = 5.0
+    trajectory(run, hp, 4, "agc-" + optimizer, lockstep=True)
+    norms, coefs, flags = run.ctx.get_norms()
+    kinds = np.array([s.kind for s in w.specs])
+    assert flags[kinds == "bias"].all() and (coefs[kinds == "bias"] == 0.0).all()
+    assert not flags[kinds == "norm"].any() and (coefs[kinds == "norm"] == 1.0).all()
+    big = np.array([s.kind == "matrix" and s.numel > 1000 for s in w.specs])
+    assert flags[big].all() and (coefs[big] > 0.0).all() and (coefs[big] < 1.0).all()
+    assert (to_numpy(run.gamma) == 5.0).all()                       # no state
+    for i in np.nonzero(kinds == "bias")[0]:
+        assert not to_numpy(run.params[i]).any()                    # never moved
+    # the scratch must have been reserved at creation
+    plain = P.Run(W.Workload(w.specs[:3]), mirror=False)
+    with pytest.raises(B.AdagcError) as e:
+        plain.gpu_step(plain.w.make_grads(1, DEV), B.make_hyper(clip_mode=B.ADAGC_MODE_AGC), 1)
+    assert e.value.code == B.ADAGC_ERR_STATE
+
+
+@pytest.mark.parametrize("optimizer", ["adamw", "lion"])
+def test_clippy_mode_update_clipping_by_weight_max(optimizer):
+    """Table 2's Clippy row with l-infinity norms: (lambda_rel max|theta| + lambda_abs) / (lr max|Delta|)."""
+    w = _update_clip_workload(optimizer == "lion")
+    run = P.Run(w, optimizer=optimizer, update_clipping=True)
+    hp = (B.make_hyper(lr=0.05, lambda_rel=0.5, lambda_abs=0.02, clip_mode=B.ADAGC_MODE_CLIPPY) if optimizer == "adamw"
+          else B.make_hyper(lr=0.05, beta1=0.9, beta2=0.99, lambda_rel=0.5, lambda_abs=0.02, clip_mode=B.ADAGC_MODE_CLIPPY))
+    clipped = trajectory(run, hp, 4, "clippy-" + optimizer, lockstep=True)
+    assert 10 < clipped < 4 * w.n_tensors - 10                      # clipped and unclipped tensors both occurred
+    # the same context goes back to the paper's method: the update coefficient must not linger
+    hp0 = B.make_hyper(t_start=0) if optimizer == "adamw" else B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, t_start=0)
+    run.gamma.fill_(1e-2)
+    for step in (5, 6):
+        run.h_params = [to_numpy(t) for t in run.params]
+        run.h_m = [to_numpy(t) for t in run.m]
+        if run.v is not None:
+            run.h_v = [to_numpy(t) for t in run.v]
+        run.h_gamma = to_numpy(run.gamma)
+        grads = w.make_grads(step, DEV)
+        norms, coefs, flags = run.gpu_step(grads, hp0, step)
+        rn, rc, rf, thr = run.oracle_step([to_numpy(g) for g in grads], hp0, step)
+        P.check_scalars("clippy-then-adagc step %d" % step, norms, coefs, flags, to_numpy(run.gamma), rn, rc, rf,
+                        run.h_gamma, thr)
+        exempt = None
+        if optimizer == "lion":
+            continue                                                  # the AdamW run checks the state below
+        run.compare_state("clippy-then-adagc step %d" % step, exempt)
 
 
 def _telemetry_case(optimizer, w, hp, name, **knobs):
@@ -677,6 +742,15 @@ def _teeth_scenarios():
     w = W.Workload(specs, spikes={t: (every, f) for t, f in scale.items()})
     hp = B.make_hyper(t_start=2, lambda_abs=1.2 * model_norm, clip_mode=B.ADAGC_MODE_ZCLIP, ema_beta=0.75, z_thres=2.0)
     trajectory(P.Run(w), hp, 7, "teeth-zclip", lockstep=True)
+    # AGC and Clippy: clipped and unclipped tensors, with weight decay, AdamW and Lion
+    w = W.Workload(W.gpt2_like_list(1, 64, 256, 300, 0), sigma_lo=1e-3, sigma_hi=1e-1)
+    trajectory(P.Run(w, update_clipping=True), B.make_hyper(lambda_rel=20.0, clip_mode=B.ADAGC_MODE_AGC, eps=1e-3), 3,
+               "teeth-agc", lockstep=True)
+    trajectory(P.Run(w, update_clipping=True), B.make_hyper(lr=0.05, lambda_rel=0.5, lambda_abs=0.02,
+                                                            clip_mode=B.ADAGC_MODE_CLIPPY), 3, "teeth-clippy", lockstep=True)
+    trajectory(P.Run(w, optimizer="lion", update_clipping=True),
+               B.make_hyper(lr=1e-3, beta1=0.9, beta2=0.99, lambda_rel=20.0, clip_mode=B.ADAGC_MODE_AGC), 3, "teeth-agc-lion",
+               lockstep=True)
 
 
 def test_parity_comparisons_notice_a_wrong_oracle(tmp_path):

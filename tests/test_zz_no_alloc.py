@@ -111,7 +111,7 @@ def test_static_step_rejects_what_does_not_fit():
     # launch tuning is not available here
     L = B.lib()
     import ctypes
-    cfg = B.adagc_config(0, 0, 0, 1, 0, 0, 0, 0, 0, 0)     # telemetry = 1
+    cfg = B.adagc_config(0, 0, 0, 1, 0, 0, 0, 0, 0, 0, 0)     # telemetry = 1
     descs = B._descs([16])
     p = B.ptr_array([one])
     rc = L.adagc_step_static(ctypes.cast(descs, ctypes.c_void_p), 1, ctypes.byref(cfg), p, p, p, p, None,

@@ -164,7 +164,8 @@ def main():
     ap.add_argument("--schedule-run", type=int, default=0, help="launch tuning: chunks an XCD takes in a row")
     ap.add_argument("--update-split", type=int, default=0, help="launch tuning: work items of the update kernel per chunk")
     ap.add_argument("--telemetry", action="store_true", help="also reduce per-tensor |m|, |v|, |update| norms")
-    ap.add_argument("--clip-mode", type=int, default=0, help="0 AdaGC (default), 1 GlobalGC, 2 Global AdaGC")
+    ap.add_argument("--clip-mode", type=int, default=0,
+                    help="0 AdaGC (default), 1 GlobalGC, 2 Global AdaGC, 3 ZClip, 4 AGC, 5 Clippy (the paper's settings for each)")
     ap.add_argument("--t-start", type=int, default=1, help="warm-up steps (1 = only the initialising step)")
     ap.add_argument("--alloc-order", default="good", choices=["good", "slow"],
                     help="good: gradients, params, m, v, copies; slow: params, m, v, copies, gradients")
@@ -195,6 +196,13 @@ def main():
     grad_dtype = B.ADAGC_GRAD_BF16 if w.grad_dtype == torch.bfloat16 else B.ADAGC_GRAD_F32
     rule = dict(t_start=args.t_start, clip_mode=args.clip_mode,
                 lambda_abs=1.0 if (args.clip_mode or args.t_start > 1) else float("inf"))
+    if args.clip_mode == 3:
+        rule.update(ema_beta=0.97, z_thres=2.0)            # appendix "Clipping Hyper-Parameters"
+    elif args.clip_mode == 4:
+        rule.update(lambda_rel=1e-3)
+    elif args.clip_mode == 5:
+        rule.update(lambda_rel=1e-2, lambda_abs=0.5)
+    update_clip = args.clip_mode in (4, 5)
     hp = (B.make_hyper(lr=1e-4, beta1=0.9, beta2=0.99, weight_decay=0.1, **rule) if lion else B.make_hyper(**rule))
 
     # Gradient batches, resident: the workload's own generator and spike schedule.  Step t of the run
@@ -223,7 +231,7 @@ def main():
     ctx = B.AdaGC(w.numels, optimizer, grad_dtype, w.bf16_copy, grid_blocks=args.grid_blocks,
                   unroll=args.unroll, nontemporal=args.nontemporal, schedule=args.schedule,
                   telemetry=args.telemetry, update_split=args.update_split,
-                  schedule_run=args.schedule_run)
+                  schedule_run=args.schedule_run, update_clipping=update_clip)
     if copies is not None:
         ctx.set_param_copies(copies)
     p_ptr, m_ptr = B.ptr_array(params), B.ptr_array(m)
@@ -256,6 +264,8 @@ def main():
 
     n = w.total_params
     rd, ur, uw = algorithmic_bytes(args.workload)
+    if update_clip:
+        rd = ur                # the first pass reads g, theta, m, v for the direction's norms instead of g alone
     ms_per_step = float(np.median(step_ms))
     ms_wall_mean = (t1 - t0) / args.steps * 1e3
     bytes_two_pass = (rd + ur + uw) * n

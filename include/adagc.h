@@ -133,7 +133,10 @@ typedef struct {
     float   ema_beta;      /* beta of the EMA in Eq. 3, in [0, 1) */
     float   lambda_abs;    /* GlobalGC threshold of the warm-up (Eq. 2); +inf disables it */
     int32_t t_start;       /* number of warm-up steps: steps 1..t_start take the warm-up branch.
-                              0 = never (ema_norms must then be pre-filled by the caller) */
+                              0 = never: ema_norms must then be pre-filled by the caller.  Eq. 3 is applied as
+                              printed, so a tensor whose gamma is 0 gets threshold 0, coefficient 0 (visible in
+                              adagc_get_norms) and a gamma that stays 0: the warm-up branch is what initialises
+                              gamma, and at least one warm-up step (t_start >= 1) is the intended use */
     int32_t clip_mode;     /* ADAGC_MODE_*; 0 = the paper's method */
     float   z_thres;       /* ADAGC_MODE_ZCLIP only: z-score threshold, > 0 (+inf: never clip); ignored otherwise */
 } adagc_hyper;

@@ -335,6 +335,21 @@ int adagc_get_segment_table(adagc_ctx* ctx, int64_t* chunk_begin, uint32_t* chun
 int adagc_profile_begin(adagc_ctx* ctx, int32_t max_steps);
 int adagc_profile_end(adagc_ctx* ctx, float* ms, int32_t* n_steps);
 
+/*
+ * Building block of the Muon path, exported so that it can be checked on its own: the bf16 matrix-core
+ * product of the Newton-Schulz iteration (the orthogonalisation step of Muon, the optimizer the paper pairs
+ * AdaGC with in "Optimizer Compatibility: Muon and Lion", Sec. 5.4; the iteration itself is not printed there),
+ *     C[i][j] = bf16( alpha * sum_k P[i][k] Q[j][k] + beta * D[i][j] ),   fp32 accumulation,
+ * enqueued on `stream`.  All matrices DEVICE, bf16, row-major:
+ *   P   M x K, leading dimension ldp        Q   N x K, ldq          (both operands K-contiguous)
+ *   Dt  N x M, lddt: the TRANSPOSE of D, or NULL (then beta is ignored)
+ *   C   M x N, ldc, or NULL                 Ct  N x M, ldct: the transpose of the result, or NULL (one of the two)
+ * M, N must be multiples of 128, K of 64, every leading dimension of 8.  Errors: INVALID_ARG, TOO_LARGE, HIP.
+ */
+int adagc_muon_gemm_nt(const void* P, int64_t ldp, const void* Q, int64_t ldq, int64_t M, int64_t N, int64_t K,
+                       float alpha, float beta, const void* Dt, int64_t lddt, void* C, int64_t ldc, void* Ct,
+                       int64_t ldct, void* stream);
+
 /* Static description of an error code. */
 const char* adagc_strerror(int code);
 

@@ -27,7 +27,7 @@ ADAGC_MODE_AGC, ADAGC_MODE_CLIPPY = 4, 5
 EXPORTS = [
     "adagc_chunk_elems", "adagc_build_segment_table", "adagc_build_visiting_order", "adagc_create", "adagc_destroy",
     "adagc_set_param_copies", "adagc_step", "adagc_step_graph", "adagc_step_static", "adagc_get_norms", "adagc_get_state_norms", "adagc_num_tensors",
-    "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end",
+    "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end", "adagc_muon_gemm_nt",
     "adagc_strerror",
 ]
 
@@ -110,6 +110,9 @@ def lib():
     L.adagc_profile_begin.argtypes = [vp, i32]
     L.adagc_profile_end.restype = ctypes.c_int
     L.adagc_profile_end.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    L.adagc_muon_gemm_nt.restype = ctypes.c_int
+    L.adagc_muon_gemm_nt.argtypes = [vp, i64, vp, i64, i64, i64, i64, ctypes.c_float, ctypes.c_float, vp, i64, vp, i64,
+                                     vp, i64, vp]
     L.adagc_strerror.restype = ctypes.c_char_p
     L.adagc_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -179,6 +182,18 @@ def adagc_build_visiting_order(n_chunks, parts=2, run=8):
                                             order.ctypes.data if order.size else None),
            "adagc_build_visiting_order")
     return order
+
+
+def adagc_muon_gemm_nt(P, Q, alpha=1.0, beta=0.0, Dt=None, C=None, Ct=None, stream=None):
+    """adagc_muon_gemm_nt on 2-D bf16 device tensors (row-major, possibly with a leading dimension larger than
+    the row length): C = bf16(alpha P Q^T + beta D), D passed as its transpose Dt."""
+    M, K = P.shape
+    N = Q.shape[0]
+    ld = lambda t: t.stride(0) if t is not None else 0
+    dp = lambda t: t.data_ptr() if t is not None else None
+    _check(lib().adagc_muon_gemm_nt(P.data_ptr(), ld(P), Q.data_ptr(), ld(Q), M, N, K, float(alpha), float(beta), dp(Dt),
+                                    ld(Dt), dp(C), ld(C), dp(Ct), ld(Ct), ctypes.c_void_p(stream) if stream else None),
+           "adagc_muon_gemm_nt")
 
 
 ADAGC_STATIC_MAX_TENSORS = 32768

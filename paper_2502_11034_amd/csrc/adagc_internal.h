@@ -159,6 +159,11 @@ hipError_t launch_update(const DeviceTables& t, const UpdateArgs& u, int optimiz
 // per tensor turns them into the tensor's update coefficient.
 hipError_t launch_update_clip_rule(const DeviceTables& t, const UpdateArgs& u, const RuleArgs& r, int optimizer,
                                    int grad_bf16, int items_per_chunk, int nt, int grid, hipStream_t stream);
+// bf16 matrix-core GEMM of the Newton-Schulz iteration (muon_gemm.hip): C = bf16(alpha P Q^T + beta D), D given
+// through its transpose Dt, result written row-major (C), transposed (Ct) or both.
+hipError_t launch_gemm_nt_bf16(const void* P, int ldp, const void* Q, int ldq, int M, int N, int K, float alpha,
+                               float beta, const void* Dt, int lddt, void* C, int ldc, void* Ct, int ldct,
+                               hipStream_t stream);
 // Rule stage of adagc_step_graph: scalars from device-resident step parameters, then the per-tensor
 // sums, the model-wide rule (a no-op outside warm-up and the global modes) and the per-tensor rule.
 hipError_t launch_rules_from_device(const DeviceTables& t, float* ema, const adagc_step_params* params,

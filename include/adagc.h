@@ -52,6 +52,7 @@ extern "C" {
 
 #define ADAGC_OPT_ADAMW 0
 #define ADAGC_OPT_LION  1
+#define ADAGC_OPT_MUON  2   /* every tensor is a matrix; stepped with adagc_muon_step after adagc_muon_attach */
 #define ADAGC_GRAD_F32  0
 #define ADAGC_GRAD_BF16 1
 
@@ -334,6 +335,49 @@ int adagc_get_segment_table(adagc_ctx* ctx, int64_t* chunk_begin, uint32_t* chun
  */
 int adagc_profile_begin(adagc_ctx* ctx, int32_t max_steps);
 int adagc_profile_end(adagc_ctx* ctx, float* ms, int32_t* n_steps);
+
+/*
+ * Muon with AdaGC's clipped gradient, for a context created with ADAGC_OPT_MUON (every tensor of the list a
+ * matrix).  The paper pairs AdaGC with Muon ("Optimizer Compatibility: Muon and Lion", Sec. 5.4) and prints no
+ * rule for it; this is the published one, with h_i g_i in the place of the gradient as Alg. 1 does for AdamW:
+ *     M_i <- mu M_i + h_i g_i;   U = h_i g_i + mu M_i (nesterov) or M_i;
+ *     X = U / (||U||_F + 1e-7), transposed if rows > cols;
+ *     ns_steps times:  A = X X^T;  B = b A + c A A;  X <- a X + B X,   (a, b, c) = (3.4445, -4.7750, 2.0315),
+ *         X, A, B stored as bf16, products on the matrix cores with fp32 accumulation;
+ *     theta_i <- theta_i - lr (weight_decay theta_i + sqrt(max(1, rows/cols)) X).
+ * h_i comes from the same norm pass and rule as in adagc_step (clip modes 0 to 3).
+ */
+typedef struct {
+    int64_t rows, cols;        /* rows * cols = the tensor's numel; row-major */
+} adagc_matrix_shape;
+
+typedef struct {
+    float   momentum;          /* mu in [0, 1); the published default is 0.95 */
+    int32_t nesterov;          /* 1: U = h g + mu M (published default); 0: U = M */
+    int32_t ns_steps;          /* Newton-Schulz steps, 0 to 16 (published default 5; 0 applies the normalised U itself) */
+    int32_t reserved;          /* must be 0 */
+} adagc_muon_hyper;
+
+/*
+ * Give the context the matrices' shapes and allocate the Newton-Schulz workspace (bf16, sized for the largest
+ * matrix: four copies of its padded min x max extent and two of min x min).  Once per context.
+ *   shapes  HOST  n_tensors entries, copied
+ * Errors: INVALID_ARG (shape does not match numel), STATE (context not ADAGC_OPT_MUON, or attached already),
+ * TOO_LARGE (a padded dimension beyond 2^31-1), OOM, HIP.
+ */
+int adagc_muon_attach(adagc_ctx* ctx, const adagc_matrix_shape* shapes);
+
+/*
+ * One Muon step over the whole list, enqueued on `stream`; allocates nothing.
+ *   params, grads, ema_norms, hp, step, stream   as for adagc_step (hp->beta1, beta2, eps are ignored;
+ *                                                 hp->clip_mode 0 to 3)
+ *   momentum   HOST array of n_tensors DEVICE pointers, fp32, updated in place      (M_i)
+ *   mh         HOST Muon's own hyper-parameters
+ * bf16 parameter copies are written if the context has them.
+ * Errors: INVALID_ARG, STATE (not attached; copies expected but not set), HIP.
+ */
+int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* const* grads, void* const* momentum,
+                    float* ema_norms, const adagc_hyper* hp, const adagc_muon_hyper* mh, int64_t step, void* stream);
 
 /*
  * Building block of the Muon path, exported so that it can be checked on its own: the bf16 matrix-core

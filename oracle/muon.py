@@ -50,24 +50,37 @@ def bf16_bits(x):
     return (np.ascontiguousarray(x, dtype=np.float64).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
 
 
-def newton_schulz(u, steps=5, coeffs=NS_COEFFS, storage="bf16", trace=None):
-    """The iteration above on one matrix (float64 in, float64 out, same shape).  trace: a list that
-    receives (name, matrix) for every stored intermediate, in the order they are produced."""
+def ns_iterate(x, steps, coeffs=NS_COEFFS, storage="bf16", trace=None):
+    """`steps` passes of A = X X^T; B = b A + c A A; X <- a X + B X on an already normalised wide matrix."""
     a, b, c = coeffs
     rnd = to_bf16 if storage == "bf16" else (lambda z: z)
-    u = np.asarray(u, dtype=np.float64)
-    flip = u.shape[0] > u.shape[1]
-    x = u.T if flip else u
-    x = rnd(x / (math.sqrt(float(np.sum(u * u))) + NS_EPS))
-    if trace is not None:
-        trace.append(("X0", x))
+    x = np.asarray(x, dtype=np.float64)
     for k in range(steps):
         gram = rnd(x @ x.T)
         poly = rnd(b * gram + c * (gram @ gram))
         x = rnd(a * x + poly @ x)
         if trace is not None:
             trace += [("A%d" % (k + 1), gram), ("B%d" % (k + 1), poly), ("X%d" % (k + 1), x)]
-    return x.T if flip else x
+    return x
+
+
+def normalise(u, storage="bf16"):
+    """X0: U over its Frobenius norm (plus the 1e-7 guard), transposed if it is tall, as stored."""
+    rnd = to_bf16 if storage == "bf16" else (lambda z: z)
+    u = np.asarray(u, dtype=np.float64)
+    x = u.T if u.shape[0] > u.shape[1] else u
+    return rnd(x / (math.sqrt(float(np.sum(u * u))) + NS_EPS))
+
+
+def newton_schulz(u, steps=5, coeffs=NS_COEFFS, storage="bf16", trace=None):
+    """The iteration above on one matrix (float64 in, float64 out, same shape).  trace: a list that
+    receives (name, matrix) for every stored intermediate, in the order they are produced."""
+    u = np.asarray(u, dtype=np.float64)
+    x = normalise(u, storage)
+    if trace is not None:
+        trace.append(("X0", x))
+    x = ns_iterate(x, steps, coeffs, storage, trace)
+    return x.T if u.shape[0] > u.shape[1] else x
 
 
 def ns_scalar_map(sigma, steps=5, coeffs=NS_COEFFS):

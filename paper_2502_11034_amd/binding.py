@@ -19,7 +19,7 @@ ADAGC_ERR_HIP = -3
 ADAGC_ERR_TOO_LARGE = -4
 ADAGC_ERR_STATE = -5
 
-ADAGC_OPT_ADAMW, ADAGC_OPT_LION = 0, 1
+ADAGC_OPT_ADAMW, ADAGC_OPT_LION, ADAGC_OPT_MUON = 0, 1, 2
 ADAGC_GRAD_F32, ADAGC_GRAD_BF16 = 0, 1
 ADAGC_MODE_ADAGC, ADAGC_MODE_GLOBALGC, ADAGC_MODE_GLOBAL_ADAGC, ADAGC_MODE_ZCLIP = 0, 1, 2, 3
 ADAGC_MODE_AGC, ADAGC_MODE_CLIPPY = 4, 5
@@ -27,7 +27,7 @@ ADAGC_MODE_AGC, ADAGC_MODE_CLIPPY = 4, 5
 EXPORTS = [
     "adagc_chunk_elems", "adagc_build_segment_table", "adagc_build_visiting_order", "adagc_create", "adagc_destroy",
     "adagc_set_param_copies", "adagc_step", "adagc_step_graph", "adagc_step_static", "adagc_get_norms", "adagc_get_state_norms", "adagc_num_tensors",
-    "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end", "adagc_muon_gemm_nt",
+    "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end", "adagc_muon_gemm_nt", "adagc_muon_attach", "adagc_muon_step",
     "adagc_strerror",
 ]
 
@@ -51,6 +51,15 @@ class adagc_hyper(ctypes.Structure):
                 ("lambda_rel", ctypes.c_float), ("ema_beta", ctypes.c_float),
                 ("lambda_abs", ctypes.c_float), ("t_start", ctypes.c_int32), ("clip_mode", ctypes.c_int32),
                 ("z_thres", ctypes.c_float)]
+
+
+class adagc_matrix_shape(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int64), ("cols", ctypes.c_int64)]
+
+
+class adagc_muon_hyper(ctypes.Structure):
+    _fields_ = [("momentum", ctypes.c_float), ("nesterov", ctypes.c_int32), ("ns_steps", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 class adagc_step_params(ctypes.Structure):
@@ -110,6 +119,10 @@ def lib():
     L.adagc_profile_begin.argtypes = [vp, i32]
     L.adagc_profile_end.restype = ctypes.c_int
     L.adagc_profile_end.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    L.adagc_muon_attach.restype = ctypes.c_int
+    L.adagc_muon_attach.argtypes = [vp, vp]
+    L.adagc_muon_step.restype = ctypes.c_int
+    L.adagc_muon_step.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(adagc_hyper), ctypes.POINTER(adagc_muon_hyper), i64, vp]
     L.adagc_muon_gemm_nt.restype = ctypes.c_int
     L.adagc_muon_gemm_nt.argtypes = [vp, i64, vp, i64, i64, i64, i64, ctypes.c_float, ctypes.c_float, vp, i64, vp, i64,
                                      vp, i64, vp]
@@ -258,6 +271,18 @@ class AdaGC:
         _check(lib().adagc_step(self._ctx, p, g, m, v, ema_norms.data_ptr(), ctypes.byref(hyper), int(step),
                                 ctypes.c_void_p(stream) if stream else None), "adagc_step")
 
+    # -- adagc_muon_attach / adagc_muon_step
+    def muon_attach(self, shapes):
+        arr = (adagc_matrix_shape * len(shapes))()
+        for i, (r, c) in enumerate(shapes):
+            arr[i].rows, arr[i].cols = int(r), int(c)
+        _check(lib().adagc_muon_attach(self._ctx, ctypes.cast(arr, ctypes.c_void_p)), "adagc_muon_attach")
+
+    def muon_step(self, params, grads, momentum, ema_norms, hyper, muon_hyper, step, stream=None):
+        p, g, m = (ptr_array(x) for x in (params, grads, momentum))
+        _check(lib().adagc_muon_step(self._ctx, p, g, m, ema_norms.data_ptr(), ctypes.byref(hyper), ctypes.byref(muon_hyper),
+                                     int(step), ctypes.c_void_p(stream) if stream else None), "adagc_muon_step")
+
     # -- adagc_step_graph
     def step_graph(self, params, grads, exp_avg, exp_avg_sq, ema_norms, step_params, stream=None):
         """As step(), with hyper-parameters and step number read on the GPU from `step_params`: a device
@@ -308,6 +333,10 @@ class AdaGC:
         n = ctypes.c_int32(0)
         _check(lib().adagc_profile_end(self._ctx, ms.ctypes.data, ctypes.byref(n)), "adagc_profile_end")
         return ms[:3 * n.value].reshape(n.value, 3).copy()
+
+
+def make_muon_hyper(momentum=0.95, nesterov=True, ns_steps=5):
+    return adagc_muon_hyper(momentum, int(bool(nesterov)), int(ns_steps), 0)
 
 
 def make_hyper(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, lambda_rel=1.04,

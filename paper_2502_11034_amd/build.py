@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadagc.so")
-SOURCES = ["api.cpp", "segment_table.cpp", "kernels.hip", "static_step.hip", "muon_gemm.hip"]
+SOURCES = ["api.cpp", "segment_table.cpp", "kernels.hip", "static_step.hip", "muon_gemm.hip", "muon.hip"]
 HEADERS = [os.path.join(ROOT, "include", "adagc.h"), os.path.join(CSRC, "adagc_internal.h")]
 
 

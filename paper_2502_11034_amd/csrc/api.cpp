@@ -41,6 +41,11 @@ struct adagc_ctx {
     uint64_t     uploads = 0;                 // tables uploaded so far; slot = uploads % kStagingSlots
     bool         device_scalars_used = false;   // adagc_step_graph was called: its status word is meaningful
 
+    // Muon (adagc_muon_attach): shapes and the Newton-Schulz workspace, carved out of one allocation
+    std::vector<adagc_matrix_shape> shapes;
+    void*     muon_ws = nullptr;
+    uint16_t *ws_x[2] = {nullptr, nullptr}, *ws_y[2] = {nullptr, nullptr}, *ws_a = nullptr, *ws_b = nullptr;
+
     std::vector<hipEvent_t> prof_events;      // 4 per step while profiling
     int32_t                 prof_capacity = 0;
     int32_t                 prof_steps = 0;
@@ -76,6 +81,7 @@ void free_ctx(adagc_ctx* c)
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->upload_done)
         if (e) (void)hipEventDestroy(e);
+    if (c->muon_ws) (void)hipFree(c->muon_ws);
     if (c->staging) (void)hipHostFree(c->staging);
     if (c->slab) (void)hipFree(c->slab);
     delete c;
@@ -102,7 +108,9 @@ extern "C" int adagc_create(adagc_ctx** out, const adagc_tensor_desc* descs, int
                             const adagc_config* cfg)
 {
     if (!out || !descs || !cfg || n_tensors <= 0) return ADAGC_ERR_INVALID_ARG;
-    if (cfg->optimizer != ADAGC_OPT_ADAMW && cfg->optimizer != ADAGC_OPT_LION) return ADAGC_ERR_INVALID_ARG;
+    if (cfg->optimizer != ADAGC_OPT_ADAMW && cfg->optimizer != ADAGC_OPT_LION && cfg->optimizer != ADAGC_OPT_MUON)
+        return ADAGC_ERR_INVALID_ARG;
+    if (cfg->optimizer == ADAGC_OPT_MUON && (cfg->telemetry || cfg->update_clipping)) return ADAGC_ERR_INVALID_ARG;
     if (cfg->grad_dtype != ADAGC_GRAD_F32 && cfg->grad_dtype != ADAGC_GRAD_BF16) return ADAGC_ERR_INVALID_ARG;
     if (cfg->has_bf16_param_copy != 0 && cfg->has_bf16_param_copy != 1) return ADAGC_ERR_INVALID_ARG;
     if (cfg->grid_blocks < 0 || cfg->nontemporal < 0 || cfg->nontemporal > 2 || cfg->schedule < 0 ||
@@ -345,6 +353,7 @@ extern "C" int adagc_step(adagc_ctx* ctx, void* const* params, const void* const
                           const adagc_hyper* hp, int64_t step, void* stream_v)
 {
     if (!ctx || !params || !grads || !exp_avg || !ema_norms || !hp || step < 1) return ADAGC_ERR_INVALID_ARG;
+    if (ctx->cfg.optimizer == ADAGC_OPT_MUON) return ADAGC_ERR_STATE;      // stepped with adagc_muon_step
     if (!hyper_ok(*hp, ctx->cfg.optimizer)) return ADAGC_ERR_INVALID_ARG;
     const bool update_clip = hp->clip_mode == ADAGC_MODE_AGC || hp->clip_mode == ADAGC_MODE_CLIPPY;
     if (update_clip && !ctx->cfg.update_clipping) return ADAGC_ERR_STATE;
@@ -396,6 +405,7 @@ extern "C" int adagc_step_graph(adagc_ctx* ctx, void* const* params, const void*
                                 const adagc_step_params* step_params, void* stream_v)
 {
     if (!ctx || !params || !grads || !exp_avg || !ema_norms || !step_params) return ADAGC_ERR_INVALID_ARG;
+    if (ctx->cfg.optimizer == ADAGC_OPT_MUON) return ADAGC_ERR_STATE;
     const bool bf16g = ctx->cfg.grad_dtype == ADAGC_GRAD_BF16;
     const bool copy = ctx->cfg.has_bf16_param_copy != 0;
     DeviceGuard guard(ctx->device);
@@ -420,6 +430,133 @@ extern "C" int adagc_step_graph(adagc_ctx* ctx, void* const* params, const void*
     if (launch_update(ctx->tables, UpdateArgs{}, ctx->cfg.optimizer, bf16g, copy, ctx->unroll, ctx->items_per_chunk,
                       ctx->nontemporal, ctx->cfg.telemetry, ctx->grid_update, stream, true) != hipSuccess)
         return ADAGC_ERR_HIP;
+    if (prof) {
+        if (hipEventRecord(ev[3], stream) != hipSuccess) return ADAGC_ERR_HIP;
+        ctx->prof_steps++;
+    }
+    return ADAGC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Muon
+
+namespace {
+constexpr int64_t kMuonTile = 128;     // the matrix-core kernel's block tile: workspace matrices are padded to it
+inline int64_t pad_to_tile(int64_t x) { return (x + kMuonTile - 1) / kMuonTile * kMuonTile; }
+}  // namespace
+
+extern "C" int adagc_muon_attach(adagc_ctx* ctx, const adagc_matrix_shape* shapes)
+{
+    if (!ctx || !shapes) return ADAGC_ERR_INVALID_ARG;
+    if (ctx->cfg.optimizer != ADAGC_OPT_MUON || ctx->muon_ws) return ADAGC_ERR_STATE;
+    int64_t max_mn = 0, max_mm = 0;
+    for (int64_t i = 0; i < ctx->n_tensors; ++i) {
+        const int64_t r = shapes[i].rows, c = shapes[i].cols;
+        if (r <= 0 || c <= 0 || r > INT32_MAX || c > INT32_MAX || r * c != ctx->numel[(size_t)i]) return ADAGC_ERR_INVALID_ARG;
+        const int64_t mp = pad_to_tile(r < c ? r : c), np = pad_to_tile(r < c ? c : r);
+        if (np > INT32_MAX || np / 64 > 65535) return ADAGC_ERR_TOO_LARGE;
+        if (mp * np > max_mn) max_mn = mp * np;
+        if (mp * mp > max_mm) max_mm = mp * mp;
+    }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    try {
+        ctx->shapes.assign(shapes, shapes + ctx->n_tensors);
+    } catch (const std::bad_alloc&) { return ADAGC_ERR_OOM; }
+    const size_t bytes = (size_t)(4 * max_mn + 2 * max_mm) * sizeof(uint16_t);
+    const hipError_t e = hipMalloc(&ctx->muon_ws, bytes);
+    if (e != hipSuccess) {
+        ctx->muon_ws = nullptr;
+        ctx->shapes.clear();
+        return e == hipErrorOutOfMemory ? ADAGC_ERR_OOM : ADAGC_ERR_HIP;
+    }
+    uint16_t* p = static_cast<uint16_t*>(ctx->muon_ws);
+    ctx->ws_x[0] = p;
+    ctx->ws_x[1] = p + max_mn;
+    ctx->ws_y[0] = p + 2 * max_mn;
+    ctx->ws_y[1] = p + 3 * max_mn;
+    ctx->ws_a = p + 4 * max_mn;
+    ctx->ws_b = ctx->ws_a + max_mm;
+    return ADAGC_OK;
+}
+
+extern "C" int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* const* grads, void* const* momentum,
+                               float* ema_norms, const adagc_hyper* hp, const adagc_muon_hyper* mh, int64_t step,
+                               void* stream_v)
+{
+    if (!ctx || !params || !grads || !momentum || !ema_norms || !hp || !mh || step < 1) return ADAGC_ERR_INVALID_ARG;
+    if (ctx->cfg.optimizer != ADAGC_OPT_MUON || !ctx->muon_ws) return ADAGC_ERR_STATE;
+    adagc_hyper h = *hp;
+    h.beta1 = 0.0f;     // Adam's rates and epsilon play no part here; neutral values pass the shared check
+    h.beta2 = 0.0f;
+    h.eps = 0.0f;
+    if (!hyper_ok(h, ADAGC_OPT_LION) || h.clip_mode > ADAGC_MODE_ZCLIP) return ADAGC_ERR_INVALID_ARG;
+    if (!(mh->momentum >= 0.0f && mh->momentum < 1.0f) || (mh->nesterov != 0 && mh->nesterov != 1) || mh->ns_steps < 0 ||
+        mh->ns_steps > 16 || mh->reserved != 0)
+        return ADAGC_ERR_INVALID_ARG;
+    const bool bf16g = ctx->cfg.grad_dtype == ADAGC_GRAD_BF16;
+    const bool copy = ctx->cfg.has_bf16_param_copy != 0;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const int rc = prepare_tables(ctx, params, grads, momentum, nullptr, stream, false);
+    if (rc != ADAGC_OK) return rc;
+
+    RuleArgs r;
+    UpdateArgs u;
+    host_step_scalars(h, step, r, u);
+    const bool global_rule = r.warmup || h.clip_mode != ADAGC_MODE_ADAGC;
+    ctx->device_scalars_used = false;
+    const bool prof = ctx->prof_steps < ctx->prof_capacity;
+    hipEvent_t* ev = prof ? &ctx->prof_events[(size_t)ctx->prof_steps * 4] : nullptr;
+    const DeviceTables& t = ctx->tables;
+
+    // gradient norms and clip coefficients: the kernels of adagc_step
+    if (prof && hipEventRecord(ev[0], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (launch_sumsq_partials(t, bf16g, ctx->nontemporal, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (prof && hipEventRecord(ev[1], stream) != hipSuccess) return ADAGC_ERR_HIP;
+    const hipError_t e = global_rule ? launch_finalize_global(t, ema_norms, r, stream) : launch_finalize_adagc(t, ema_norms, r, stream);
+    if (e != hipSuccess) return ADAGC_ERR_HIP;
+    if (prof && hipEventRecord(ev[2], stream) != hipSuccess) return ADAGC_ERR_HIP;
+
+    // momentum with the clipped gradient, and ||U||_F^2 of every tensor
+    const double mu = (double)mh->momentum;
+    if (launch_muon_momentum(t, mu, mh->nesterov, bf16g, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
+    if (launch_tensor_sumsq(t, stream) != hipSuccess) return ADAGC_ERR_HIP;
+
+    // Newton-Schulz and the update, matrix by matrix
+    const float ns_a = 3.4445f, ns_b = -4.7750f, ns_c = 2.0315f;
+    for (int64_t i = 0; i < ctx->n_tensors; ++i) {
+        const int64_t rows = ctx->shapes[(size_t)i].rows, cols = ctx->shapes[(size_t)i].cols;
+        const bool flip = rows > cols;                      // the iteration runs on the wide orientation
+        const int64_t m = flip ? cols : rows, n = flip ? rows : cols;
+        const int mp = (int)pad_to_tile(m), np = (int)pad_to_tile(n);
+        uint16_t *x = ctx->ws_x[0], *y = ctx->ws_y[0], *x2 = ctx->ws_x[1], *y2 = ctx->ws_y[1];
+        // X is mp x np (leading dimension np), Y = X^T is np x mp (leading dimension mp)
+        hipError_t g = flip ? launch_muon_normalise(grads[i], momentum[i], rows, cols, np, mp, t.coef64 + i, t.sumsq + i, mu,
+                                                    mh->nesterov, bf16g, y, mp, x, np, stream)
+                            : launch_muon_normalise(grads[i], momentum[i], rows, cols, mp, np, t.coef64 + i, t.sumsq + i, mu,
+                                                    mh->nesterov, bf16g, x, np, y, mp, stream);
+        if (g != hipSuccess) return ADAGC_ERR_HIP;
+        for (int k = 0; k < mh->ns_steps; ++k) {
+            // A = X X^T (symmetric: its transposed store is itself)
+            if (launch_gemm_nt_bf16(x, np, x, np, mp, mp, np, 1.0f, 0.0f, nullptr, 0, nullptr, 0, ctx->ws_a, mp, stream) != hipSuccess)
+                return ADAGC_ERR_HIP;
+            // B = b A + c A A
+            if (launch_gemm_nt_bf16(ctx->ws_a, mp, ctx->ws_a, mp, mp, mp, mp, ns_c, ns_b, ctx->ws_a, mp, nullptr, 0, ctx->ws_b, mp,
+                                    stream) != hipSuccess)
+                return ADAGC_ERR_HIP;
+            // X' = a X + B X, written as X' and as Y' = X'^T; (B X)[i][j] = sum_k B[i][k] Y[j][k]
+            if (launch_gemm_nt_bf16(ctx->ws_b, mp, y, mp, mp, np, mp, 1.0f, ns_a, y, mp, x2, np, y2, mp, stream) != hipSuccess)
+                return ADAGC_ERR_HIP;
+            uint16_t* s = x; x = x2; x2 = s;
+            s = y; y = y2; y2 = s;
+        }
+        const double scale = std::sqrt(rows > cols ? (double)rows / (double)cols : 1.0);
+        g = launch_muon_apply(params[i], flip ? y : x, flip ? mp : np, rows, cols, (double)h.lr, (double)h.weight_decay, scale,
+                              copy ? ctx->param_copies[(size_t)i] : nullptr, stream);
+        if (g != hipSuccess) return ADAGC_ERR_HIP;
+    }
     if (prof) {
         if (hipEventRecord(ev[3], stream) != hipSuccess) return ADAGC_ERR_HIP;
         ctx->prof_steps++;

@@ -935,6 +935,12 @@ hipError_t launch_finalize_adagc(const DeviceTables& t, float* ema, const RuleAr
     return hipGetLastError();
 }
 
+hipError_t launch_tensor_sumsq(const DeviceTables& t, hipStream_t stream)
+{
+    tensor_sumsq_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t);
+    return hipGetLastError();
+}
+
 hipError_t launch_finalize_global(const DeviceTables& t, float* ema, const RuleArgs& r, hipStream_t stream)
 {
     tensor_sumsq_kernel<<<dim3(t.n_tensors), dim3(kBlock), 0, stream>>>(t);

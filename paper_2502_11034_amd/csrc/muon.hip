@@ -1,0 +1,179 @@
+// Elementwise kernels of the Muon step with AdaGC's clipped gradient (Muon is the optimizer the paper pairs
+// AdaGC with in "Optimizer Compatibility: Muon and Lion", Sec. 5.4; its rule is the published one, the paper
+// prints none):
+//
+//   muon_momentum_kernel    per chunk:  M <- mu M + h g;  partial sum of squares of U
+//                                       (U = h g + mu M in the Nesterov form, U = M otherwise)
+//   muon_normalise_kernel   per matrix: X0 = bf16(U / (||U||_F + 1e-7)) into the zero-padded workspace, row-major
+//                                       and transposed (the matrix-core products want both, see muon_gemm.hip)
+//   muon_apply_kernel       per matrix: theta <- theta - lr (wd theta + scale O), optional bf16 copy
+//
+// The clip coefficient h of every tensor comes from the same norm and rule kernels as for AdamW and Lion
+// (kernels.hip); the Newton-Schulz products run in muon_gemm.hip.  Arithmetic is double with one rounding per
+// stored value, as in the other update kernels; reductions are in fixed order.
+
+#include "adagc_internal.h"
+
+namespace adagc {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? ((u >> 16) | 0x40u) : rounded;
+}
+
+template <bool BF16>
+__device__ __forceinline__ float grad_at(const void* g, int64_t j)
+{
+    if constexpr (BF16) return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(g)[j] << 16);
+    else return reinterpret_cast<const float*>(g)[j];
+}
+
+// M' and U of one element.  The momentum is stored as fp32; U uses the stored value.
+__device__ __forceinline__ double momentum_elem(double h, double mu, int nesterov, float g, float m_prev, float* m_new)
+{
+    const double gh = h * (double)g;
+    const float m = (float)(mu * (double)m_prev + gh);
+    *m_new = m;
+    return nesterov ? gh + mu * (double)m : (double)m;
+}
+
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);    // a fixed butterfly: same value in every lane
+    return x;
+}
+
+// One workgroup per chunk (positions b, b+grid, ... of the list): momentum update and the chunk's sum of U^2.
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void muon_momentum_kernel(DeviceTables t, double mu, int nesterov)
+{
+    __shared__ double wave_sums[kWavesPerBlock];
+    const int tid = threadIdx.x;
+    for (uint32_t c = blockIdx.x; c < t.n_chunks; c += gridDim.x) {
+        const ChunkRef ck = t.chunks[c];
+        const TensorArgs& ta = t.targs[ck.tensor];
+        const int64_t first = (int64_t)ck.index * kChunkElems;
+        const int64_t rest = ta.numel - first;
+        const int len = rest < (int64_t)kChunkElems ? (int)rest : kChunkElems;
+        const double h = t.coef64[ck.tensor];
+        float* m = reinterpret_cast<float*>(ta.exp_avg) + first;
+        double acc = 0.0;
+        for (int j = tid; j < len; j += kBlock) {
+            float m_new;
+            const double u = momentum_elem(h, mu, nesterov, grad_at<BF16>(ta.grad, first + j), m[j], &m_new);
+            m[j] = m_new;
+            acc = fma(u, u, acc);
+        }
+        const double s = wave_sum(acc);
+        if ((tid & 63) == 0) wave_sums[tid >> 6] = s;
+        __syncthreads();
+        if (tid == 0) {
+            double b = wave_sums[0];
+#pragma unroll
+            for (int w = 1; w < kWavesPerBlock; ++w) b += wave_sums[w];
+            t.partials[c] = b;
+        }
+        __syncthreads();
+    }
+}
+
+// X0 of one matrix.  The source U (rows x cols, recomputed from g and the updated momentum) is walked in 64 x 64
+// tiles of its extent padded to (rows_p, cols_p); every element of the padded extent is written: zeros outside
+// the matrix.  same[r][c] (leading dimension ld_same) receives the tile as is, trans[c][r] (ld_trans) its
+// transpose, through LDS so that both are written along their rows.
+template <bool BF16>
+__global__ __launch_bounds__(256) void muon_normalise_kernel(const void* g, const float* m, int64_t rows, int64_t cols,
+                                                              int64_t rows_p, int64_t cols_p, const double* coef,
+                                                              const double* sumsq, double mu, int nesterov,
+                                                              uint16_t* same, int64_t ld_same, uint16_t* trans, int64_t ld_trans)
+{
+    __shared__ uint16_t tile[64][66];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+    const double h = *coef;
+    const double denom = sqrt(*sumsq) + 1e-7;
+#pragma unroll 4
+    for (int k = 0; k < 16; ++k) {
+        const int64_t r = r0 + ty + 4 * k, c = c0 + tx;
+        uint16_t bits = 0;
+        if (r < rows && c < cols) {
+            const int64_t j = r * cols + c;
+            const double gh = h * (double)grad_at<BF16>(g, j);
+            const double u = nesterov ? gh + mu * (double)m[j] : (double)m[j];     // m already holds this step's momentum
+            bits = (uint16_t)f32_to_bf16_bits((float)(u / denom));
+        }
+        tile[ty + 4 * k][tx] = bits;
+        if (r < rows_p && c < cols_p) same[r * ld_same + c] = bits;
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int k = 0; k < 16; ++k) {
+        const int64_t c = c0 + ty + 4 * k, r = r0 + tx;
+        if (r < rows_p && c < cols_p) trans[c * ld_trans + r] = tile[tx][ty + 4 * k];
+    }
+}
+
+// theta <- theta - lr (wd theta + scale O) on one matrix; O is bf16 with leading dimension ld_o.
+template <bool COPY>
+__global__ __launch_bounds__(256) void muon_apply_kernel(float* theta, const uint16_t* o, int64_t ld_o, int64_t rows, int64_t cols,
+                                                          double lr, double wd, double scale, uint16_t* copy)
+{
+    const int64_t r = blockIdx.x;
+    for (int64_t c = (int64_t)blockIdx.y * 256 + threadIdx.x; c < cols; c += (int64_t)gridDim.y * 256) {
+        const int64_t j = r * cols + c;
+        const double th = (double)theta[j];
+        const double ov = (double)__uint_as_float((uint32_t)o[r * ld_o + c] << 16);
+        const float out = (float)(th - lr * (wd * th + scale * ov));
+        theta[j] = out;
+        if constexpr (COPY) copy[j] = (uint16_t)f32_to_bf16_bits(out);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_muon_momentum(const DeviceTables& t, double mu, int nesterov, int grad_bf16, int grid, hipStream_t stream)
+{
+    if (grad_bf16) muon_momentum_kernel<true><<<dim3(grid), dim3(kBlock), 0, stream>>>(t, mu, nesterov);
+    else muon_momentum_kernel<false><<<dim3(grid), dim3(kBlock), 0, stream>>>(t, mu, nesterov);
+    return hipGetLastError();
+}
+
+hipError_t launch_muon_normalise(const void* g, const void* m, int64_t rows, int64_t cols, int64_t rows_p, int64_t cols_p,
+                                 const double* coef, const double* sumsq, double mu, int nesterov, int grad_bf16,
+                                 void* same, int64_t ld_same, void* trans, int64_t ld_trans, hipStream_t stream)
+{
+    const dim3 grid((uint32_t)(cols_p / 64), (uint32_t)(rows_p / 64));
+    if (grid.y > 65535u) return hipErrorInvalidValue;
+    if (grad_bf16)
+        muon_normalise_kernel<true><<<grid, dim3(256), 0, stream>>>(g, static_cast<const float*>(m), rows, cols, rows_p, cols_p, coef,
+                                                                    sumsq, mu, nesterov, static_cast<uint16_t*>(same), ld_same,
+                                                                    static_cast<uint16_t*>(trans), ld_trans);
+    else
+        muon_normalise_kernel<false><<<grid, dim3(256), 0, stream>>>(g, static_cast<const float*>(m), rows, cols, rows_p, cols_p, coef,
+                                                                     sumsq, mu, nesterov, static_cast<uint16_t*>(same), ld_same,
+                                                                     static_cast<uint16_t*>(trans), ld_trans);
+    return hipGetLastError();
+}
+
+hipError_t launch_muon_apply(void* theta, const void* o, int64_t ld_o, int64_t rows, int64_t cols, double lr, double wd,
+                             double scale, void* copy, hipStream_t stream)
+{
+    int64_t col_blocks = (cols + 255) / 256;
+    if (col_blocks > 64) col_blocks = 64;
+    const dim3 grid((uint32_t)rows, (uint32_t)col_blocks);
+    if (copy)
+        muon_apply_kernel<true><<<grid, dim3(256), 0, stream>>>(static_cast<float*>(theta), static_cast<const uint16_t*>(o), ld_o, rows,
+                                                                cols, lr, wd, scale, static_cast<uint16_t*>(copy));
+    else
+        muon_apply_kernel<false><<<grid, dim3(256), 0, stream>>>(static_cast<float*>(theta), static_cast<const uint16_t*>(o), ld_o, rows,
+                                                                 cols, lr, wd, scale, nullptr);
+    return hipGetLastError();
+}
+
+}  // namespace adagc

@@ -88,3 +88,224 @@ def test_matrix_core_product_rejects_shapes_it_does_not_tile():
         assert e.value.code == B.ADAGC_ERR_INVALID_ARG
     with pytest.raises(B.AdagcError):
         B.adagc_muon_gemm_nt(z, z, 1.0, 0.0, None, None, None)
+
+
+# --------------------------------------------------------------------------- the Muon step
+
+import oracle
+from paper_2502_11034_amd.workloads import to_numpy
+
+SHAPES = [(64, 200), (300, 100), (128, 128), (256, 640), (1, 50), (40, 40), (512, 128)]
+
+
+def _inputs(seed, shapes=SHAPES, spike=None):
+    rng = np.random.default_rng(seed)
+    sig = np.exp(rng.uniform(np.log(1e-3), np.log(1e-1), len(shapes)))
+    g = [(rng.standard_normal(s) * sig[i] * (spike if spike and i % 2 == 0 else 1.0)).astype(np.float32) for i, s in enumerate(shapes)]
+    m = [(rng.standard_normal(s) * sig[i] * 0.5).astype(np.float32) for i, s in enumerate(shapes)]
+    th = [(rng.standard_normal(s) * 0.02).astype(np.float32) for s in shapes]
+    return g, m, th
+
+
+def _dev(arrs):
+    return [torch.from_numpy(a.reshape(-1).copy()).to(DEV) for a in arrs]
+
+
+def _gpu_muon(shapes, g, m, th, gamma, hp, mh, step, copies=False):
+    """One adagc_muon_step from the given host state.  Returns (theta, momentum, gamma, norms, coefs, flags[, copies])."""
+    ctx = B.AdaGC([r * c for r, c in shapes], B.ADAGC_OPT_MUON, B.ADAGC_GRAD_F32, copies)
+    ctx.muon_attach(shapes)
+    dg, dm, dth = _dev(g), _dev(m), _dev(th)
+    dgam = torch.from_numpy(gamma.copy()).to(DEV)
+    dcp = None
+    if copies:
+        dcp = [torch.zeros(r * c, dtype=torch.bfloat16, device=DEV) for r, c in shapes]
+        ctx.set_param_copies(dcp)
+    ctx.muon_step(dth, dg, dm, dgam, hp, mh, step)
+    norms, coefs, flags = ctx.get_norms()
+    out = ([to_numpy(t).reshape(s) for t, s in zip(dth, shapes)], [to_numpy(t).reshape(s) for t, s in zip(dm, shapes)],
+           to_numpy(dgam), norms, coefs, flags)
+    if copies:
+        out += ([to_numpy(t).reshape(s) for t, s in zip(dcp, shapes)],)
+    ctx.close()
+    return out
+
+
+def _direction(shapes, g, m, gamma, hp_kw, mh, step):
+    """O of every tensor as the GPU computes it: theta = 0, lr = 1, no decay gives theta' = fp32(-scale * O); dividing by
+    the scale and rounding to the nearest bf16 value gives O back exactly (fp32's rounding error is far below bf16's
+    spacing)."""
+    hp = B.make_hyper(lr=1.0, weight_decay=0.0, **hp_kw)
+    th0 = [np.zeros(s, np.float32) for s in shapes]
+    res = _gpu_muon(shapes, g, m, th0, gamma, hp, mh, step)
+    return [OM.to_bf16(-(t.astype(np.float64)) / OM.update_scale(*s)) for t, s in zip(res[0], shapes)], res
+
+
+def _bf16_ulps(a, b):
+    """Distance in bf16 steps between two arrays of bf16-representable values."""
+    def key(x):
+        bits = OM.bf16_bits(x).astype(np.int32)
+        return np.where(bits & 0x8000, -(bits & 0x7FFF), bits & 0x7FFF)
+    return np.abs(key(a) - key(b))
+
+
+def test_muon_momentum_normalisation_and_update_without_iteration():
+    """ns_steps = 0: O is X0 = bf16(U / ||U||_F), so this checks the clip coefficient entering the momentum, the
+    Nesterov form, the norm, the transposed orientation of tall matrices, the padding and the parameter update."""
+    g, m, th = _inputs(1)
+    lam, beta = float(np.float32(1.04)), float(np.float32(0.99))
+    gamma = np.array([oracle.l2_norm(x.reshape(-1)) for x in g], np.float32)
+    gamma[::2] *= np.float32(0.5)                              # every other tensor is clipped
+    for nesterov in (True, False):
+        mh = B.make_muon_hyper(momentum=0.95, nesterov=nesterov, ns_steps=0)
+        O, res = _direction(SHAPES, g, m, gamma, dict(t_start=0), mh, 7)
+        _, m_gpu, gam_gpu, norms, coefs, flags = res
+        clipped = 0
+        for i, s in enumerate(SHAPES):
+            n = oracle.l2_norm(g[i].reshape(-1))
+            h, g_new, c = oracle.adagc_rule(n, float(gamma[i]), lam, beta)
+            np.testing.assert_allclose(norms[i], n, rtol=1e-5)
+            np.testing.assert_allclose(coefs[i], h, rtol=1e-5)
+            np.testing.assert_allclose(gam_gpu[i], np.float32(g_new), rtol=1e-5)
+            assert flags[i] == c
+            clipped += c
+            th_ref, m_ref = np.zeros(s, np.float32), m[i].copy()
+            o_ref = OM.muon_update(th_ref, g[i], m_ref, h, lr=1.0, weight_decay=0.0, mu=0.95, nesterov=nesterov, steps=0)
+            assert (np.abs(m_gpu[i].astype(np.float64) - m_ref) <= 1e-5 * np.abs(m_ref)).all(), "momentum of tensor %d" % i
+            assert (m_gpu[i].view(np.uint32) != m_ref.view(np.uint32)).mean() < 1e-3
+            d = _bf16_ulps(O[i], o_ref)
+            assert d.max() <= 1 and (d > 0).mean() < 0.01, "X0 of tensor %d: max %d steps, %.3f %% differ" % (i, d.max(), 100 * (d > 0).mean())
+        assert 3 <= clipped <= 4
+    # the update itself: theta' = theta - lr (wd theta + scale O) with the O the GPU produced, and the bf16 copies
+    mh = B.make_muon_hyper(ns_steps=0)
+    O, _ = _direction(SHAPES, g, m, gamma, dict(t_start=0), mh, 7)
+    hp = B.make_hyper(lr=0.02, weight_decay=0.1, t_start=0)
+    res = _gpu_muon(SHAPES, g, m, th, gamma, hp, mh, 7, copies=True)
+    for i, s in enumerate(SHAPES):
+        t64 = th[i].astype(np.float64)
+        ref = (t64 - float(np.float32(0.02)) * (float(np.float32(0.1)) * t64 + OM.update_scale(*s) * O[i])).astype(np.float32)
+        assert (np.abs(res[0][i].astype(np.float64) - ref) <= 1e-5 * np.abs(ref)).all(), "theta of tensor %d" % i
+        exact = torch.from_numpy(res[0][i]).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(res[6][i], exact)
+
+
+def test_muon_newton_schulz_step_by_step():
+    """Lockstep through the iteration: the GPU's X_k (read back through a step with theta = 0) is handed to the oracle,
+    whose one step is compared with the GPU's X_(k+1).  Within one step the GPU accumulates its products in fp32 where
+    the oracle is exact, so a stored bf16 value can be the oracle's neighbour, and a neighbour in A or B moves X by a
+    few more steps at most: every value within 4 bf16 steps or 2^-9 of the row's largest value, 98 % identical."""
+    g, m, _ = _inputs(2)
+    gamma = np.full(len(SHAPES), 1e9, np.float32)               # nothing clipped here
+    prev = None
+    for k in range(0, 6):
+        O, _ = _direction(SHAPES, g, m, gamma, dict(t_start=0), B.make_muon_hyper(ns_steps=k), 3)
+        X = [o.T if s[0] > s[1] else o for o, s in zip(O, SHAPES)]            # the wide orientation the iteration runs on
+        if prev is not None:
+            worst, frac = 0.0, 0.0
+            for i, s in enumerate(SHAPES):
+                ref = OM.ns_iterate(prev[i], 1)
+                d = _bf16_ulps(X[i], ref)
+                rel = np.abs(X[i] - ref) / np.abs(ref).max(axis=1, keepdims=True)
+                assert ((d <= 4) | (rel <= 2.0 ** -9)).all(), "step %d tensor %d: %d bf16 steps apart" % (k, i, d.max())
+                worst, frac = max(worst, float(rel.max())), max(frac, float((d > 0).mean()))
+                assert (d > 0).mean() < 0.02
+            say("Newton-Schulz step %d: at most %.1e of the row's largest value from the oracle's step, %.3f %% of values not identical"
+                % (k, worst, 100 * frac))
+        prev = X
+
+
+def test_muon_five_steps_end_to_end():
+    """The whole iteration against the oracle's, started from the same U: rounding differences of single values are
+    carried through five steps, so the comparison is in the large: root-mean-square difference below 1 % of the
+    result's own, and the same singular values to 0.01 (the iteration leaves them in about [0.68, 1.2], except those that
+    started too close to zero for five steps)."""
+    g, m, _ = _inputs(3)
+    gamma = np.full(len(SHAPES), 1e9, np.float32)
+    O, _ = _direction(SHAPES, g, m, gamma, dict(t_start=0), B.make_muon_hyper(), 3)
+    for i, s in enumerate(SHAPES):
+        th_ref, m_ref = np.zeros(s, np.float32), m[i].copy()
+        o_ref = OM.muon_update(th_ref, g[i], m_ref, 1.0, lr=1.0, weight_decay=0.0, mu=0.95)
+        rms = np.sqrt(np.mean(o_ref ** 2))
+        diff = np.sqrt(np.mean((O[i] - o_ref) ** 2))
+        sv = np.linalg.svd(O[i], compute_uv=False)
+        say("tensor %d %s: rms difference %.2e of rms %.2e; singular values %.3f .. %.3f" % (i, s, diff, rms, sv.min(), sv.max()))
+        assert diff <= 0.01 * rms
+        sv_ref = np.linalg.svd(o_ref, compute_uv=False)
+        assert np.abs(sv - sv_ref).max() <= 0.01 and sv.max() < 1.25
+
+
+def test_muon_trajectory_with_adagc_clipping():
+    """Three steps with the paper's schedule in small (one warm-up step, then Eq. 3), a spike on the third step:
+    norms, coefficients, flags and gamma against the C oracle's rule, the momentum against the oracle to 1e-5."""
+    shapes = SHAPES
+    hp = B.make_hyper(lr=0.02, weight_decay=0.1, t_start=1)
+    mh = B.make_muon_hyper()
+    ctx = B.AdaGC([r * c for r, c in shapes], B.ADAGC_OPT_MUON, B.ADAGC_GRAD_F32)
+    ctx.muon_attach(shapes)
+    _, m0, th0 = _inputs(5)
+    dm, dth = _dev([np.zeros_like(x) for x in m0]), _dev(th0)
+    dgam = torch.zeros(len(shapes), dtype=torch.float32, device=DEV)
+    h_m = [np.zeros(s, np.float32) for s in shapes]
+    h_th = [t.copy() for t in th0]
+    h_gam = np.zeros(len(shapes), np.float32)
+    lam, beta = float(np.float32(1.04)), float(np.float32(0.99))
+    total_clipped = 0
+    for step in (1, 2, 3):
+        g, _, _ = _inputs(10 + step, spike=30.0 if step == 3 else None)
+        ctx.muon_step(dth, _dev(g), dm, dgam, hp, mh, step)
+        norms, coefs, flags = ctx.get_norms()
+        for i, s in enumerate(shapes):
+            n = oracle.l2_norm(g[i].reshape(-1))
+            if step == 1:
+                h, g_new, c = 1.0, n, False
+            else:
+                h, g_new, c = oracle.adagc_rule(n, float(h_gam[i]), lam, beta)
+            h_gam[i] = np.float32(g_new)
+            np.testing.assert_allclose(norms[i], n, rtol=1e-5)
+            np.testing.assert_allclose(coefs[i], h, rtol=1e-5)
+            assert flags[i] == c
+            total_clipped += int(c)
+            OM.muon_update(h_th[i], g[i], h_m[i], h, lr=0.02, weight_decay=0.1, mu=0.95)
+            gm = to_numpy(dm[i]).reshape(s)
+            assert (np.abs(gm.astype(np.float64) - h_m[i]) <= 1e-5 * np.abs(h_m[i])).all()
+            gt = to_numpy(dth[i]).reshape(s).astype(np.float64)
+            # theta differs only through O: |lr * scale * (O_gpu - O_ref)|, O's values are below 0.5 in magnitude here
+            assert np.sqrt(np.mean((gt - h_th[i]) ** 2)) <= 0.02 * OM.update_scale(*s) * 0.01 * 0.2 * step
+        np.testing.assert_allclose(to_numpy(dgam), h_gam, rtol=1e-5)
+    assert total_clipped >= 4
+    ctx.close()
+
+
+def test_muon_argument_checks():
+    ctx = B.AdaGC([128 * 64, 10], B.ADAGC_OPT_MUON)
+    z = [torch.zeros(128 * 64, device=DEV), torch.zeros(10, device=DEV)]
+    gam = torch.zeros(2, device=DEV)
+    with pytest.raises(B.AdagcError) as e:
+        ctx.muon_step(z, z, z, gam, B.make_hyper(), B.make_muon_hyper(), 1)       # not attached
+    assert e.value.code == B.ADAGC_ERR_STATE
+    with pytest.raises(B.AdagcError) as e:
+        ctx.muon_attach([(128, 64), (3, 4)])                                          # 3*4 != 10
+    assert e.value.code == B.ADAGC_ERR_INVALID_ARG
+    ctx.muon_attach([(128, 64), (2, 5)])
+    with pytest.raises(B.AdagcError) as e:
+        ctx.muon_attach([(128, 64), (2, 5)])                                          # once
+    assert e.value.code == B.ADAGC_ERR_STATE
+    with pytest.raises(B.AdagcError) as e:
+        ctx.step(z, z, z, z, gam, B.make_hyper(), 1)                                  # the wrong entry point
+    assert e.value.code == B.ADAGC_ERR_STATE
+    for bad in (B.make_muon_hyper(momentum=1.0), B.make_muon_hyper(ns_steps=17), B.make_muon_hyper(ns_steps=-1)):
+        with pytest.raises(B.AdagcError) as e:
+            ctx.muon_step(z, z, z, gam, B.make_hyper(), bad, 1)
+        assert e.value.code == B.ADAGC_ERR_INVALID_ARG
+    with pytest.raises(B.AdagcError) as e:
+        ctx.muon_step(z, z, z, gam, B.make_hyper(clip_mode=B.ADAGC_MODE_AGC), B.make_muon_hyper(), 1)
+    assert e.value.code == B.ADAGC_ERR_INVALID_ARG
+    ctx.muon_step(z, z, z, gam, B.make_hyper(), B.make_muon_hyper(), 1)               # zeros in, zeros out
+    torch.cuda.synchronize()
+    assert not z[0].any() and not z[1].any()
+    ctx.close()
+    adam = B.AdaGC([16])
+    with pytest.raises(B.AdagcError) as e:
+        adam.muon_attach([(4, 4)])
+    assert e.value.code == B.ADAGC_ERR_STATE
+    adam.close()

@@ -151,12 +151,85 @@ def placement_probe(args):
         return {"error": "%s: %s" % (type(exc).__name__, exc)}
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core rate
+
+
+def muon_bench(args):
+    """Muon with AdaGC on the 224 hidden matrices of the Llama-3-8B-shaped list (q, k, v, o, gate, up, down of every
+    layer: the tensors Muon is used for; embeddings, head and norm weights stay with AdamW).  Another roofline than the
+    headline workload: the step is bound by the Newton-Schulz products on the matrix cores."""
+    import numpy as np
+    import torch
+    from paper_2502_11034_amd import binding as B
+    from paper_2502_11034_amd import workloads as W
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    specs = [s for s in W.llama3_8b_list() if len(s.shape) == 2 and "." in s.name]        # l<k>.q, l<k>.gate, ...
+    w = W.Workload(specs)
+    shapes = [s.shape for s in specs]
+    grads = {p: w.make_grads(p, dev) for p in (1, 2)}
+    params, mom, _, _ = w.make_state(dev, "lion")
+    gamma = torch.zeros(w.n_tensors, dtype=torch.float32, device=dev)
+    ctx = B.AdaGC(w.numels, B.ADAGC_OPT_MUON, B.ADAGC_GRAD_F32)
+    ctx.muon_attach(shapes)
+    hp = B.make_hyper(lr=0.02, weight_decay=0.1, t_start=1)
+    mh = B.make_muon_hyper()
+    p_ptr, m_ptr = B.ptr_array(params), B.ptr_array(mom)
+    g_ptr = {p: B.ptr_array(g) for p, g in grads.items()}
+    step = 0
+    for _ in range(args.warmup):
+        step += 1
+        ctx.muon_step(p_ptr, g_ptr[1 + step % 2], m_ptr, gamma, hp, mh, step)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    ctx.profile_begin(args.steps)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step += 1
+        ev[k][0].record()
+        ctx.muon_step(p_ptr, g_ptr[1 + step % 2], m_ptr, gamma, hp, mh, step)
+        ev[k][1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per_kernel = ctx.profile_end()                 # [steps, 3] ms: gradient norms, rule, momentum + Newton-Schulz + update
+    step_ms = np.array([a.elapsed_time(b) for a, b in ev], dtype=np.float64)
+    # Multiply-adds of the iteration.  "full": the three products of a step written out, 4 m^2 n + 2 m^3.  "performed":
+    # A = X X^T and A A are symmetric and only their tiles on and below the diagonal are computed (128 x 128 tiles).
+    flops, performed = 0.0, 0.0
+    for r, c in shapes:
+        m, n = min(r, c), max(r, c)
+        flops += mh.ns_steps * (4.0 * m * m * n + 2.0 * m * m * m)
+        half = (m * m + 128.0 * m) / 2.0                       # elements of the lower triangle of tiles
+        performed += mh.ns_steps * (2.0 * half * n + 2.0 * half * m + 2.0 * m * m * n)
+    ms = float(np.median(step_ms))
+    ns_ms = float(per_kernel[:, 2].mean())
+    out = {
+        "metric": "Muon+AdaGC step: Newton-Schulz TFLOP/s (multiplications performed) over the whole step, hidden matrices of Llama-3-8B shapes",
+        "value": round(performed / (ms * 1e-3) / 1e12, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 3), "ms_min": round(float(step_ms.min()), 3), "ms_max": round(float(step_ms.max()), 3),
+        "ms_mean_wall_clock": round((t1 - t0) / args.steps * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "muon: %d matrices, %d params, fp32 grads, fp32 theta and momentum, bf16 Newton-Schulz (%d steps)"
+                               % (w.n_tensors, w.total_params, mh.ns_steps),
+                   "flops_per_step_performed": performed, "flops_per_step_full_products": flops,
+                   "tflops_full_product_equivalent": round(flops / (ms * 1e-3) / 1e12, 1)},
+        "kernels_ms": {"sumsq_partials": round(float(per_kernel[:, 0].mean()), 4), "finalize": round(float(per_kernel[:, 1].mean()), 4),
+                       "momentum_newton_schulz_update": round(ns_ms, 3)},
+        "roofline": {"kernel": "gemm_nt_bf16_kernel (with the elementwise kernels between its launches)", "bound": "mfma",
+                     "achieved": round(performed / (ns_ms * 1e-3) / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(performed / (ns_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None},
+    }
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4", "config5"])
+    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4", "config5", "muon"])
     ap.add_argument("--grid-blocks", type=int, default=0, help="launch tuning: workgroups of the persistent grids")
     ap.add_argument("--unroll", type=int, default=0, help="launch tuning: vectors in flight per lane per stream")
     ap.add_argument("--nontemporal", type=int, default=0, help="launch tuning: 1 on, 2 off")
@@ -176,6 +249,8 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
 
+    if args.workload == "muon":
+        return muon_bench(args)
     worst = None
     if not args.no_placement_probe and args.alloc_order == "good":
         worst = placement_probe(args)          # before anything here touches the GPU

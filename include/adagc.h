@@ -388,11 +388,13 @@ int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* const* grad
  *   P   M x K, leading dimension ldp        Q   N x K, ldq          (both operands K-contiguous)
  *   Dt  N x M, lddt: the TRANSPOSE of D, or NULL (then beta is ignored)
  *   C   M x N, ldc, or NULL                 Ct  N x M, ldct: the transpose of the result, or NULL (one of the two)
- * M, N must be multiples of 128, K of 64, every leading dimension of 8.  Errors: INVALID_ARG, TOO_LARGE, HIP.
+ *   symmetric = 1: P = Q, M = N and D symmetric, so the result is symmetric; it is written to Ct (C NULL or the same
+ *                  array) and only the tiles on and below the diagonal are computed, each stored twice
+ * M, N and K must be multiples of 128, every leading dimension of 8.  Errors: INVALID_ARG, TOO_LARGE, HIP.
  */
 int adagc_muon_gemm_nt(const void* P, int64_t ldp, const void* Q, int64_t ldq, int64_t M, int64_t N, int64_t K,
                        float alpha, float beta, const void* Dt, int64_t lddt, void* C, int64_t ldc, void* Ct,
-                       int64_t ldct, void* stream);
+                       int64_t ldct, int32_t symmetric, void* stream);
 
 /* Static description of an error code. */
 const char* adagc_strerror(int code);

@@ -125,7 +125,7 @@ def lib():
     L.adagc_muon_step.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(adagc_hyper), ctypes.POINTER(adagc_muon_hyper), i64, vp]
     L.adagc_muon_gemm_nt.restype = ctypes.c_int
     L.adagc_muon_gemm_nt.argtypes = [vp, i64, vp, i64, i64, i64, i64, ctypes.c_float, ctypes.c_float, vp, i64, vp, i64,
-                                     vp, i64, vp]
+                                     vp, i64, i32, vp]
     L.adagc_strerror.restype = ctypes.c_char_p
     L.adagc_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -197,7 +197,7 @@ def adagc_build_visiting_order(n_chunks, parts=2, run=8):
     return order
 
 
-def adagc_muon_gemm_nt(P, Q, alpha=1.0, beta=0.0, Dt=None, C=None, Ct=None, stream=None):
+def adagc_muon_gemm_nt(P, Q, alpha=1.0, beta=0.0, Dt=None, C=None, Ct=None, stream=None, symmetric=False):
     """adagc_muon_gemm_nt on 2-D bf16 device tensors (row-major, possibly with a leading dimension larger than
     the row length): C = bf16(alpha P Q^T + beta D), D passed as its transpose Dt."""
     M, K = P.shape
@@ -205,7 +205,8 @@ def adagc_muon_gemm_nt(P, Q, alpha=1.0, beta=0.0, Dt=None, C=None, Ct=None, stre
     ld = lambda t: t.stride(0) if t is not None else 0
     dp = lambda t: t.data_ptr() if t is not None else None
     _check(lib().adagc_muon_gemm_nt(P.data_ptr(), ld(P), Q.data_ptr(), ld(Q), M, N, K, float(alpha), float(beta), dp(Dt),
-                                    ld(Dt), dp(C), ld(C), dp(Ct), ld(Ct), ctypes.c_void_p(stream) if stream else None),
+                                    ld(Dt), dp(C), ld(C), dp(Ct), ld(Ct), int(bool(symmetric)),
+                                    ctypes.c_void_p(stream) if stream else None),
            "adagc_muon_gemm_nt")
 
 

@@ -163,7 +163,7 @@ hipError_t launch_update_clip_rule(const DeviceTables& t, const UpdateArgs& u, c
 // through its transpose Dt, result written row-major (C), transposed (Ct) or both.
 hipError_t launch_gemm_nt_bf16(const void* P, int ldp, const void* Q, int ldq, int M, int N, int K, float alpha,
                                float beta, const void* Dt, int lddt, void* C, int ldc, void* Ct, int ldct,
-                               hipStream_t stream);
+                               hipStream_t stream, bool symmetric = false);
 // Muon (muon.hip): per-tensor sums of the per-chunk partials into t.sumsq; momentum update with the clipped
 // gradient and the partial sums of squares of U; X0 of one matrix into the padded workspace; the parameter update.
 hipError_t launch_tensor_sumsq(const DeviceTables& t, hipStream_t stream);

@@ -540,11 +540,11 @@ extern "C" int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* 
         if (g != hipSuccess) return ADAGC_ERR_HIP;
         for (int k = 0; k < mh->ns_steps; ++k) {
             // A = X X^T (symmetric: its transposed store is itself)
-            if (launch_gemm_nt_bf16(x, np, x, np, mp, mp, np, 1.0f, 0.0f, nullptr, 0, nullptr, 0, ctx->ws_a, mp, stream) != hipSuccess)
+            if (launch_gemm_nt_bf16(x, np, x, np, mp, mp, np, 1.0f, 0.0f, nullptr, 0, nullptr, 0, ctx->ws_a, mp, stream, true) != hipSuccess)
                 return ADAGC_ERR_HIP;
             // B = b A + c A A
             if (launch_gemm_nt_bf16(ctx->ws_a, mp, ctx->ws_a, mp, mp, mp, mp, ns_c, ns_b, ctx->ws_a, mp, nullptr, 0, ctx->ws_b, mp,
-                                    stream) != hipSuccess)
+                                    stream, true) != hipSuccess)
                 return ADAGC_ERR_HIP;
             // X' = a X + B X, written as X' and as Y' = X'^T; (B X)[i][j] = sum_k B[i][k] Y[j][k]
             if (launch_gemm_nt_bf16(ctx->ws_b, mp, y, mp, mp, np, mp, 1.0f, ns_a, y, mp, x2, np, y2, mp, stream) != hipSuccess)

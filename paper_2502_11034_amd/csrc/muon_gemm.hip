@@ -13,13 +13,16 @@
 // Dt (N x M): in the accumulator layout a lane holds 4 consecutive rows of one column, which are 4
 // consecutive elements of a transposed array, so those accesses are 8-byte vectors.
 //
-// All dimensions are multiples of the 128 x 128 x 64 block tile: the caller (muon.hip) keeps every matrix
+// A = X X^T and A A are symmetric: for those only the tiles on and below the diagonal are computed and each is
+// written twice, to its place and to its mirror image, which saves a third of a step's multiplications.
+//
+// M and N are multiples of the 128 x 128 block tile and K of 128 (two 64-deep tiles): the caller (muon.hip) keeps every matrix
 // in zero-padded workspace buffers, and zero rows and columns stay zero through the iteration.
 //
-// Tiling: 256 lanes = 4 waves in a 2 x 2 grid, each wave a 64 x 64 tile = 2 x 2 accumulators of
+// Tiling (128 x 128 block tile; 256 x 256 for large products): 256 lanes = 4 waves in a 2 x 2 grid, each wave a
+// 64 x 64 (128 x 128) tile = 2 x 2 (4 x 4) accumulators of
 // v_mfma_f32_32x32x16_bf16 (fp32 accumulation).  Operand tiles go global -> registers -> LDS (rows padded
-// by 16 bytes against bank conflicts), double-buffered: the loads of tile k+1 are in flight while tile k
-// is multiplied.  Workgroups are dealt to the 8 XCDs in turn, so block ids are remapped to give each XCD
+// by 16 bytes against bank conflicts), double-buffered, with the global loads issued two tiles ahead.  Workgroups are dealt to the 8 XCDs in turn, so block ids are remapped to give each XCD
 // (one L2 each) a contiguous band of output tiles.
 
 #include "adagc_internal.h"
@@ -32,12 +35,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
 
-constexpr int kBM = 128, kBN = 128, kBK = 64;
+constexpr int kBK = 64;
 constexpr int kLdsRow = kBK + 8;                       // bf16 elements per LDS row (16 bytes of padding)
 constexpr int kGemmThreads = 256;
 constexpr int kVecPerRow = kBK / 8;                    // 16-byte vectors per tile row
-constexpr int kLoadsP = kBM * kVecPerRow / kGemmThreads;   // 16-byte loads per lane per P tile (4)
-constexpr int kLoadsQ = kBN * kVecPerRow / kGemmThreads;
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
 {
@@ -49,11 +50,19 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+// BT x BT block tile (128 or 256).  SYM: the result is symmetric (P = Q, D symmetric) and C = Ct is one array: only
+// the tiles on and below the diagonal are computed, each written to its own place and to its mirror image.
+template <int BT, bool SYM>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
     const uint16_t* __restrict__ P, int ldp, const uint16_t* __restrict__ Q, int ldq, int M, int N, int K,
     float alpha, float beta, const uint16_t* __restrict__ Dt, int lddt, uint16_t* __restrict__ C, int ldc,
     uint16_t* __restrict__ Ct, int ldct)
 {
+    constexpr int kBM = BT, kBN = BT;
+    constexpr int kTM = kBM / 2, kTN = kBN / 2;            // wave tile (waves in a 2 x 2 grid)
+    constexpr int kMI = kTM / 32, kNI = kTN / 32;          // 32 x 32 accumulators per wave
+    constexpr int kLoadsP = kBM * kVecPerRow / kGemmThreads;   // 16-byte loads per lane per P tile
+    constexpr int kLoadsQ = kBN * kVecPerRow / kGemmThreads;
     __shared__ __attribute__((aligned(16))) uint16_t lds_p[2][kBM * kLdsRow];
     __shared__ __attribute__((aligned(16))) uint16_t lds_q[2][kBN * kLdsRow];
 
@@ -64,78 +73,99 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
 
     // XCD-aware tile order: block b runs on XCD b mod 8; give XCD x the x-th contiguous eighth of the tiles.
     const int tiles_n = N / kBN;
-    const int n_tiles = (M / kBM) * tiles_n;
+    const int n_tiles = SYM ? tiles_n * (tiles_n + 1) / 2 : (M / kBM) * tiles_n;
     int b = blockIdx.x;
     if (n_tiles % 8 == 0) b = (b % 8) * (n_tiles / 8) + b / 8;
-    const int tile_m = b / tiles_n, tile_n = b % tiles_n;
+    int tile_m, tile_n;
+    if constexpr (SYM) {
+        // b-th tile of the lower triangle, row by row: row r starts at r (r + 1) / 2
+        int r = (int)((sqrtf(8.0f * (float)b + 1.0f) - 1.0f) * 0.5f);
+        while (r * (r + 1) / 2 > b) --r;
+        while ((r + 1) * (r + 2) / 2 <= b) ++r;
+        tile_m = r;
+        tile_n = b - r * (r + 1) / 2;
+    } else {
+        tile_m = b / tiles_n;
+        tile_n = b % tiles_n;
+    }
     const uint16_t* Pt = P + (size_t)tile_m * kBM * ldp;
     const uint16_t* Qt = Q + (size_t)tile_n * kBN * ldq;
 
-    f32x16 acc[2][2];
+    f32x16 acc[kMI][kNI];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < kMI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < kNI; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    u32x4 stage_p[kLoadsP], stage_q[kLoadsQ];
-    auto load_tile = [&](int kt) {
+    // Two register sets for operand tiles in flight: the loads of tile k+2 are issued before tile k is multiplied
+    // and are written to LDS one tile later, so a load has two tiles' worth of matrix-core work to arrive.
+    u32x4 stage_p[2][kLoadsP], stage_q[2][kLoadsQ];
+    auto load_tile = [&](int kt, u32x4 (&sp)[kLoadsP], u32x4 (&sq)[kLoadsQ]) {
 #pragma unroll
         for (int u = 0; u < kLoadsP; ++u) {
             const int v = u * kGemmThreads + tid;
             const int row = v / kVecPerRow, kv = v % kVecPerRow;
-            stage_p[u] = *reinterpret_cast<const u32x4*>(Pt + (size_t)row * ldp + kt * kBK + kv * 8);
+            sp[u] = *reinterpret_cast<const u32x4*>(Pt + (size_t)row * ldp + kt * kBK + kv * 8);
         }
 #pragma unroll
         for (int u = 0; u < kLoadsQ; ++u) {
             const int v = u * kGemmThreads + tid;
             const int row = v / kVecPerRow, kv = v % kVecPerRow;
-            stage_q[u] = *reinterpret_cast<const u32x4*>(Qt + (size_t)row * ldq + kt * kBK + kv * 8);
+            sq[u] = *reinterpret_cast<const u32x4*>(Qt + (size_t)row * ldq + kt * kBK + kv * 8);
         }
     };
-    auto store_tile = [&](int buf) {
+    auto store_tile = [&](int buf, const u32x4 (&sp)[kLoadsP], const u32x4 (&sq)[kLoadsQ]) {
 #pragma unroll
         for (int u = 0; u < kLoadsP; ++u) {
             const int v = u * kGemmThreads + tid;
             const int row = v / kVecPerRow, kv = v % kVecPerRow;
-            *reinterpret_cast<u32x4*>(&lds_p[buf][row * kLdsRow + kv * 8]) = stage_p[u];
+            *reinterpret_cast<u32x4*>(&lds_p[buf][row * kLdsRow + kv * 8]) = sp[u];
         }
 #pragma unroll
         for (int u = 0; u < kLoadsQ; ++u) {
             const int v = u * kGemmThreads + tid;
             const int row = v / kVecPerRow, kv = v % kVecPerRow;
-            *reinterpret_cast<u32x4*>(&lds_q[buf][row * kLdsRow + kv * 8]) = stage_q[u];
+            *reinterpret_cast<u32x4*>(&lds_q[buf][row * kLdsRow + kv * 8]) = sq[u];
         }
     };
-
-    const int k_tiles = K / kBK;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-
     // fragment addressing: lane l holds row (l % 32), k offset (l / 32) * 8 of a 32 x 16 operand block
     const int frag_row = lane & 31;
     const int frag_k = (lane >> 5) * 8;
-    for (int kt = 0; kt < k_tiles; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < k_tiles) load_tile(kt + 1);
+    auto multiply_tile = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < kBK / 16; ++kk) {
-            bf16x8 fa[2], fb[2];
+            bf16x8 fa[kMI], fb[kNI];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8*>(&lds_p[buf][(wm * 64 + i * 32 + frag_row) * kLdsRow + kk * 16 + frag_k]);
+            for (int i = 0; i < kMI; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8*>(&lds_p[buf][(wm * kTM + i * 32 + frag_row) * kLdsRow + kk * 16 + frag_k]);
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8*>(&lds_q[buf][(wn * 64 + j * 32 + frag_row) * kLdsRow + kk * 16 + frag_k]);
+            for (int j = 0; j < kNI; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8*>(&lds_q[buf][(wn * kTN + j * 32 + frag_row) * kLdsRow + kk * 16 + frag_k]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < kMI; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < kNI; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < k_tiles) store_tile(buf ^ 1);
+    };
+
+    const int k_tiles = K / kBK;          // even: K is a multiple of 128
+    load_tile(0, stage_p[0], stage_q[0]);
+    load_tile(1, stage_p[1], stage_q[1]);
+    store_tile(0, stage_p[0], stage_q[0]);
+    __syncthreads();
+    for (int kt = 0; kt < k_tiles; kt += 2) {
+        // tile kt is in LDS buffer 0, tile kt+1 in register set 1
+        if (kt + 2 < k_tiles) load_tile(kt + 2, stage_p[0], stage_q[0]);
+        multiply_tile(0);
+        store_tile(1, stage_p[1], stage_q[1]);
+        __syncthreads();
+        // tile kt+1 is in LDS buffer 1, tile kt+2 in register set 0
+        if (kt + 3 < k_tiles) load_tile(kt + 3, stage_p[1], stage_q[1]);
+        multiply_tile(1);
+        if (kt + 2 < k_tiles) store_tile(0, stage_p[0], stage_q[0]);
         __syncthreads();
     }
 
@@ -144,13 +174,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
     const int col_in = lane & 31;
     const int row_in = (lane >> 5) * 4;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < kMI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int col = tile_n * kBN + wn * 64 + j * 32 + col_in;
+        for (int j = 0; j < kNI; ++j) {
+            const int col = tile_n * kBN + wn * kTN + j * 32 + col_in;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int row0 = tile_m * kBM + wm * 64 + i * 32 + q * 8 + row_in;
+                const int row0 = tile_m * kBM + wm * kTM + i * 32 + q * 8 + row_in;
                 float v[4] = {alpha * acc[i][j][q * 4 + 0], alpha * acc[i][j][q * 4 + 1], alpha * acc[i][j][q * 4 + 2],
                               alpha * acc[i][j][q * 4 + 3]};
                 if (Dt) {
@@ -168,7 +198,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
                     o.y = h2 | (h3 << 16);
                     *reinterpret_cast<u32x2v*>(Ct + (size_t)col * ldct + row0) = o;
                 }
-                if (C) {
+                if (SYM ? (tile_m != tile_n) : (C != nullptr)) {      // SYM: the mirror image, C is the same array as Ct
                     C[(size_t)(row0 + 0) * ldc + col] = (uint16_t)h0;
                     C[(size_t)(row0 + 1) * ldc + col] = (uint16_t)h1;
                     C[(size_t)(row0 + 2) * ldc + col] = (uint16_t)h2;
@@ -180,18 +210,37 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
 
 }  // namespace
 
-// Shapes must be multiples of the block tile and every leading dimension a multiple of 8 elements (16-byte rows).
+// M, N, K must be multiples of 128 and every leading dimension a multiple of 8 elements (16-byte rows).
+// symmetric: P = Q (and D symmetric), so the result is symmetric: C and Ct are then the same array (pass it as Ct)
+// and only the lower triangle of tiles is computed.  Tiles of 256 x 256 where the shape allows and fills the GPU.
 hipError_t launch_gemm_nt_bf16(const void* P, int ldp, const void* Q, int ldq, int M, int N, int K, float alpha,
                                float beta, const void* Dt, int lddt, void* C, int ldc, void* Ct, int ldct,
-                               hipStream_t stream)
+                               hipStream_t stream, bool symmetric)
 {
-    if (M <= 0 || N <= 0 || K <= 0 || M % kBM || N % kBN || K % kBK || ldp % 8 || ldq % 8 || (Dt && lddt % 8) ||
+    if (M <= 0 || N <= 0 || K <= 0 || M % 128 || N % 128 || K % 128 || ldp % 8 || ldq % 8 || (Dt && lddt % 8) ||
         (Ct && ldct % 8) || (!C && !Ct))
         return hipErrorInvalidValue;
-    const int blocks = (M / kBM) * (N / kBN);
-    gemm_nt_bf16_kernel<<<dim3(blocks), dim3(kGemmThreads), 0, stream>>>(
-        static_cast<const uint16_t*>(P), ldp, static_cast<const uint16_t*>(Q), ldq, M, N, K, alpha, beta,
-        static_cast<const uint16_t*>(Dt), lddt, static_cast<uint16_t*>(C), ldc, static_cast<uint16_t*>(Ct), ldct);
+    if (symmetric && (M != N || P != Q || !Ct || (C && C != Ct))) return hipErrorInvalidValue;
+    const uint16_t *p = static_cast<const uint16_t*>(P), *q = static_cast<const uint16_t*>(Q), *dt = static_cast<const uint16_t*>(Dt);
+    uint16_t *c = static_cast<uint16_t*>(C), *ct = static_cast<uint16_t*>(Ct);
+    // 256 x 256 tiles multiply faster, but only when there are enough of them for the 256 compute units
+    const int64_t big_tiles = symmetric ? (int64_t)(M / 256) * (M / 256 + 1) / 2 : (int64_t)(M / 256) * (N / 256);
+    const bool big = (M % 256 == 0) && (N % 256 == 0) && big_tiles >= 256;
+    if (symmetric) {
+        c = ct;
+        ldc = ldct;
+        if (big) {
+            const int t = M / 256;
+            gemm_nt_bf16_kernel<256, true><<<dim3(t * (t + 1) / 2), dim3(kGemmThreads), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+        } else {
+            const int t = M / 128;
+            gemm_nt_bf16_kernel<128, true><<<dim3(t * (t + 1) / 2), dim3(kGemmThreads), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+        }
+    } else if (big) {
+        gemm_nt_bf16_kernel<256, false><<<dim3((M / 256) * (N / 256)), dim3(kGemmThreads), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+    } else {
+        gemm_nt_bf16_kernel<128, false><<<dim3((M / 128) * (N / 128)), dim3(kGemmThreads), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+    }
     return hipGetLastError();
 }
 
@@ -200,7 +249,7 @@ hipError_t launch_gemm_nt_bf16(const void* P, int ldp, const void* Q, int ldq, i
 // Test hook of the matrix-core GEMM through the C ABI (see include/adagc.h).
 extern "C" int adagc_muon_gemm_nt(const void* P, int64_t ldp, const void* Q, int64_t ldq, int64_t M, int64_t N, int64_t K,
                                   float alpha, float beta, const void* Dt, int64_t lddt, void* C, int64_t ldc, void* Ct,
-                                  int64_t ldct, void* stream)
+                                  int64_t ldct, int32_t symmetric, void* stream)
 {
     if (!P || !Q) return ADAGC_ERR_INVALID_ARG;
     if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldp > INT32_MAX || ldq > INT32_MAX || lddt > INT32_MAX ||
@@ -208,7 +257,7 @@ extern "C" int adagc_muon_gemm_nt(const void* P, int64_t ldp, const void* Q, int
         return ADAGC_ERR_TOO_LARGE;
     if (ldp < K || ldq < K || (Dt && lddt < M) || (C && ldc < N) || (Ct && ldct < M)) return ADAGC_ERR_INVALID_ARG;
     const hipError_t e = adagc::launch_gemm_nt_bf16(P, (int)ldp, Q, (int)ldq, (int)M, (int)N, (int)K, alpha, beta, Dt, (int)lddt,
-                                                    C, (int)ldc, Ct, (int)ldct, static_cast<hipStream_t>(stream));
+                                                    C, (int)ldc, Ct, (int)ldct, static_cast<hipStream_t>(stream), symmetric != 0);
     if (e == hipErrorInvalidValue) return ADAGC_ERR_INVALID_ARG;
     return e == hipSuccess ? ADAGC_OK : ADAGC_ERR_HIP;
 }

@@ -28,7 +28,8 @@ def host64(t):
     return t.to(torch.float32).cpu().numpy().astype(np.float64)
 
 
-@pytest.mark.parametrize("M,N,K,ld_extra", [(128, 128, 64, 0), (256, 384, 192, 8), (128, 512, 1024, 64), (1024, 1024, 4096, 0)])
+@pytest.mark.parametrize("M,N,K,ld_extra", [(128, 128, 128, 0), (256, 384, 384, 8), (128, 512, 1024, 64), (1024, 1024, 4096, 0),
+                                              (4096, 4096, 256, 0)])       # the last one runs on 256 x 256 tiles
 def test_matrix_core_product_matches_the_oracle(M, N, K, ld_extra):
     rng = np.random.default_rng(M + N + K)
     P = OM.to_bf16(rng.standard_normal((M, K)) * 0.05)
@@ -65,6 +66,32 @@ def test_matrix_core_product_matches_the_oracle(M, N, K, ld_extra):
     assert (np.abs(g2 - ref2) <= 2.0 ** -7 * np.abs(ref2) + 1e-5 * (np.abs(P) @ np.abs(Q).T)).all()
 
 
+@pytest.mark.parametrize("M,K", [(128, 128), (384, 256), (1024, 512), (6144, 128)])
+def test_symmetric_matrix_core_product(M, K):
+    """P = Q: only the tiles on and below the diagonal are computed and each is stored twice.  The result must be
+    exactly symmetric and equal to the full product's (the same sums in the same order)."""
+    rng = np.random.default_rng(M + K)
+    P = OM.to_bf16(rng.standard_normal((M, K)) * 0.05)
+    D = rng.standard_normal((M, M)) * 0.3
+    D = OM.to_bf16(D + D.T)
+    dP, dD = bf16_dev(P), bf16_dev(D)
+    S = torch.full((M, M), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.adagc_muon_gemm_nt(dP, dP, 2.0315, -4.775, dD, None, S, symmetric=True)
+    F = torch.zeros((M, M), dtype=torch.bfloat16, device=DEV)
+    B.adagc_muon_gemm_nt(dP, dP, 2.0315, -4.775, dD, F, None)
+    torch.cuda.synchronize()
+    got = host64(S)
+    assert not np.isnan(got).any(), "a tile was not written"
+    assert np.array_equal(got, got.T)
+    assert np.array_equal(got, host64(F))
+    f = lambda v: float(np.float32(v))
+    ref = OM.to_bf16(f(2.0315) * (P @ P.T) + f(-4.775) * D)
+    slack = 1e-5 * (np.abs(f(2.0315)) * (np.abs(P) @ np.abs(P).T) + np.abs(f(-4.775) * D))
+    assert (np.abs(got - ref) <= 2.0 ** -7 * np.abs(ref) + slack).all()
+    with pytest.raises(B.AdagcError):
+        B.adagc_muon_gemm_nt(dP, bf16_dev(P), 1.0, 0.0, None, None, S, symmetric=True)      # P and Q must be the same array
+
+
 def test_matrix_core_product_places_every_element():
     """Index check with exactly representable data: P row i holds i+1 at column i (others 0), Q row j holds small
     integers, so C[i][j] = (i+1) * Q[j][i] exactly, and a misplaced lane or register shows as a wrong integer."""
@@ -80,9 +107,9 @@ def test_matrix_core_product_places_every_element():
 
 
 def test_matrix_core_product_rejects_shapes_it_does_not_tile():
-    z = torch.zeros((128, 64), dtype=torch.bfloat16, device=DEV)
+    z = torch.zeros((128, 128), dtype=torch.bfloat16, device=DEV)
     out = torch.zeros((128, 128), dtype=torch.bfloat16, device=DEV)
-    for P, Q in [(z[:100], z), (z[:, :32], z[:, :32])]:
+    for P, Q in [(z[:100], z), (z[:, :64], z[:, :64])]:
         with pytest.raises(B.AdagcError) as e:
             B.adagc_muon_gemm_nt(P, Q, 1.0, 0.0, None, out[:P.shape[0]], None)
         assert e.value.code == B.ADAGC_ERR_INVALID_ARG

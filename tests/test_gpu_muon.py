@@ -336,3 +336,65 @@ def test_muon_argument_checks():
         adam.muon_attach([(4, 4)])
     assert e.value.code == B.ADAGC_ERR_STATE
     adam.close()
+
+
+# --------------------------------------------------------------------------- Llama-3-8B shapes
+
+def _sampled_rows_check(name, P, Q, alpha, beta, D, got, rows):
+    """Rows of bf16(alpha P Q^T + beta D) computed one by one by the oracle's arithmetic."""
+    f = lambda v: float(np.float32(v))
+    for i in rows:
+        exact = f(alpha) * (P[i] @ Q.T)
+        slack = 1e-5 * np.abs(f(alpha)) * (np.abs(P[i]) @ np.abs(Q).T)
+        if D is not None:
+            exact = exact + f(beta) * D[i]
+            slack = slack + 1e-5 * np.abs(f(beta) * D[i])
+        ref = OM.to_bf16(exact)
+        assert (np.abs(got[i] - ref) <= 2.0 ** -7 * np.abs(ref) + slack).all(), "%s row %d" % (name, i)
+
+
+def test_newton_schulz_products_at_llama3_8b_ffn_shape():
+    """One step's three products at the size of a 4096 x 14336 weight, in the tile configuration the step uses there
+    (symmetric products on 128 x 128 tiles, the last product on 256 x 256): each checked on sampled rows that the
+    oracle computes one by one from the GPU's own operands, and the symmetric ones for exact symmetry."""
+    m, n = 4096, 14336
+    gen = torch.Generator(device=DEV).manual_seed(9)
+    x = (torch.randn(m, n, device=DEV, generator=gen) * (1.0 / np.sqrt(m * n)) * 3.0).to(torch.bfloat16)      # like a normalised U
+    y = x.t().contiguous()
+    a_, b_, c_ = 3.4445, -4.7750, 2.0315
+    A = torch.empty((m, m), dtype=torch.bfloat16, device=DEV)
+    Bm = torch.empty((m, m), dtype=torch.bfloat16, device=DEV)
+    X2 = torch.empty((m, n), dtype=torch.bfloat16, device=DEV)
+    Y2 = torch.empty((n, m), dtype=torch.bfloat16, device=DEV)
+    B.adagc_muon_gemm_nt(x, x, 1.0, 0.0, None, None, A, symmetric=True)
+    B.adagc_muon_gemm_nt(A, A, c_, b_, A, None, Bm, symmetric=True)
+    B.adagc_muon_gemm_nt(Bm, y, 1.0, a_, y, X2, Y2)
+    torch.cuda.synchronize()
+    hx, hA, hB, hX2 = host64(x), host64(A), host64(Bm), host64(X2)
+    assert np.array_equal(hA, hA.T) and np.array_equal(hB, hB.T)
+    assert torch.equal(Y2, X2.t().contiguous())
+    rows = [0, 1, 127, 128, 2047, 2048, 3000, 4095]
+    _sampled_rows_check("A = X X^T", hx, hx, 1.0, 0.0, None, hA, rows)
+    _sampled_rows_check("B = b A + c A A", hA, hA, c_, b_, hA, hB, rows)
+    _sampled_rows_check("X' = a X + B X", hB, hx.T.copy(), 1.0, a_, hx, hX2, rows)
+    say("Newton-Schulz products at 4096 x 14336: %d sampled rows of each product agree with the oracle" % len(rows))
+
+
+def test_muon_step_at_llama3_8b_attention_shapes():
+    """The whole step on a k-projection (1024 x 4096) and a q-projection (4096 x 4096) at real size, five steps of the
+    iteration, against the oracle's (numpy, float64 products): root-mean-square difference and singular values."""
+    shapes = [(1024, 4096), (4096, 4096)]
+    g, m, _ = _inputs(21, shapes)
+    gamma = np.full(len(shapes), 1e9, np.float32)
+    O, _ = _direction(shapes, g, m, gamma, dict(t_start=0), B.make_muon_hyper(), 3)
+    for i, s in enumerate(shapes):
+        th_ref, m_ref = np.zeros(s, np.float32), m[i].copy()
+        o_ref = OM.muon_update(th_ref, g[i], m_ref, 1.0, lr=1.0, weight_decay=0.0, mu=0.95)
+        rms = np.sqrt(np.mean(o_ref ** 2))
+        diff = np.sqrt(np.mean((O[i] - o_ref) ** 2))
+        same = float((O[i] == o_ref).mean())
+        say("%s: rms difference %.2e of rms %.2e, %.1f %% of the values identical" % (s, diff, rms, 100 * same))
+        assert diff <= 0.01 * rms
+        if s[0] < s[1]:
+            sv, sv_ref = np.linalg.svd(O[i], compute_uv=False), np.linalg.svd(o_ref, compute_uv=False)
+            assert np.abs(sv - sv_ref).max() <= 0.01 and 0.6 < sv.min() and sv.max() < 1.25

@@ -19,11 +19,12 @@
 // M and N are multiples of the 128 x 128 block tile and K of 128 (two 64-deep tiles): the caller (muon.hip) keeps every matrix
 // in zero-padded workspace buffers, and zero rows and columns stay zero through the iteration.
 //
-// Tiling (128 x 128 block tile; 256 x 256 for large products): 256 lanes = 4 waves in a 2 x 2 grid, each wave a
-// 64 x 64 (128 x 128) tile = 2 x 2 (4 x 4) accumulators of
-// v_mfma_f32_32x32x16_bf16 (fp32 accumulation).  Operand tiles go global -> registers -> LDS (rows padded
-// by 16 bytes against bank conflicts), double-buffered, with the global loads issued two tiles ahead.  Workgroups are dealt to the 8 XCDs in turn, so block ids are remapped to give each XCD
-// (one L2 each) a contiguous band of output tiles.
+// Tiling: 128 x 128 block tile with 4 waves in a 2 x 2 grid (each wave 64 x 64 = 2 x 2 accumulators of
+// v_mfma_f32_32x32x16_bf16, fp32 accumulation); for products with at least 256 tiles of 256 x 256, that tile with
+// 8 waves in a 4 x 2 grid (each 64 x 128).  Operand tiles, 64 deep, go global -> registers -> LDS (rows padded by
+// 16 bytes against bank conflicts), double-buffered in LDS, with the global loads issued two tiles ahead.
+// Workgroups are dealt to the 8 XCDs in turn, so block ids are remapped to give each XCD (one L2 each) a
+// contiguous band of output tiles.
 
 #include "adagc_internal.h"
 
@@ -35,9 +36,11 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
 
+#ifndef ADAGC_GEMM_BIG_THREADS
+#define ADAGC_GEMM_BIG_THREADS 512      // lanes of a 256 x 256 workgroup: 8 waves (512) measured 5-7 % faster than 4 (256)
+#endif
 constexpr int kBK = 64;
 constexpr int kLdsRow = kBK + 8;                       // bf16 elements per LDS row (16 bytes of padding)
-constexpr int kGemmThreads = 256;
 constexpr int kVecPerRow = kBK / 8;                    // 16-byte vectors per tile row
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
@@ -52,14 +55,15 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 
 // BT x BT block tile (128 or 256).  SYM: the result is symmetric (P = Q, D symmetric) and C = Ct is one array: only
 // the tiles on and below the diagonal are computed, each written to its own place and to its mirror image.
-template <int BT, bool SYM>
+template <int BT, bool SYM, int kGemmThreads>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
     const uint16_t* __restrict__ P, int ldp, const uint16_t* __restrict__ Q, int ldq, int M, int N, int K,
     float alpha, float beta, const uint16_t* __restrict__ Dt, int lddt, uint16_t* __restrict__ C, int ldc,
     uint16_t* __restrict__ Ct, int ldct)
 {
     constexpr int kBM = BT, kBN = BT;
-    constexpr int kTM = kBM / 2, kTN = kBN / 2;            // wave tile (waves in a 2 x 2 grid)
+    constexpr int kWM = kGemmThreads / 128;                // waves in a kWM x 2 grid
+    constexpr int kTM = kBM / kWM, kTN = kBN / 2;          // wave tile
     constexpr int kMI = kTM / 32, kNI = kTN / 32;          // 32 x 32 accumulators per wave
     constexpr int kLoadsP = kBM * kVecPerRow / kGemmThreads;   // 16-byte loads per lane per P tile
     constexpr int kLoadsQ = kBN * kVecPerRow / kGemmThreads;
@@ -69,7 +73,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave >> 1, wn = wave & 1;               // wm in [0, kWM)
 
     // XCD-aware tile order: block b runs on XCD b mod 8; give XCD x the x-th contiguous eighth of the tiles.
     const int tiles_n = N / kBN;
@@ -231,15 +235,15 @@ hipError_t launch_gemm_nt_bf16(const void* P, int ldp, const void* Q, int ldq, i
         ldc = ldct;
         if (big) {
             const int t = M / 256;
-            gemm_nt_bf16_kernel<256, true><<<dim3(t * (t + 1) / 2), dim3(kGemmThreads), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+            gemm_nt_bf16_kernel<256, true, ADAGC_GEMM_BIG_THREADS><<<dim3(t * (t + 1) / 2), dim3(ADAGC_GEMM_BIG_THREADS), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
         } else {
             const int t = M / 128;
-            gemm_nt_bf16_kernel<128, true><<<dim3(t * (t + 1) / 2), dim3(kGemmThreads), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+            gemm_nt_bf16_kernel<128, true, 256><<<dim3(t * (t + 1) / 2), dim3(256), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
         }
     } else if (big) {
-        gemm_nt_bf16_kernel<256, false><<<dim3((M / 256) * (N / 256)), dim3(kGemmThreads), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+        gemm_nt_bf16_kernel<256, false, ADAGC_GEMM_BIG_THREADS><<<dim3((M / 256) * (N / 256)), dim3(ADAGC_GEMM_BIG_THREADS), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
     } else {
-        gemm_nt_bf16_kernel<128, false><<<dim3((M / 128) * (N / 128)), dim3(kGemmThreads), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+        gemm_nt_bf16_kernel<128, false, 256><<<dim3((M / 128) * (N / 128)), dim3(256), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
     }
     return hipGetLastError();
 }

@@ -36,6 +36,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
 
+#ifndef ADAGC_GEMM_GROUP_M
+#define ADAGC_GEMM_GROUP_M 8
+#endif
 #ifndef ADAGC_GEMM_BIG_THREADS
 #define ADAGC_GEMM_BIG_THREADS 512      // lanes of a 256 x 256 workgroup: 8 waves (512) measured 5-7 % faster than 4 (256)
 #endif
@@ -89,8 +92,17 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
         tile_m = r;
         tile_n = b - r * (r + 1) / 2;
     } else {
-        tile_m = b / tiles_n;
-        tile_n = b % tiles_n;
+        // walk the tiles in panels of kGroupM tile rows, down the rows of a panel first: the workgroups that run at
+        // the same time on an XCD then form a patch a few tiles high and wide and share both operands in its L2
+        constexpr int kGroupM = ADAGC_GEMM_GROUP_M;
+        const int tiles_m = M / kBM;
+        const int per_group = kGroupM * tiles_n;
+        const int group = b / per_group;
+        const int first_m = group * kGroupM;
+        const int rows_here = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
+        const int in_group = b - group * per_group;
+        tile_m = first_m + in_group % rows_here;
+        tile_n = in_group / rows_here;
     }
     const uint16_t* Pt = P + (size_t)tile_m * kBM * ldp;
     const uint16_t* Qt = Q + (size_t)tile_n * kBN * ldq;

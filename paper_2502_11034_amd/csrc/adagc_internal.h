@@ -68,7 +68,7 @@ struct UpdateArgs {
     double eps;
     double lr;             // Lion
     double weight_decay;   // Lion
-    double bias1;          // 1 - beta1^t (the direction's norms of the update-clipping modes)
+    double inv_bias1;      // 1 / (1 - beta1^t) (the direction's norms of the update-clipping modes)
     int    update_clip;    // 1: the direction is scaled by the tensor's update coefficient
     int    pad;
 };
@@ -143,7 +143,7 @@ inline void host_step_scalars(const adagc_hyper& hp, int64_t step, RuleArgs& r, 
     u.eps = (double)hp.eps;
     u.lr = lr;
     u.weight_decay = wd;
-    u.bias1 = 1.0 - std::pow(b1, t);
+    u.inv_bias1 = 1.0 / (1.0 - std::pow(b1, t));
     u.update_clip = (hp.clip_mode == ADAGC_MODE_AGC || hp.clip_mode == ADAGC_MODE_CLIPPY) ? 1 : 0;
     u.pad = 0;
 }

@@ -423,7 +423,7 @@ __global__ void prepare_step_kernel(DeviceTables t, const adagc_step_params* par
     sc.u.eps = (double)hp.eps;
     sc.u.lr = lr;
     sc.u.weight_decay = wd;
-    sc.u.bias1 = 1.0 - pow(b1, tt);
+    sc.u.inv_bias1 = 1.0 / (1.0 - pow(b1, tt));
     sc.u.update_clip = 0;                       // the update-clipping modes are rejected above
     sc.u.pad = 0;
     sc.r.lr = lr;
@@ -703,7 +703,7 @@ __device__ __forceinline__ double direction_elem(const UpdateArgs& a, float g, f
     if constexpr (OPT == ADAGC_OPT_ADAMW) {
         const double m = a.beta1 * (double)m_prev + a.one_minus_beta1 * gd;
         const double v = a.beta2 * (double)v_prev + a.one_minus_beta2 * gd * gd;
-        return (m / a.bias1) / (sqrt(v * a.inv_bias2) + a.eps);
+        return (m * a.inv_bias1) / (sqrt(v * a.inv_bias2) + a.eps);
     } else {
         return lion_sign(a, gd, m_prev);
     }

@@ -359,13 +359,20 @@ typedef struct {
 } adagc_muon_hyper;
 
 /*
- * Give the context the matrices' shapes and allocate the Newton-Schulz workspace (bf16, sized for the largest
- * matrix: four copies of its padded min x max extent and two of min x min).  Once per context.
+ * Give the context the matrices' shapes and allocate the Newton-Schulz workspace.  Once per context.
+ * Matrices whose extents, rounded up to multiples of 128, are equal are iterated together, up to 32 at a time
+ * (fewer if 32 would need more than 24 GiB), by batched launches of the matrix-core product: one launch over many
+ * matrices fills the GPU where one matrix has too few tiles.  The workspace (bf16) holds the largest such batch: per
+ * matrix four copies of its padded min x max extent and two of min x min (adagc_muon_workspace_bytes tells the
+ * total).  A matrix's result does not depend on which others share its batch.
  *   shapes  HOST  n_tensors entries, copied
  * Errors: INVALID_ARG (shape does not match numel), STATE (context not ADAGC_OPT_MUON, or attached already),
  * TOO_LARGE (a padded dimension beyond 2^31-1), OOM, HIP.
  */
 int adagc_muon_attach(adagc_ctx* ctx, const adagc_matrix_shape* shapes);
+
+/* Bytes of device workspace adagc_muon_attach allocated for this context (0 before it, or for a NULL context). */
+int64_t adagc_muon_workspace_bytes(const adagc_ctx* ctx);
 
 /*
  * One Muon step over the whole list, enqueued on `stream`; allocates nothing.
@@ -395,6 +402,18 @@ int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* const* grad
 int adagc_muon_gemm_nt(const void* P, int64_t ldp, const void* Q, int64_t ldq, int64_t M, int64_t N, int64_t K,
                        float alpha, float beta, const void* Dt, int64_t lddt, void* C, int64_t ldc, void* Ct,
                        int64_t ldct, int32_t symmetric, void* stream);
+
+/*
+ * The same product for `batch` (>= 1) sets of matrices of one shape in a single launch, as adagc_muon_step issues
+ * it: matrix z of every array starts z * its stride (in elements, a multiple of 8, >= 0) after the pointer given.
+ * strides  HOST array of 5: for P, Q, Dt, C, Ct in this order (entries of absent arrays are ignored; with
+ *          symmetric = 1 the strides of P and Q must be equal).  The caller sees to it that the batch's outputs do
+ *          not overlap.  Every matrix's result is the one adagc_muon_gemm_nt gives for it alone.
+ * Errors: INVALID_ARG, TOO_LARGE, HIP.
+ */
+int adagc_muon_gemm_nt_batched(const void* P, int64_t ldp, const void* Q, int64_t ldq, int64_t M, int64_t N, int64_t K,
+                               float alpha, float beta, const void* Dt, int64_t lddt, void* C, int64_t ldc, void* Ct,
+                               int64_t ldct, int32_t symmetric, int64_t batch, const int64_t* strides, void* stream);
 
 /* Static description of an error code. */
 const char* adagc_strerror(int code);

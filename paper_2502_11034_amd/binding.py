@@ -27,7 +27,8 @@ ADAGC_MODE_AGC, ADAGC_MODE_CLIPPY = 4, 5
 EXPORTS = [
     "adagc_chunk_elems", "adagc_build_segment_table", "adagc_build_visiting_order", "adagc_create", "adagc_destroy",
     "adagc_set_param_copies", "adagc_step", "adagc_step_graph", "adagc_step_static", "adagc_get_norms", "adagc_get_state_norms", "adagc_num_tensors",
-    "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end", "adagc_muon_gemm_nt", "adagc_muon_attach", "adagc_muon_step",
+    "adagc_num_chunks", "adagc_get_segment_table", "adagc_profile_begin", "adagc_profile_end", "adagc_muon_gemm_nt", "adagc_muon_gemm_nt_batched", "adagc_muon_attach",
+    "adagc_muon_workspace_bytes", "adagc_muon_step",
     "adagc_strerror",
 ]
 
@@ -126,6 +127,11 @@ def lib():
     L.adagc_muon_gemm_nt.restype = ctypes.c_int
     L.adagc_muon_gemm_nt.argtypes = [vp, i64, vp, i64, i64, i64, i64, ctypes.c_float, ctypes.c_float, vp, i64, vp, i64,
                                      vp, i64, i32, vp]
+    L.adagc_muon_gemm_nt_batched.restype = ctypes.c_int
+    L.adagc_muon_gemm_nt_batched.argtypes = [vp, i64, vp, i64, i64, i64, i64, ctypes.c_float, ctypes.c_float, vp, i64, vp, i64,
+                                             vp, i64, i32, i64, vp, vp]
+    L.adagc_muon_workspace_bytes.restype = ctypes.c_int64
+    L.adagc_muon_workspace_bytes.argtypes = [vp]
     L.adagc_strerror.restype = ctypes.c_char_p
     L.adagc_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -210,6 +216,19 @@ def adagc_muon_gemm_nt(P, Q, alpha=1.0, beta=0.0, Dt=None, C=None, Ct=None, stre
            "adagc_muon_gemm_nt")
 
 
+def adagc_muon_gemm_nt_batched(P, Q, alpha=1.0, beta=0.0, Dt=None, C=None, Ct=None, stream=None, symmetric=False):
+    """adagc_muon_gemm_nt_batched on 3-D bf16 device tensors [batch, rows, cols]: matrix z of every array is its [z]."""
+    batch, M, K = P.shape
+    N = Q.shape[1]
+    ld = lambda t: t.stride(1) if t is not None else 0
+    dp = lambda t: t.data_ptr() if t is not None else None
+    strides = (ctypes.c_int64 * 5)(*[t.stride(0) if t is not None else 0 for t in (P, Q, Dt, C, Ct)])
+    _check(lib().adagc_muon_gemm_nt_batched(P.data_ptr(), ld(P), Q.data_ptr(), ld(Q), M, N, K, float(alpha), float(beta), dp(Dt),
+                                            ld(Dt), dp(C), ld(C), dp(Ct), ld(Ct), int(bool(symmetric)), int(batch), strides,
+                                            ctypes.c_void_p(stream) if stream else None),
+           "adagc_muon_gemm_nt_batched")
+
+
 ADAGC_STATIC_MAX_TENSORS = 32768
 ADAGC_STATIC_MAX_CHUNKS = 524288
 
@@ -278,6 +297,9 @@ class AdaGC:
         for i, (r, c) in enumerate(shapes):
             arr[i].rows, arr[i].cols = int(r), int(c)
         _check(lib().adagc_muon_attach(self._ctx, ctypes.cast(arr, ctypes.c_void_p)), "adagc_muon_attach")
+
+    def muon_workspace_bytes(self):
+        return int(lib().adagc_muon_workspace_bytes(self._ctx))
 
     def muon_step(self, params, grads, momentum, ema_norms, hyper, muon_hyper, step, stream=None):
         p, g, m = (ptr_array(x) for x in (params, grads, momentum))

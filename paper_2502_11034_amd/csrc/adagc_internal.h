@@ -160,10 +160,12 @@ hipError_t launch_update(const DeviceTables& t, const UpdateArgs& u, int optimiz
 hipError_t launch_update_clip_rule(const DeviceTables& t, const UpdateArgs& u, const RuleArgs& r, int optimizer,
                                    int grad_bf16, int items_per_chunk, int nt, int grid, hipStream_t stream);
 // bf16 matrix-core GEMM of the Newton-Schulz iteration (muon_gemm.hip): C = bf16(alpha P Q^T + beta D), D given
-// through its transpose Dt, result written row-major (C), transposed (Ct) or both.
+// through its transpose Dt, result written row-major (C), transposed (Ct) or both; batch products of one shape per
+// launch, matrix z of each array at base + z * stride elements.
 hipError_t launch_gemm_nt_bf16(const void* P, int ldp, const void* Q, int ldq, int M, int N, int K, float alpha,
                                float beta, const void* Dt, int lddt, void* C, int ldc, void* Ct, int ldct,
-                               hipStream_t stream, bool symmetric = false);
+                               hipStream_t stream, bool symmetric = false, int batch = 1, int64_t stride_p = 0,
+                               int64_t stride_q = 0, int64_t stride_dt = 0, int64_t stride_c = 0, int64_t stride_ct = 0);
 // Muon (muon.hip): per-tensor sums of the per-chunk partials into t.sumsq; momentum update with the clipped
 // gradient and the partial sums of squares of U; X0 of one matrix into the padded workspace; the parameter update.
 hipError_t launch_tensor_sumsq(const DeviceTables& t, hipStream_t stream);

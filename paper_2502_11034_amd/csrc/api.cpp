@@ -41,10 +41,16 @@ struct adagc_ctx {
     uint64_t     uploads = 0;                 // tables uploaded so far; slot = uploads % kStagingSlots
     bool         device_scalars_used = false;   // adagc_step_graph was called: its status word is meaningful
 
-    // Muon (adagc_muon_attach): shapes and the Newton-Schulz workspace, carved out of one allocation
+    // Muon (adagc_muon_attach): shapes, the batches the Newton-Schulz iteration runs in (matrices of one padded
+    // shape, iterated together by batched launches) and the workspace one batch at a time is carved out of
+    struct MuonBatch {
+        int mp = 0, np = 0;                  // padded extent of the wide orientation
+        std::vector<int64_t> members;        // tensor indices
+    };
     std::vector<adagc_matrix_shape> shapes;
-    void*     muon_ws = nullptr;
-    uint16_t *ws_x[2] = {nullptr, nullptr}, *ws_y[2] = {nullptr, nullptr}, *ws_a = nullptr, *ws_b = nullptr;
+    std::vector<MuonBatch> muon_batches;
+    void*  muon_ws = nullptr;
+    size_t muon_ws_bytes = 0;
 
     std::vector<hipEvent_t> prof_events;      // 4 per step while profiling
     int32_t                 prof_capacity = 0;
@@ -442,43 +448,73 @@ extern "C" int adagc_step_graph(adagc_ctx* ctx, void* const* params, const void*
 
 namespace {
 constexpr int64_t kMuonTile = 128;     // the matrix-core kernel's block tile: workspace matrices are padded to it
+// Matrices of one padded shape are iterated together, up to this many per batched launch and as many as fit this much
+// workspace (32 matrices of 4096 x 14336 take 17.2 GB).  32 is where the symmetric products of 4096-row matrices fill
+// whole rounds of workgroups: 32 x 136 tiles of 256 x 256 = 17 x 256 compute units.
+constexpr int64_t kMuonMaxBatch = 32;
+constexpr int64_t kMuonWorkspaceBudget = (int64_t)24 << 30;
 inline int64_t pad_to_tile(int64_t x) { return (x + kMuonTile - 1) / kMuonTile * kMuonTile; }
+// bf16 elements of workspace per matrix: X and Y = X^T twice (a step reads one pair and writes the other), A and B
+inline int64_t muon_ws_elems(int64_t mp, int64_t np) { return 4 * mp * np + 2 * mp * mp; }
 }  // namespace
 
 extern "C" int adagc_muon_attach(adagc_ctx* ctx, const adagc_matrix_shape* shapes)
 {
     if (!ctx || !shapes) return ADAGC_ERR_INVALID_ARG;
     if (ctx->cfg.optimizer != ADAGC_OPT_MUON || ctx->muon_ws) return ADAGC_ERR_STATE;
-    int64_t max_mn = 0, max_mm = 0;
-    for (int64_t i = 0; i < ctx->n_tensors; ++i) {
-        const int64_t r = shapes[i].rows, c = shapes[i].cols;
-        if (r <= 0 || c <= 0 || r > INT32_MAX || c > INT32_MAX || r * c != ctx->numel[(size_t)i]) return ADAGC_ERR_INVALID_ARG;
-        const int64_t mp = pad_to_tile(r < c ? r : c), np = pad_to_tile(r < c ? c : r);
-        if (np > INT32_MAX || np / 64 > 65535) return ADAGC_ERR_TOO_LARGE;
-        if (mp * np > max_mn) max_mn = mp * np;
-        if (mp * mp > max_mm) max_mm = mp * mp;
-    }
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return ADAGC_ERR_HIP;
+    std::vector<adagc_ctx::MuonBatch> groups, batches;
+    int64_t ws_elems = 0;
     try {
+        for (int64_t i = 0; i < ctx->n_tensors; ++i) {
+            const int64_t r = shapes[i].rows, c = shapes[i].cols;
+            if (r <= 0 || c <= 0 || r > INT32_MAX || c > INT32_MAX || r * c != ctx->numel[(size_t)i]) return ADAGC_ERR_INVALID_ARG;
+            const int64_t mp = pad_to_tile(r < c ? r : c), np = pad_to_tile(r < c ? c : r);
+            if (np > INT32_MAX || np / 64 > 65535) return ADAGC_ERR_TOO_LARGE;
+            size_t g = 0;
+            while (g < groups.size() && (groups[g].mp != mp || groups[g].np != np)) ++g;
+            if (g == groups.size()) {
+                groups.emplace_back();
+                groups[g].mp = (int)mp;
+                groups[g].np = (int)np;
+            }
+            groups[g].members.push_back(i);
+        }
+        // cut every group into batches of equal size (to one matrix), as large as the limits allow
+        for (const adagc_ctx::MuonBatch& grp : groups) {
+            const int64_t per_matrix = muon_ws_elems(grp.mp, grp.np) * (int64_t)sizeof(uint16_t);
+            int64_t cap = kMuonWorkspaceBudget / per_matrix;
+            if (cap > kMuonMaxBatch) cap = kMuonMaxBatch;
+            if (cap < 1) cap = 1;
+            const int64_t count = (int64_t)grp.members.size();
+            const int64_t n_batches = (count + cap - 1) / cap;
+            const int64_t size = (count + n_batches - 1) / n_batches;
+            for (int64_t first = 0; first < count; first += size) {
+                const int64_t n = count - first < size ? count - first : size;
+                batches.emplace_back();
+                batches.back().mp = grp.mp;
+                batches.back().np = grp.np;
+                batches.back().members.assign(grp.members.begin() + first, grp.members.begin() + first + n);
+                const int64_t need = n * muon_ws_elems(grp.mp, grp.np);
+                if (need > ws_elems) ws_elems = need;
+            }
+        }
         ctx->shapes.assign(shapes, shapes + ctx->n_tensors);
     } catch (const std::bad_alloc&) { return ADAGC_ERR_OOM; }
-    const size_t bytes = (size_t)(4 * max_mn + 2 * max_mm) * sizeof(uint16_t);
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return ADAGC_ERR_HIP;
+    const size_t bytes = (size_t)ws_elems * sizeof(uint16_t);
     const hipError_t e = hipMalloc(&ctx->muon_ws, bytes);
     if (e != hipSuccess) {
         ctx->muon_ws = nullptr;
         ctx->shapes.clear();
         return e == hipErrorOutOfMemory ? ADAGC_ERR_OOM : ADAGC_ERR_HIP;
     }
-    uint16_t* p = static_cast<uint16_t*>(ctx->muon_ws);
-    ctx->ws_x[0] = p;
-    ctx->ws_x[1] = p + max_mn;
-    ctx->ws_y[0] = p + 2 * max_mn;
-    ctx->ws_y[1] = p + 3 * max_mn;
-    ctx->ws_a = p + 4 * max_mn;
-    ctx->ws_b = ctx->ws_a + max_mm;
+    ctx->muon_ws_bytes = bytes;
+    ctx->muon_batches.swap(batches);
     return ADAGC_OK;
 }
+
+extern "C" int64_t adagc_muon_workspace_bytes(const adagc_ctx* ctx) { return ctx && ctx->muon_ws ? (int64_t)ctx->muon_ws_bytes : 0; }
 
 extern "C" int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* const* grads, void* const* momentum,
                                float* ema_norms, const adagc_hyper* hp, const adagc_muon_hyper* mh, int64_t step,
@@ -524,38 +560,52 @@ extern "C" int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* 
     if (launch_muon_momentum(t, mu, mh->nesterov, bf16g, ctx->grid_norm, stream) != hipSuccess) return ADAGC_ERR_HIP;
     if (launch_tensor_sumsq(t, stream) != hipSuccess) return ADAGC_ERR_HIP;
 
-    // Newton-Schulz and the update, matrix by matrix
+    // Newton-Schulz and the update, batch by batch.  Matrix z of a batch has slot z of each workspace array:
+    // X is mp x np (leading dimension np), Y = X^T is np x mp (leading dimension mp), A and B are mp x mp.
     const float ns_a = 3.4445f, ns_b = -4.7750f, ns_c = 2.0315f;
-    for (int64_t i = 0; i < ctx->n_tensors; ++i) {
-        const int64_t rows = ctx->shapes[(size_t)i].rows, cols = ctx->shapes[(size_t)i].cols;
-        const bool flip = rows > cols;                      // the iteration runs on the wide orientation
-        const int64_t m = flip ? cols : rows, n = flip ? rows : cols;
-        const int mp = (int)pad_to_tile(m), np = (int)pad_to_tile(n);
-        uint16_t *x = ctx->ws_x[0], *y = ctx->ws_y[0], *x2 = ctx->ws_x[1], *y2 = ctx->ws_y[1];
-        // X is mp x np (leading dimension np), Y = X^T is np x mp (leading dimension mp)
-        hipError_t g = flip ? launch_muon_normalise(grads[i], momentum[i], rows, cols, np, mp, t.coef64 + i, t.sumsq + i, mu,
-                                                    mh->nesterov, bf16g, y, mp, x, np, stream)
-                            : launch_muon_normalise(grads[i], momentum[i], rows, cols, mp, np, t.coef64 + i, t.sumsq + i, mu,
-                                                    mh->nesterov, bf16g, x, np, y, mp, stream);
-        if (g != hipSuccess) return ADAGC_ERR_HIP;
+    for (const adagc_ctx::MuonBatch& bt : ctx->muon_batches) {
+        const int mp = bt.mp, np = bt.np;
+        const int count = (int)bt.members.size();
+        const int64_t mn = (int64_t)mp * np, mm = (int64_t)mp * mp;
+        uint16_t* base = static_cast<uint16_t*>(ctx->muon_ws);
+        uint16_t *x = base, *x2 = base + count * mn, *y = base + 2 * count * mn, *y2 = base + 3 * count * mn;
+        uint16_t *wa = base + 4 * count * mn, *wb = wa + count * mm;
+        for (int z = 0; z < count; ++z) {
+            const int64_t i = bt.members[(size_t)z];
+            const int64_t rows = ctx->shapes[(size_t)i].rows, cols = ctx->shapes[(size_t)i].cols;
+            const bool flip = rows > cols;                  // the iteration runs on the wide orientation
+            const hipError_t g =
+                flip ? launch_muon_normalise(grads[i], momentum[i], rows, cols, np, mp, t.coef64 + i, t.sumsq + i, mu, mh->nesterov,
+                                             bf16g, y + z * mn, mp, x + z * mn, np, stream)
+                     : launch_muon_normalise(grads[i], momentum[i], rows, cols, mp, np, t.coef64 + i, t.sumsq + i, mu, mh->nesterov,
+                                             bf16g, x + z * mn, np, y + z * mn, mp, stream);
+            if (g != hipSuccess) return ADAGC_ERR_HIP;
+        }
         for (int k = 0; k < mh->ns_steps; ++k) {
             // A = X X^T (symmetric: its transposed store is itself)
-            if (launch_gemm_nt_bf16(x, np, x, np, mp, mp, np, 1.0f, 0.0f, nullptr, 0, nullptr, 0, ctx->ws_a, mp, stream, true) != hipSuccess)
+            if (launch_gemm_nt_bf16(x, np, x, np, mp, mp, np, 1.0f, 0.0f, nullptr, 0, nullptr, 0, wa, mp, stream, true, count, mn, mn,
+                                    0, mm, mm) != hipSuccess)
                 return ADAGC_ERR_HIP;
             // B = b A + c A A
-            if (launch_gemm_nt_bf16(ctx->ws_a, mp, ctx->ws_a, mp, mp, mp, mp, ns_c, ns_b, ctx->ws_a, mp, nullptr, 0, ctx->ws_b, mp,
-                                    stream, true) != hipSuccess)
+            if (launch_gemm_nt_bf16(wa, mp, wa, mp, mp, mp, mp, ns_c, ns_b, wa, mp, nullptr, 0, wb, mp, stream, true, count, mm, mm, mm,
+                                    mm, mm) != hipSuccess)
                 return ADAGC_ERR_HIP;
             // X' = a X + B X, written as X' and as Y' = X'^T; (B X)[i][j] = sum_k B[i][k] Y[j][k]
-            if (launch_gemm_nt_bf16(ctx->ws_b, mp, y, mp, mp, np, mp, 1.0f, ns_a, y, mp, x2, np, y2, mp, stream) != hipSuccess)
+            if (launch_gemm_nt_bf16(wb, mp, y, mp, mp, np, mp, 1.0f, ns_a, y, mp, x2, np, y2, mp, stream, false, count, mm, mn, mn, mn,
+                                    mn) != hipSuccess)
                 return ADAGC_ERR_HIP;
             uint16_t* s = x; x = x2; x2 = s;
             s = y; y = y2; y2 = s;
         }
-        const double scale = std::sqrt(rows > cols ? (double)rows / (double)cols : 1.0);
-        g = launch_muon_apply(params[i], flip ? y : x, flip ? mp : np, rows, cols, (double)h.lr, (double)h.weight_decay, scale,
-                              copy ? ctx->param_copies[(size_t)i] : nullptr, stream);
-        if (g != hipSuccess) return ADAGC_ERR_HIP;
+        for (int z = 0; z < count; ++z) {
+            const int64_t i = bt.members[(size_t)z];
+            const int64_t rows = ctx->shapes[(size_t)i].rows, cols = ctx->shapes[(size_t)i].cols;
+            const bool flip = rows > cols;
+            const double scale = std::sqrt(flip ? (double)rows / (double)cols : 1.0);
+            const hipError_t g = launch_muon_apply(params[i], (flip ? y : x) + z * mn, flip ? mp : np, rows, cols, (double)h.lr,
+                                                   (double)h.weight_decay, scale, copy ? ctx->param_copies[(size_t)i] : nullptr, stream);
+            if (g != hipSuccess) return ADAGC_ERR_HIP;
+        }
     }
     if (prof) {
         if (hipEventRecord(ev[3], stream) != hipSuccess) return ADAGC_ERR_HIP;

@@ -20,8 +20,8 @@
 // in zero-padded workspace buffers, and zero rows and columns stay zero through the iteration.
 //
 // Tiling: 128 x 128 block tile with 4 waves in a 2 x 2 grid (each wave 64 x 64 = 2 x 2 accumulators of
-// v_mfma_f32_32x32x16_bf16, fp32 accumulation); for products with at least 256 tiles of 256 x 256, that tile with
-// 8 waves in a 4 x 2 grid (each 64 x 128).  Operand tiles, 64 deep, go global -> registers -> LDS (rows padded by
+// v_mfma_f32_32x32x16_bf16, fp32 accumulation); where the launch has enough of them to fill the compute units,
+// 256 x 256 tiles with 8 waves in a 4 x 2 grid (each 64 x 128).  One launch can cover a batch of equal-shaped products.  Operand tiles, 64 deep, go global -> registers -> LDS (rows padded by
 // 16 bytes against bank conflicts), double-buffered in LDS, with the global loads issued two tiles ahead.
 // Workgroups are dealt to the 8 XCDs in turn, so block ids are remapped to give each XCD (one L2 each) a
 // contiguous band of output tiles.
@@ -35,6 +35,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+
+// Distance in elements from one matrix of a batch to the next, per array (0 for a single product).
+struct GemmBatch {
+    int64_t stride_p, stride_q, stride_dt, stride_c, stride_ct;
+};
 
 #ifndef ADAGC_GEMM_GROUP_M
 #define ADAGC_GEMM_GROUP_M 8
@@ -62,7 +67,7 @@ template <int BT, bool SYM, int kGemmThreads>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
     const uint16_t* __restrict__ P, int ldp, const uint16_t* __restrict__ Q, int ldq, int M, int N, int K,
     float alpha, float beta, const uint16_t* __restrict__ Dt, int lddt, uint16_t* __restrict__ C, int ldc,
-    uint16_t* __restrict__ Ct, int ldct)
+    uint16_t* __restrict__ Ct, int ldct, GemmBatch bt)
 {
     constexpr int kBM = BT, kBN = BT;
     constexpr int kWM = kGemmThreads / 128;                // waves in a kWM x 2 grid
@@ -78,11 +83,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
     const int wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;               // wm in [0, kWM)
 
-    // XCD-aware tile order: block b runs on XCD b mod 8; give XCD x the x-th contiguous eighth of the tiles.
+    // XCD-aware tile order: block b runs on XCD b mod 8; give XCD x the x-th contiguous eighth of the tiles of the
+    // whole batch (with 8 or more matrices in the batch an XCD then stays on its own matrices).
     const int tiles_n = N / kBN;
-    const int n_tiles = SYM ? tiles_n * (tiles_n + 1) / 2 : (M / kBM) * tiles_n;
+    const int n_tiles = SYM ? tiles_n * (tiles_n + 1) / 2 : (M / kBM) * tiles_n;     // per matrix
+    const int all_tiles = (int)gridDim.x;                                             // n_tiles x matrices
     int b = blockIdx.x;
-    if (n_tiles % 8 == 0) b = (b % 8) * (n_tiles / 8) + b / 8;
+    if (all_tiles % 8 == 0) b = (b % 8) * (all_tiles / 8) + b / 8;
+    const int z = b / n_tiles;                             // matrix of the batch
+    b -= z * n_tiles;
+    P += (size_t)z * bt.stride_p;
+    Q += (size_t)z * bt.stride_q;
+    if (Dt) Dt += (size_t)z * bt.stride_dt;
+    if (C) C += (size_t)z * bt.stride_c;
+    if (Ct) Ct += (size_t)z * bt.stride_ct;
     int tile_m, tile_n;
     if constexpr (SYM) {
         // b-th tile of the lower triangle, row by row: row r starts at r (r + 1) / 2
@@ -228,52 +242,83 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
 
 // M, N, K must be multiples of 128 and every leading dimension a multiple of 8 elements (16-byte rows).
 // symmetric: P = Q (and D symmetric), so the result is symmetric: C and Ct are then the same array (pass it as Ct)
-// and only the lower triangle of tiles is computed.  Tiles of 256 x 256 where the shape allows and fills the GPU.
+// and only the lower triangle of tiles is computed.
+// batch > 1: that many products of the same shape in one launch, matrix z of every array at its base + z * stride
+// (elements).  One launch over many matrices keeps all compute units busy where one matrix has too few tiles, and
+// spreads the partly filled last round of workgroups over the whole batch instead of paying it per matrix.
 hipError_t launch_gemm_nt_bf16(const void* P, int ldp, const void* Q, int ldq, int M, int N, int K, float alpha,
                                float beta, const void* Dt, int lddt, void* C, int ldc, void* Ct, int ldct,
-                               hipStream_t stream, bool symmetric)
+                               hipStream_t stream, bool symmetric, int batch, int64_t stride_p, int64_t stride_q,
+                               int64_t stride_dt, int64_t stride_c, int64_t stride_ct)
 {
     if (M <= 0 || N <= 0 || K <= 0 || M % 128 || N % 128 || K % 128 || ldp % 8 || ldq % 8 || (Dt && lddt % 8) ||
-        (Ct && ldct % 8) || (!C && !Ct))
+        (Ct && ldct % 8) || (!C && !Ct) || batch < 1)
         return hipErrorInvalidValue;
-    if (symmetric && (M != N || P != Q || !Ct || (C && C != Ct))) return hipErrorInvalidValue;
+    if ((stride_p | stride_q | stride_dt | stride_c | stride_ct) % 8 || stride_p < 0 || stride_q < 0 || stride_dt < 0 ||
+        stride_c < 0 || stride_ct < 0)
+        return hipErrorInvalidValue;
+    if (symmetric && (M != N || P != Q || stride_p != stride_q || !Ct || (C && (C != Ct || stride_c != stride_ct))))
+        return hipErrorInvalidValue;
     const uint16_t *p = static_cast<const uint16_t*>(P), *q = static_cast<const uint16_t*>(Q), *dt = static_cast<const uint16_t*>(Dt);
     uint16_t *c = static_cast<uint16_t*>(C), *ct = static_cast<uint16_t*>(Ct);
-    // 256 x 256 tiles multiply faster, but only when there are enough of them for the 256 compute units
-    const int64_t big_tiles = symmetric ? (int64_t)(M / 256) * (M / 256 + 1) / 2 : (int64_t)(M / 256) * (N / 256);
-    const bool big = (M % 256 == 0) && (N % 256 == 0) && big_tiles >= 256;
+    // Tile choice.  A compute unit holds one 256 x 256 workgroup or two 128 x 128 ones, and multiplies about a quarter
+    // faster on the large tile (fewer LDS reads per matrix-core instruction); a launch costs whole rounds of workgroups.
+    // Compare the two in units of "one 128-tile on a shared compute unit": a round of large tiles is 4 / 1.25 of them.
+    const int64_t t128 = symmetric ? (int64_t)(M / 128) * (M / 128 + 1) / 2 : (int64_t)(M / 128) * (N / 128);
+    const int64_t t256 = symmetric ? (int64_t)(M / 256) * (M / 256 + 1) / 2 : (int64_t)(M / 256) * (N / 256);
+    const int64_t n128 = t128 * batch, n256 = t256 * batch;
+    const double cost128 = 2.0 * (double)((n128 + 511) / 512);
+    const double cost256 = 3.2 * (double)((n256 + 255) / 256);
+    const bool big = (M % 256 == 0) && (N % 256 == 0) && cost256 < cost128;
+    const int64_t blocks = big ? n256 : n128;
+    if (blocks > INT32_MAX) return hipErrorInvalidValue;
+    const GemmBatch bt{stride_p, stride_q, stride_dt, symmetric ? stride_ct : stride_c, stride_ct};
     if (symmetric) {
         c = ct;
         ldc = ldct;
-        if (big) {
-            const int t = M / 256;
-            gemm_nt_bf16_kernel<256, true, ADAGC_GEMM_BIG_THREADS><<<dim3(t * (t + 1) / 2), dim3(ADAGC_GEMM_BIG_THREADS), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
-        } else {
-            const int t = M / 128;
-            gemm_nt_bf16_kernel<128, true, 256><<<dim3(t * (t + 1) / 2), dim3(256), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
-        }
+        if (big)
+            gemm_nt_bf16_kernel<256, true, ADAGC_GEMM_BIG_THREADS><<<dim3((uint32_t)blocks), dim3(ADAGC_GEMM_BIG_THREADS), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct, bt);
+        else
+            gemm_nt_bf16_kernel<128, true, 256><<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct, bt);
     } else if (big) {
-        gemm_nt_bf16_kernel<256, false, ADAGC_GEMM_BIG_THREADS><<<dim3((M / 256) * (N / 256)), dim3(ADAGC_GEMM_BIG_THREADS), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+        gemm_nt_bf16_kernel<256, false, ADAGC_GEMM_BIG_THREADS><<<dim3((uint32_t)blocks), dim3(ADAGC_GEMM_BIG_THREADS), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct, bt);
     } else {
-        gemm_nt_bf16_kernel<128, false, 256><<<dim3((M / 128) * (N / 128)), dim3(256), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct);
+        gemm_nt_bf16_kernel<128, false, 256><<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(p, ldp, q, ldq, M, N, K, alpha, beta, dt, lddt, c, ldc, ct, ldct, bt);
     }
     return hipGetLastError();
 }
 
 }  // namespace adagc
 
-// Test hook of the matrix-core GEMM through the C ABI (see include/adagc.h).
+// The matrix-core GEMM through the C ABI, single and batched (see include/adagc.h).
+extern "C" int adagc_muon_gemm_nt_batched(const void* P, int64_t ldp, const void* Q, int64_t ldq, int64_t M, int64_t N, int64_t K,
+                                          float alpha, float beta, const void* Dt, int64_t lddt, void* C, int64_t ldc, void* Ct,
+                                          int64_t ldct, int32_t symmetric, int64_t batch, const int64_t* strides, void* stream)
+{
+    if (!P || !Q || batch < 1 || (batch > 1 && !strides)) return ADAGC_ERR_INVALID_ARG;
+    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldp > INT32_MAX || ldq > INT32_MAX || lddt > INT32_MAX ||
+        ldc > INT32_MAX || ldct > INT32_MAX || batch > INT32_MAX)
+        return ADAGC_ERR_TOO_LARGE;
+    if (ldp < K || ldq < K || (Dt && lddt < M) || (C && ldc < N) || (Ct && ldct < M)) return ADAGC_ERR_INVALID_ARG;
+    int64_t st[5] = {0, 0, 0, 0, 0};
+    if (strides) {
+        st[0] = strides[0];
+        st[1] = strides[1];
+        st[2] = Dt ? strides[2] : 0;
+        st[3] = C ? strides[3] : 0;
+        st[4] = Ct ? strides[4] : 0;
+        if (symmetric && C == nullptr) st[3] = st[4];
+    }
+    const hipError_t e = adagc::launch_gemm_nt_bf16(P, (int)ldp, Q, (int)ldq, (int)M, (int)N, (int)K, alpha, beta, Dt, (int)lddt,
+                                                    C, (int)ldc, Ct, (int)ldct, static_cast<hipStream_t>(stream), symmetric != 0,
+                                                    (int)batch, st[0], st[1], st[2], st[3], st[4]);
+    if (e == hipErrorInvalidValue) return ADAGC_ERR_INVALID_ARG;
+    return e == hipSuccess ? ADAGC_OK : ADAGC_ERR_HIP;
+}
+
 extern "C" int adagc_muon_gemm_nt(const void* P, int64_t ldp, const void* Q, int64_t ldq, int64_t M, int64_t N, int64_t K,
                                   float alpha, float beta, const void* Dt, int64_t lddt, void* C, int64_t ldc, void* Ct,
                                   int64_t ldct, int32_t symmetric, void* stream)
 {
-    if (!P || !Q) return ADAGC_ERR_INVALID_ARG;
-    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldp > INT32_MAX || ldq > INT32_MAX || lddt > INT32_MAX ||
-        ldc > INT32_MAX || ldct > INT32_MAX)
-        return ADAGC_ERR_TOO_LARGE;
-    if (ldp < K || ldq < K || (Dt && lddt < M) || (C && ldc < N) || (Ct && ldct < M)) return ADAGC_ERR_INVALID_ARG;
-    const hipError_t e = adagc::launch_gemm_nt_bf16(P, (int)ldp, Q, (int)ldq, (int)M, (int)N, (int)K, alpha, beta, Dt, (int)lddt,
-                                                    C, (int)ldc, Ct, (int)ldct, static_cast<hipStream_t>(stream), symmetric != 0);
-    if (e == hipErrorInvalidValue) return ADAGC_ERR_INVALID_ARG;
-    return e == hipSuccess ? ADAGC_OK : ADAGC_ERR_HIP;
+    return adagc_muon_gemm_nt_batched(P, ldp, Q, ldq, M, N, K, alpha, beta, Dt, lddt, C, ldc, Ct, ldct, symmetric, 1, nullptr, stream);
 }

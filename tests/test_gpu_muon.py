@@ -66,7 +66,7 @@ def test_matrix_core_product_matches_the_oracle(M, N, K, ld_extra):
     assert (np.abs(g2 - ref2) <= 2.0 ** -7 * np.abs(ref2) + 1e-5 * (np.abs(P) @ np.abs(Q).T)).all()
 
 
-@pytest.mark.parametrize("M,K", [(128, 128), (384, 256), (1024, 512), (6144, 128)])
+@pytest.mark.parametrize("M,K", [(128, 128), (384, 256), (1024, 512), (4096, 128), (6144, 128)])   # 4096: 256 x 256 tiles
 def test_symmetric_matrix_core_product(M, K):
     """P = Q: only the tiles on and below the diagonal are computed and each is stored twice.  The result must be
     exactly symmetric and equal to the full product's (the same sums in the same order)."""
@@ -90,6 +90,47 @@ def test_symmetric_matrix_core_product(M, K):
     assert (np.abs(got - ref) <= 2.0 ** -7 * np.abs(ref) + slack).all()
     with pytest.raises(B.AdagcError):
         B.adagc_muon_gemm_nt(dP, bf16_dev(P), 1.0, 0.0, None, None, S, symmetric=True)      # P and Q must be the same array
+
+
+@pytest.mark.parametrize("batch,M,N,K,symmetric", [(3, 128, 256, 128, False), (5, 384, 384, 256, True), (2, 4096, 4096, 128, True),
+                                                     (8, 1024, 2048, 128, False), (32, 512, 512, 128, True)])
+def test_batched_matrix_core_product_equals_the_single_ones(batch, M, N, K, symmetric):
+    """One launch over a batch of products of one shape: every matrix's result is, bit for bit, what the single
+    launch gives for it (whatever tile size either launch picks: a result element is the same sum in the same
+    order on both tiles), and nothing outside the batch's outputs is written."""
+    rng = np.random.default_rng(batch * 1000 + M + N + K)
+    gen = torch.Generator(device="cpu").manual_seed(int(rng.integers(1 << 30)))
+    P = (torch.randn((batch, M, K), generator=gen) * 0.05).to(torch.bfloat16).to(DEV)
+    Q = P if symmetric else (torch.randn((batch, N, K), generator=gen) * 0.05).to(torch.bfloat16).to(DEV)
+    D = torch.randn((batch, N, M), generator=gen) * 0.3
+    if symmetric:
+        D = D + D.transpose(1, 2)
+    Dt = D.to(torch.bfloat16).to(DEV)
+    guard = 7.0
+    Ct = torch.full((batch + 1, N, M), guard, dtype=torch.bfloat16, device=DEV)
+    C = None if symmetric else torch.full((batch + 1, M, N), guard, dtype=torch.bfloat16, device=DEV)
+    B.adagc_muon_gemm_nt_batched(P, Q, 2.0315, -4.775, Dt, None if symmetric else C[:batch], Ct[:batch], symmetric=symmetric)
+    torch.cuda.synchronize()
+    assert (Ct[batch] == guard).all() and (symmetric or (C[batch] == guard).all())
+    for z in range(batch):
+        one_t = torch.zeros((N, M), dtype=torch.bfloat16, device=DEV)
+        one = None if symmetric else torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+        B.adagc_muon_gemm_nt(P[z], Q[z], 2.0315, -4.775, Dt[z], one, one_t, symmetric=symmetric)
+        torch.cuda.synchronize()
+        assert torch.equal(Ct[z].view(torch.int16), one_t.view(torch.int16)), "matrix %d of the batch" % z
+        if not symmetric:
+            assert torch.equal(C[z].view(torch.int16), one.view(torch.int16)), "matrix %d of the batch (row-major)" % z
+    # and one matrix of the batch against the oracle's product
+    z = batch - 1
+    f = lambda v: float(np.float32(v))
+    p64, q64, d64 = host64(P[z]), host64(Q[z]), host64(Dt[z]).T
+    ref = OM.to_bf16(f(2.0315) * (p64 @ q64.T) + f(-4.775) * d64)
+    slack = 1e-5 * (f(2.0315) * (np.abs(p64) @ np.abs(q64).T) + np.abs(f(-4.775) * d64))
+    assert (np.abs(host64(Ct[z]).T - ref) <= 2.0 ** -7 * np.abs(ref) + slack).all()
+    if batch == 3:
+        buf = torch.zeros(batch * (N * M + 4), dtype=torch.bfloat16, device=DEV)
+        with pytest.raises(B.AdagcError):            # a stride that is not a multiple of 8 elements
+            B.adagc_muon_gemm_nt_batched(P, Q, 1.0, 0.0, None, None, buf.as_strided((batch, N, M), (N * M + 4, M, 1)))
 
 
 def test_matrix_core_product_places_every_element():
@@ -259,6 +300,35 @@ def test_muon_five_steps_end_to_end():
         assert diff <= 0.01 * rms
         sv_ref = np.linalg.svd(o_ref, compute_uv=False)
         assert np.abs(sv - sv_ref).max() <= 0.01 and sv.max() < 1.25
+
+
+def test_muon_matrices_iterated_in_batches_give_the_results_of_single_ones():
+    """Matrices whose padded extents agree share batched launches (here: 64 x 200, 200 x 64 and 100 x 250 all pad to
+    128 x 256, wide and tall ones mixed; 40 of one shape make two batches of 20).  Every tensor's parameters and momentum
+    must be, bit for bit, what a context holding that tensor alone produces."""
+    shapes = [(64, 200), (300, 100), (200, 64), (64, 200), (100, 250), (100, 300), (128, 128)] + [(130, 300)] * 40
+    g, m, th = _inputs(8, shapes)
+    gamma = np.array([oracle.l2_norm(x.reshape(-1)) for x in g], np.float32)
+    gamma[::3] *= np.float32(0.4)
+    hp = B.make_hyper(lr=0.02, weight_decay=0.1, t_start=0)
+    mh = B.make_muon_hyper()
+    ctx = B.AdaGC([r * c for r, c in shapes], B.ADAGC_OPT_MUON, B.ADAGC_GRAD_F32)
+    ctx.muon_attach(shapes)
+    # the largest batch: 20 matrices padded to 256 x 384, each 4 x 256 x 384 + 2 x 256 x 256 bf16 values
+    assert ctx.muon_workspace_bytes() == 20 * (4 * 256 * 384 + 2 * 256 * 256) * 2
+    ctx.close()
+    together = _gpu_muon(shapes, g, m, th, gamma, hp, mh, 4)
+    for i in list(range(8)) + [26, 27, 46]:
+        alone = _gpu_muon([shapes[i]], [g[i]], [m[i]], [th[i]], gamma[i:i + 1], hp, mh, 4)
+        assert np.array_equal(together[0][i].view(np.uint32), alone[0][0].view(np.uint32)), "parameters of tensor %d" % i
+        assert np.array_equal(together[1][i].view(np.uint32), alone[1][0].view(np.uint32)), "momentum of tensor %d" % i
+        assert together[4][i] == alone[4][0]
+    # and against the oracle, as for the single ones
+    for i in (0, 2, 4, 30):
+        th_ref, m_ref = th[i].copy(), m[i].copy()
+        OM.muon_update(th_ref, g[i], m_ref, float(together[4][i]), lr=0.02, weight_decay=0.1, mu=0.95)
+        diff = np.sqrt(np.mean((together[0][i].astype(np.float64) - th_ref) ** 2))
+        assert diff <= 0.02 * OM.update_scale(*shapes[i]) * 0.01 * 0.2
 
 
 def test_muon_trajectory_with_adagc_clipping():

@@ -21,10 +21,11 @@
 //
 // Tiling: 128 x 128 block tile with 4 waves in a 2 x 2 grid (each wave 64 x 64 = 2 x 2 accumulators of
 // v_mfma_f32_32x32x16_bf16, fp32 accumulation); where the launch has enough of them to fill the compute units,
-// 256 x 256 tiles with 8 waves in a 4 x 2 grid (each 64 x 128).  One launch can cover a batch of equal-shaped products.  Operand tiles, 64 deep, go global -> registers -> LDS (rows padded by
-// 16 bytes against bank conflicts), double-buffered in LDS, with the global loads issued two tiles ahead.
-// Workgroups are dealt to the 8 XCDs in turn, so block ids are remapped to give each XCD (one L2 each) a
-// contiguous band of output tiles.
+// 256 x 256 tiles with 8 waves in a 4 x 2 grid (each 64 x 128).  One launch can cover a batch of equal-shaped
+// products.  Operand tiles, 64 deep, are loaded from global memory straight into LDS (global_load_lds_dwordx4, no
+// staging registers), swizzled against bank conflicts, double-buffered; the fragment reads of the next 16-deep
+// slice overlap the current slice's multiplications.  Workgroups are dealt to the 8 XCDs in turn, so block ids are
+// remapped to give each XCD (one L2 each) a contiguous band of output tiles.
 
 #include "adagc_internal.h"
 
@@ -48,7 +49,6 @@ struct GemmBatch {
 #define ADAGC_GEMM_BIG_THREADS 512      // lanes of a 256 x 256 workgroup: 8 waves (512) measured 5-7 % faster than 4 (256)
 #endif
 constexpr int kBK = 64;
-constexpr int kLdsRow = kBK + 8;                       // bf16 elements per LDS row (16 bytes of padding)
 constexpr int kVecPerRow = kBK / 8;                    // 16-byte vectors per tile row
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
@@ -61,156 +61,64 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// BT x BT block tile (128 or 256).  SYM: the result is symmetric (P = Q, D symmetric) and C = Ct is one array: only
-// the tiles on and below the diagonal are computed, each written to its own place and to its mirror image.
-template <int BT, bool SYM, int kGemmThreads>
-__global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
-    const uint16_t* __restrict__ P, int ldp, const uint16_t* __restrict__ Q, int ldq, int M, int N, int K,
-    float alpha, float beta, const uint16_t* __restrict__ Dt, int lddt, uint16_t* __restrict__ C, int ldc,
-    uint16_t* __restrict__ Ct, int ldct, GemmBatch bt)
+// Which output tile a workgroup computes, and the batch's matrix it belongs to.
+struct TilePlace {
+    int tile_m, tile_n, z;
+};
+
+// XCD-aware tile order: block b runs on XCD b mod 8; XCD x gets the x-th contiguous eighth of the tiles of the whole
+// batch (with 8 or more matrices in the batch an XCD then stays on its own matrices).  Within a matrix: SYM walks the
+// lower triangle row by row; otherwise the tiles are walked in panels of kGroupM tile rows, down the rows of a panel
+// first: the workgroups that run at the same time on an XCD then form a patch a few tiles high and wide and share
+// both operands in its L2.
+template <int BT, bool SYM>
+__device__ __forceinline__ TilePlace place_tile(int b, int all_tiles, int M, int N)
 {
-    constexpr int kBM = BT, kBN = BT;
-    constexpr int kWM = kGemmThreads / 128;                // waves in a kWM x 2 grid
-    constexpr int kTM = kBM / kWM, kTN = kBN / 2;          // wave tile
-    constexpr int kMI = kTM / 32, kNI = kTN / 32;          // 32 x 32 accumulators per wave
-    constexpr int kLoadsP = kBM * kVecPerRow / kGemmThreads;   // 16-byte loads per lane per P tile
-    constexpr int kLoadsQ = kBN * kVecPerRow / kGemmThreads;
-    __shared__ __attribute__((aligned(16))) uint16_t lds_p[2][kBM * kLdsRow];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_q[2][kBN * kLdsRow];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;               // wm in [0, kWM)
-
-    // XCD-aware tile order: block b runs on XCD b mod 8; give XCD x the x-th contiguous eighth of the tiles of the
-    // whole batch (with 8 or more matrices in the batch an XCD then stays on its own matrices).
-    const int tiles_n = N / kBN;
-    const int n_tiles = SYM ? tiles_n * (tiles_n + 1) / 2 : (M / kBM) * tiles_n;     // per matrix
-    const int all_tiles = (int)gridDim.x;                                             // n_tiles x matrices
-    int b = blockIdx.x;
+    const int tiles_n = N / BT;
+    const int n_tiles = SYM ? tiles_n * (tiles_n + 1) / 2 : (M / BT) * tiles_n;     // per matrix
     if (all_tiles % 8 == 0) b = (b % 8) * (all_tiles / 8) + b / 8;
-    const int z = b / n_tiles;                             // matrix of the batch
-    b -= z * n_tiles;
-    P += (size_t)z * bt.stride_p;
-    Q += (size_t)z * bt.stride_q;
-    if (Dt) Dt += (size_t)z * bt.stride_dt;
-    if (C) C += (size_t)z * bt.stride_c;
-    if (Ct) Ct += (size_t)z * bt.stride_ct;
-    int tile_m, tile_n;
+    TilePlace t;
+    t.z = b / n_tiles;
+    b -= t.z * n_tiles;
     if constexpr (SYM) {
-        // b-th tile of the lower triangle, row by row: row r starts at r (r + 1) / 2
+        // b-th tile of the lower triangle: row r starts at r (r + 1) / 2
         int r = (int)((sqrtf(8.0f * (float)b + 1.0f) - 1.0f) * 0.5f);
         while (r * (r + 1) / 2 > b) --r;
         while ((r + 1) * (r + 2) / 2 <= b) ++r;
-        tile_m = r;
-        tile_n = b - r * (r + 1) / 2;
+        t.tile_m = r;
+        t.tile_n = b - r * (r + 1) / 2;
     } else {
-        // walk the tiles in panels of kGroupM tile rows, down the rows of a panel first: the workgroups that run at
-        // the same time on an XCD then form a patch a few tiles high and wide and share both operands in its L2
         constexpr int kGroupM = ADAGC_GEMM_GROUP_M;
-        const int tiles_m = M / kBM;
+        const int tiles_m = M / BT;
         const int per_group = kGroupM * tiles_n;
         const int group = b / per_group;
         const int first_m = group * kGroupM;
         const int rows_here = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
         const int in_group = b - group * per_group;
-        tile_m = first_m + in_group % rows_here;
-        tile_n = in_group / rows_here;
+        t.tile_m = first_m + in_group % rows_here;
+        t.tile_n = in_group / rows_here;
     }
-    const uint16_t* Pt = P + (size_t)tile_m * kBM * ldp;
-    const uint16_t* Qt = Q + (size_t)tile_n * kBN * ldq;
+    return t;
+}
 
-    f32x16 acc[kMI][kNI];
-#pragma unroll
-    for (int i = 0; i < kMI; ++i)
-#pragma unroll
-        for (int j = 0; j < kNI; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // Two register sets for operand tiles in flight: the loads of tile k+2 are issued before tile k is multiplied
-    // and are written to LDS one tile later, so a load has two tiles' worth of matrix-core work to arrive.
-    u32x4 stage_p[2][kLoadsP], stage_q[2][kLoadsQ];
-    auto load_tile = [&](int kt, u32x4 (&sp)[kLoadsP], u32x4 (&sq)[kLoadsQ]) {
-#pragma unroll
-        for (int u = 0; u < kLoadsP; ++u) {
-            const int v = u * kGemmThreads + tid;
-            const int row = v / kVecPerRow, kv = v % kVecPerRow;
-            sp[u] = *reinterpret_cast<const u32x4*>(Pt + (size_t)row * ldp + kt * kBK + kv * 8);
-        }
-#pragma unroll
-        for (int u = 0; u < kLoadsQ; ++u) {
-            const int v = u * kGemmThreads + tid;
-            const int row = v / kVecPerRow, kv = v % kVecPerRow;
-            sq[u] = *reinterpret_cast<const u32x4*>(Qt + (size_t)row * ldq + kt * kBK + kv * 8);
-        }
-    };
-    auto store_tile = [&](int buf, const u32x4 (&sp)[kLoadsP], const u32x4 (&sq)[kLoadsQ]) {
-#pragma unroll
-        for (int u = 0; u < kLoadsP; ++u) {
-            const int v = u * kGemmThreads + tid;
-            const int row = v / kVecPerRow, kv = v % kVecPerRow;
-            *reinterpret_cast<u32x4*>(&lds_p[buf][row * kLdsRow + kv * 8]) = sp[u];
-        }
-#pragma unroll
-        for (int u = 0; u < kLoadsQ; ++u) {
-            const int v = u * kGemmThreads + tid;
-            const int row = v / kVecPerRow, kv = v % kVecPerRow;
-            *reinterpret_cast<u32x4*>(&lds_q[buf][row * kLdsRow + kv * 8]) = sq[u];
-        }
-    };
-    // fragment addressing: lane l holds row (l % 32), k offset (l / 32) * 8 of a 32 x 16 operand block
-    const int frag_row = lane & 31;
-    const int frag_k = (lane >> 5) * 8;
-    auto multiply_tile = [&](int buf) {
-#pragma unroll
-        for (int kk = 0; kk < kBK / 16; ++kk) {
-            bf16x8 fa[kMI], fb[kNI];
-#pragma unroll
-            for (int i = 0; i < kMI; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8*>(&lds_p[buf][(wm * kTM + i * 32 + frag_row) * kLdsRow + kk * 16 + frag_k]);
-#pragma unroll
-            for (int j = 0; j < kNI; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8*>(&lds_q[buf][(wn * kTN + j * 32 + frag_row) * kLdsRow + kk * 16 + frag_k]);
-#pragma unroll
-            for (int i = 0; i < kMI; ++i)
-#pragma unroll
-                for (int j = 0; j < kNI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
-    };
-
-    const int k_tiles = K / kBK;          // even: K is a multiple of 128
-    load_tile(0, stage_p[0], stage_q[0]);
-    load_tile(1, stage_p[1], stage_q[1]);
-    store_tile(0, stage_p[0], stage_q[0]);
-    __syncthreads();
-    for (int kt = 0; kt < k_tiles; kt += 2) {
-        // tile kt is in LDS buffer 0, tile kt+1 in register set 1
-        if (kt + 2 < k_tiles) load_tile(kt + 2, stage_p[0], stage_q[0]);
-        multiply_tile(0);
-        store_tile(1, stage_p[1], stage_q[1]);
-        __syncthreads();
-        // tile kt+1 is in LDS buffer 1, tile kt+2 in register set 0
-        if (kt + 3 < k_tiles) load_tile(kt + 3, stage_p[1], stage_q[1]);
-        multiply_tile(1);
-        if (kt + 2 < k_tiles) store_tile(0, stage_p[0], stage_q[0]);
-        __syncthreads();
-    }
-
-    // Epilogue.  Accumulator register r of lane l is element (row (r/4)*8 + (l/32)*4 + r%4, column l%32) of its
-    // 32 x 32 block: four consecutive registers are four consecutive rows of one column.
+// Epilogue of one wave: bf16(alpha acc + beta D) to Ct (8-byte vectors) and C (2-byte stores).  Accumulator register
+// r of lane l is element (row (r/4)*8 + (l/32)*4 + r%4, column l%32) of its 32 x 32 block: four consecutive registers
+// are four consecutive rows of one column.  row_base, col_base: the wave tile's first row and column in the matrix.
+template <int kMI, int kNI, bool SYM>
+__device__ __forceinline__ void store_result(const f32x16 (&acc)[kMI][kNI], int lane, int row_base, int col_base, bool diagonal,
+                                             float alpha, float beta, const uint16_t* __restrict__ Dt, int lddt,
+                                             uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ Ct, int ldct)
+{
     const int col_in = lane & 31;
     const int row_in = (lane >> 5) * 4;
 #pragma unroll
     for (int i = 0; i < kMI; ++i)
 #pragma unroll
         for (int j = 0; j < kNI; ++j) {
-            const int col = tile_n * kBN + wn * kTN + j * 32 + col_in;
+            const int col = col_base + j * 32 + col_in;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int row0 = tile_m * kBM + wm * kTM + i * 32 + q * 8 + row_in;
+                const int row0 = row_base + i * 32 + q * 8 + row_in;
                 float v[4] = {alpha * acc[i][j][q * 4 + 0], alpha * acc[i][j][q * 4 + 1], alpha * acc[i][j][q * 4 + 2],
                               alpha * acc[i][j][q * 4 + 3]};
                 if (Dt) {
@@ -228,7 +136,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
                     o.y = h2 | (h3 << 16);
                     *reinterpret_cast<u32x2v*>(Ct + (size_t)col * ldct + row0) = o;
                 }
-                if (SYM ? (tile_m != tile_n) : (C != nullptr)) {      // SYM: the mirror image, C is the same array as Ct
+                if (SYM ? !diagonal : (C != nullptr)) {      // SYM: the mirror image, C is the same array as Ct
                     C[(size_t)(row0 + 0) * ldc + col] = (uint16_t)h0;
                     C[(size_t)(row0 + 1) * ldc + col] = (uint16_t)h1;
                     C[(size_t)(row0 + 2) * ldc + col] = (uint16_t)h2;
@@ -237,6 +145,155 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
             }
         }
 }
+
+// s_waitcnt for "at most n vector-memory operations of this wave still outstanding", nothing else waited for
+#define ADAGC_WAIT_VMEM(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (0xF << 8))
+// nothing is moved across this point by the compiler's instruction scheduler
+#define ADAGC_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// BT x BT block tile (128 or 256), operand tiles loaded from global memory straight into LDS.
+// One global_load_lds_dwordx4 of a wave writes 1024 contiguous LDS bytes, lane i the i-th 16: that is 8 rows of a
+// 64-deep tile stored without padding.  Bank conflicts of the fragment reads (16 lanes = 16 consecutive rows per
+// clock over 64 banks) are avoided by a swizzle instead: the 16-byte vector v of tile row r sits at position
+// v ^ ((r / 2) mod 8) of its LDS row, which the loading lane applies on the global side.
+template <int BT, bool SYM, int kGemmThreads>
+__global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
+    const uint16_t* __restrict__ P, int ldp, const uint16_t* __restrict__ Q, int ldq, int M, int N, int K,
+    float alpha, float beta, const uint16_t* __restrict__ Dt, int lddt, uint16_t* __restrict__ C, int ldc,
+    uint16_t* __restrict__ Ct, int ldct, GemmBatch bt)
+{
+    constexpr int kWaves = kGemmThreads / 64;
+    constexpr int kWM = kGemmThreads / 128;                // waves in a kWM x 2 grid
+    constexpr int kTM = BT / kWM, kTN = BT / 2;            // wave tile
+    constexpr int kMI = kTM / 32, kNI = kTN / 32;          // 32 x 32 accumulators per wave
+    constexpr int kRowsPerLoad = 64 / kVecPerRow;          // tile rows one wave-wide load covers: 8
+    constexpr int kLoads = BT / kRowsPerLoad / kWaves;     // loads per wave per operand tile
+    static_assert(kWaves % 2 == 0, "the swizzle of a load is taken from the wave's parity");
+    __shared__ __attribute__((aligned(16))) uint16_t lds_p0[BT * kBK], lds_p1[BT * kBK], lds_q0[BT * kBK], lds_q1[BT * kBK];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // the same in all lanes: kept in a scalar register
+    const int wm = wave >> 1, wn = wave & 1;
+
+    const TilePlace tp = place_tile<BT, SYM>((int)blockIdx.x, (int)gridDim.x, M, N);
+    const int tile_m = tp.tile_m, tile_n = tp.tile_n;
+    P += (size_t)tp.z * bt.stride_p;
+    Q += (size_t)tp.z * bt.stride_q;
+    if (Dt) Dt += (size_t)tp.z * bt.stride_dt;
+    if (C) C += (size_t)tp.z * bt.stride_c;
+    if (Ct) Ct += (size_t)tp.z * bt.stride_ct;
+    const uint16_t* Pt = P + (size_t)tile_m * BT * ldp;
+    const uint16_t* Qt = Q + (size_t)tile_n * BT * ldq;
+
+    f32x16 acc[kMI][kNI];
+#pragma unroll
+    for (int i = 0; i < kMI; ++i)
+#pragma unroll
+        for (int j = 0; j < kNI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // Load u of this wave covers tile rows first .. first + 7, first = (u kWaves + wave) 8; lane i writes LDS row
+    // first + i / 8, position i mod 8, so it fetches vector (i mod 8) ^ ((row / 2) mod 8) of that row, and
+    // (row / 2) mod 8 = (4 (wave mod 2) + i / 16) mod 8 because kWaves is even.
+    // The address is split into a part common to the wave (scalar registers) and one 32-bit offset per lane.
+    const int load_row = lane >> 3;
+    const int load_vec = (lane & 7) ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);
+    const uint32_t lane_off_p = (uint32_t)(load_row * ldp + load_vec * 8) * 2u;      // bytes
+    const uint32_t lane_off_q = (uint32_t)(load_row * ldq + load_vec * 8) * 2u;
+    auto load_tile = [&](int kt, uint16_t* bp, uint16_t* bq) {
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            const int first = (u * kWaves + wave) * kRowsPerLoad;
+            const char* row0 = reinterpret_cast<const char*>(Pt + (size_t)first * ldp + kt * kBK);
+            __builtin_amdgcn_global_load_lds(row0 + lane_off_p, bp + first * kBK, 16, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            const int first = (u * kWaves + wave) * kRowsPerLoad;
+            const char* row0 = reinterpret_cast<const char*>(Qt + (size_t)first * ldq + kt * kBK);
+            __builtin_amdgcn_global_load_lds(row0 + lane_off_q, bq + first * kBK, 16, 0, 0);
+        }
+    };
+    // Fragment addressing: lane l holds row l mod 32 of its 32-row block and the 16-byte vector 2 kk + l / 32 of that
+    // row; a block's first row is a multiple of 32, so (row / 2) mod 8 = (l / 2) mod 8.
+    const int frag_row = lane & 31;
+    const int frag_hi = lane >> 5;
+    const int frag_x = (lane >> 1) & 7;
+    auto read_frags = [&](const uint16_t* bp, const uint16_t* bq, int kk, bf16x8 (&fa)[kMI], bf16x8 (&fb)[kNI]) {
+        const int pos = ((kk * 2 + frag_hi) ^ frag_x) * 8;
+#pragma unroll
+        for (int i = 0; i < kMI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(bp + (wm * kTM + i * 32 + frag_row) * kBK + pos);
+#pragma unroll
+        for (int j = 0; j < kNI; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(bq + (wn * kTN + j * 32 + frag_row) * kBK + pos);
+    };
+    auto multiply = [&](const bf16x8 (&fa)[kMI], const bf16x8 (&fb)[kNI]) {
+#pragma unroll
+        for (int i = 0; i < kMI; ++i)
+#pragma unroll
+            for (int j = 0; j < kNI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+
+    // Software pipeline.  A 64-deep tile is four 16-deep slices; the fragments of slice s+1 are read from LDS while
+    // slice s is multiplied (two fragment register sets).  Before the last slice of tile k is multiplied, every wave
+    // has read all of tile k: after the barrier there the tile's buffer is free for the loads of tile k+2, which then
+    // have until the same point of tile k+1 to arrive, and the first slice of tile k+1 is read during the last
+    // multiplications of tile k.
+    bf16x8 fa0[kMI], fb0[kNI], fa1[kMI], fb1[kNI];
+    const int k_tiles = K / kBK;          // even: K is a multiple of 128
+    // slices 0 to 2 of the tile in (cur_p, cur_q); on entry set 0 holds slice 0, on exit set 1 holds slice 3, this
+    // wave's loads have arrived and all waves are past the barrier
+    auto first_three_slices = [&](const uint16_t* cur_p, const uint16_t* cur_q) {
+        read_frags(cur_p, cur_q, 1, fa1, fb1);
+        ADAGC_SCHED_FENCE();
+        multiply(fa0, fb0);
+        ADAGC_SCHED_FENCE();
+        read_frags(cur_p, cur_q, 2, fa0, fb0);
+        ADAGC_SCHED_FENCE();
+        multiply(fa1, fb1);
+        ADAGC_SCHED_FENCE();
+        read_frags(cur_p, cur_q, 3, fa1, fb1);
+        ADAGC_SCHED_FENCE();
+        multiply(fa0, fb0);
+        ADAGC_SCHED_FENCE();
+        ADAGC_WAIT_VMEM(0);
+        __syncthreads();
+    };
+    load_tile(0, lds_p0, lds_q0);
+    ADAGC_WAIT_VMEM(0);
+    __syncthreads();
+    load_tile(1, lds_p1, lds_q1);
+    read_frags(lds_p0, lds_q0, 0, fa0, fb0);
+    ADAGC_SCHED_FENCE();
+    first_three_slices(lds_p0, lds_q0);
+    for (int kt = 0; kt + 2 < k_tiles; kt += 2) {
+        // tile kt (buffer 0): slice 3 left; tile kt+1 is in buffer 1
+        load_tile(kt + 2, lds_p0, lds_q0);
+        read_frags(lds_p1, lds_q1, 0, fa0, fb0);
+        ADAGC_SCHED_FENCE();
+        multiply(fa1, fb1);
+        ADAGC_SCHED_FENCE();
+        first_three_slices(lds_p1, lds_q1);
+        // tile kt+1 (buffer 1): slice 3 left; tile kt+2 is in buffer 0
+        load_tile(kt + 3, lds_p1, lds_q1);
+        read_frags(lds_p0, lds_q0, 0, fa0, fb0);
+        ADAGC_SCHED_FENCE();
+        multiply(fa1, fb1);
+        ADAGC_SCHED_FENCE();
+        first_three_slices(lds_p0, lds_q0);
+    }
+    // the last two tiles: k_tiles - 2 (buffer 0, slice 3 left) and k_tiles - 1 (buffer 1)
+    read_frags(lds_p1, lds_q1, 0, fa0, fb0);
+    ADAGC_SCHED_FENCE();
+    multiply(fa1, fb1);
+    ADAGC_SCHED_FENCE();
+    first_three_slices(lds_p1, lds_q1);
+    multiply(fa1, fb1);
+    store_result<kMI, kNI, SYM>(acc, lane, tile_m * BT + wm * kTM, tile_n * BT + wn * kTN, tile_m == tile_n, alpha, beta, Dt, lddt, C,
+                                ldc, Ct, ldct);
+}
+
 
 }  // namespace
 

@@ -397,7 +397,8 @@ int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* const* grad
  *   C   M x N, ldc, or NULL                 Ct  N x M, ldct: the transpose of the result, or NULL (one of the two)
  *   symmetric = 1: P = Q, M = N and D symmetric, so the result is symmetric; it is written to Ct (C NULL or the same
  *                  array) and only the tiles on and below the diagonal are computed, each stored twice
- * M, N and K must be multiples of 128, every leading dimension of 8.  Errors: INVALID_ARG, TOO_LARGE, HIP.
+ * M, N and K must be multiples of 128, every leading dimension of 8, every pointer 16-byte aligned.
+ * Errors: INVALID_ARG, TOO_LARGE, HIP.
  */
 int adagc_muon_gemm_nt(const void* P, int64_t ldp, const void* Q, int64_t ldq, int64_t M, int64_t N, int64_t K,
                        float alpha, float beta, const void* Dt, int64_t lddt, void* C, int64_t ldc, void* Ct,

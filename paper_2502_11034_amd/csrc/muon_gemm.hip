@@ -101,55 +101,117 @@ __device__ __forceinline__ TilePlace place_tile(int b, int all_tiles, int M, int
     return t;
 }
 
-// Epilogue of one wave: bf16(alpha acc + beta D) to Ct (8-byte vectors) and C (2-byte stores).  Accumulator register
-// r of lane l is element (row (r/4)*8 + (l/32)*4 + r%4, column l%32) of its 32 x 32 block: four consecutive registers
-// are four consecutive rows of one column.  row_base, col_base: the wave tile's first row and column in the matrix.
-template <int kMI, int kNI, bool SYM>
-__device__ __forceinline__ void store_result(const f32x16 (&acc)[kMI][kNI], int lane, int row_base, int col_base, bool diagonal,
-                                             float alpha, float beta, const uint16_t* __restrict__ Dt, int lddt,
-                                             uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ Ct, int ldct)
+// s_waitcnt for "at most n vector-memory operations of this wave still outstanding", nothing else waited for
+#define ADAGC_WAIT_VMEM(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (0xF << 8))
+// nothing is moved across this point by the compiler's instruction scheduler
+#define ADAGC_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Epilogue of a workgroup: bf16(alpha acc + beta D) to Ct and C, staged through LDS so that every global access is a
+// 16-byte vector per lane along a row of the array it touches.  (In the accumulator layout a lane holds 4 consecutive
+// rows of one column and 32 lanes hold 32 columns: stored directly, that is 8 bytes per lane for Ct and D, each in a
+// different cache line, and 2 bytes per lane for C.)
+//
+// The staging tile T holds the BT x BT result transposed, T[c][r] = result(r, c), as Ct and Dt do: row c of T is BT
+// contiguous elements of global row tile_n BT + c of Ct.  Within a row the 16-byte chunks are permuted: chunk g sits
+// at position g ^ f(c), f(c) = (c ^ (c / chunks)) mod chunks, which spreads over the LDS banks both the accumulator-
+// layout accesses (32 lanes = 32 consecutive c, one r) and the reads of the C pass (8 consecutive c at a time).
+//   1. Dt's tile is loaded into T (global_load_lds, the permutation applied on the global side);
+//   2. every lane reads the D values of its accumulator elements from T, and writes the rounded results back to the
+//      same places;
+//   3. T is written out row by row to Ct, and, gathered by columns, row by row to C.
+// Accumulator register r of lane l is element (row (r/4)*8 + (l/32)*4 + r%4, column l%32) of its 32 x 32 block.
+// On entry no wave reads LDS any more (all are past the main loop's last barrier).
+template <int BT, int kMI, int kNI, bool SYM, int kWaves>
+__device__ __forceinline__ void store_result(uint16_t* T, const f32x16 (&acc)[kMI][kNI], int lane, int wave, int wave_row, int wave_col,
+                                             int tile_m, int tile_n, float alpha, float beta, const uint16_t* __restrict__ Dt,
+                                             int lddt, uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ Ct, int ldct)
 {
+    constexpr int kChunks = BT / 8;                         // 16-byte chunks per row of T
+    constexpr int kChunkBits = BT == 256 ? 5 : 4;
+    static_assert((1 << kChunkBits) == kChunks, "BT is 128 or 256");
+    constexpr int kRowsPerInst = 64 / kChunks;              // rows of T one wave-wide 16-byte access covers: 2 or 4
+    constexpr int kInsts = BT / kRowsPerInst / kWaves;      // such accesses per wave for the whole tile
+    auto f = [](int c) { return (c ^ (c >> kChunkBits)) & (kChunks - 1); };
+    const size_t row0_g = (size_t)tile_m * BT, col0_g = (size_t)tile_n * BT;
+
+    // lane i of a row-wise access: row c = first + i / kChunks of T, position i % kChunks, i.e. chunk (i % kChunks) ^ f(c)
+    const int rw_row = lane / kChunks;
+    const int rw_pos = lane % kChunks;
+    if (Dt) {
+#pragma unroll
+        for (int u = 0; u < kInsts; ++u) {
+            const int first = (u * kWaves + wave) * kRowsPerInst;
+            const int c = first + rw_row;
+            const int g = rw_pos ^ f(c);
+            __builtin_amdgcn_global_load_lds(Dt + (col0_g + c) * lddt + row0_g + g * 8, T + first * BT, 16, 0, 0);
+        }
+        ADAGC_WAIT_VMEM(0);
+        __syncthreads();
+    }
     const int col_in = lane & 31;
     const int row_in = (lane >> 5) * 4;
 #pragma unroll
     for (int i = 0; i < kMI; ++i)
 #pragma unroll
         for (int j = 0; j < kNI; ++j) {
-            const int col = col_base + j * 32 + col_in;
+            const int c = wave_col + j * 32 + col_in;
+            const int fc = f(c);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int row0 = row_base + i * 32 + q * 8 + row_in;
+                const int r = wave_row + i * 32 + q * 8 + row_in;
+                u32x2v* slot = reinterpret_cast<u32x2v*>(T + c * BT + (((r >> 3) ^ fc) << 3) + (r & 7));
                 float v[4] = {alpha * acc[i][j][q * 4 + 0], alpha * acc[i][j][q * 4 + 1], alpha * acc[i][j][q * 4 + 2],
                               alpha * acc[i][j][q * 4 + 3]};
                 if (Dt) {
-                    const u32x2v d = *reinterpret_cast<const u32x2v*>(Dt + (size_t)col * lddt + row0);
+                    const u32x2v d = *slot;
                     v[0] = fmaf(beta, bf16_lo(d.x), v[0]);
                     v[1] = fmaf(beta, bf16_hi(d.x), v[1]);
                     v[2] = fmaf(beta, bf16_lo(d.y), v[2]);
                     v[3] = fmaf(beta, bf16_hi(d.y), v[3]);
                 }
-                const uint32_t h0 = f32_to_bf16_rne(v[0]), h1 = f32_to_bf16_rne(v[1]);
-                const uint32_t h2 = f32_to_bf16_rne(v[2]), h3 = f32_to_bf16_rne(v[3]);
-                if (Ct) {
-                    u32x2v o;
-                    o.x = h0 | (h1 << 16);
-                    o.y = h2 | (h3 << 16);
-                    *reinterpret_cast<u32x2v*>(Ct + (size_t)col * ldct + row0) = o;
-                }
-                if (SYM ? !diagonal : (C != nullptr)) {      // SYM: the mirror image, C is the same array as Ct
-                    C[(size_t)(row0 + 0) * ldc + col] = (uint16_t)h0;
-                    C[(size_t)(row0 + 1) * ldc + col] = (uint16_t)h1;
-                    C[(size_t)(row0 + 2) * ldc + col] = (uint16_t)h2;
-                    C[(size_t)(row0 + 3) * ldc + col] = (uint16_t)h3;
-                }
+                u32x2v o;
+                o.x = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
+                o.y = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
+                *slot = o;
             }
         }
+    __syncthreads();
+    if (Ct) {
+#pragma unroll
+        for (int u = 0; u < kInsts; ++u) {
+            const int c = (u * kWaves + wave) * kRowsPerInst + rw_row;
+            const int g = rw_pos ^ f(c);
+            const u32x4 v = *reinterpret_cast<const u32x4*>(T + c * BT + rw_pos * 8);
+            *reinterpret_cast<u32x4*>(Ct + (col0_g + c) * ldct + row0_g + g * 8) = v;
+        }
+    }
+    if (SYM ? (tile_m != tile_n) : (C != nullptr)) {        // SYM: the mirror image, C is the same array as Ct
+        // one access: 8 rows r of the result, 8 chunks (64 columns) of each; lane i takes row i / 8, chunk i % 8
+        constexpr int kColGroups = BT / 64;
+        constexpr int kCInsts = (BT / 8) * kColGroups / kWaves;
+        const int cr = lane >> 3, cc = lane & 7;
+#pragma unroll 4
+        for (int u = 0; u < kCInsts; ++u) {
+            const int n = u * kWaves + wave;
+            const int r = (n / kColGroups) * 8 + cr;
+            const int c0 = (n % kColGroups) * 64 + cc * 8;
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int ca = c0 + 2 * e, cb = ca + 1;
+                const uint32_t lo = T[ca * BT + (((r >> 3) ^ f(ca)) << 3) + (r & 7)];
+                const uint32_t hi = T[cb * BT + (((r >> 3) ^ f(cb)) << 3) + (r & 7)];
+                w[e] = lo | (hi << 16);
+            }
+            u32x4 v;
+            v.x = w[0];
+            v.y = w[1];
+            v.z = w[2];
+            v.w = w[3];
+            *reinterpret_cast<u32x4*>(C + (row0_g + r) * ldc + col0_g + c0) = v;
+        }
+    }
 }
-
-// s_waitcnt for "at most n vector-memory operations of this wave still outstanding", nothing else waited for
-#define ADAGC_WAIT_VMEM(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (0xF << 8))
-// nothing is moved across this point by the compiler's instruction scheduler
-#define ADAGC_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // BT x BT block tile (128 or 256), operand tiles loaded from global memory straight into LDS.
 // One global_load_lds_dwordx4 of a wave writes 1024 contiguous LDS bytes, lane i the i-th 16: that is 8 rows of a
@@ -169,7 +231,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
     constexpr int kRowsPerLoad = 64 / kVecPerRow;          // tile rows one wave-wide load covers: 8
     constexpr int kLoads = BT / kRowsPerLoad / kWaves;     // loads per wave per operand tile
     static_assert(kWaves % 2 == 0, "the swizzle of a load is taken from the wave's parity");
-    __shared__ __attribute__((aligned(16))) uint16_t lds_p0[BT * kBK], lds_p1[BT * kBK], lds_q0[BT * kBK], lds_q1[BT * kBK];
+    // two buffers of a P and a Q tile each; the epilogue reuses all of it as one BT x BT staging tile (or half of it)
+    __shared__ __attribute__((aligned(16))) uint16_t lds[4 * BT * kBK];
+    uint16_t* const lds_p0 = lds;
+    uint16_t* const lds_q0 = lds + BT * kBK;
+    uint16_t* const lds_p1 = lds + 2 * BT * kBK;
+    uint16_t* const lds_q1 = lds + 3 * BT * kBK;
+    static_assert(4 * BT * kBK >= BT * BT, "the staging tile of the epilogue must fit");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -290,8 +358,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
     ADAGC_SCHED_FENCE();
     first_three_slices(lds_p1, lds_q1);
     multiply(fa1, fb1);
-    store_result<kMI, kNI, SYM>(acc, lane, tile_m * BT + wm * kTM, tile_n * BT + wn * kTN, tile_m == tile_n, alpha, beta, Dt, lddt, C,
-                                ldc, Ct, ldct);
+    store_result<BT, kMI, kNI, SYM, kWaves>(lds, acc, lane, wave, wm * kTM, wn * kTN, tile_m, tile_n, alpha, beta, Dt, lddt, C, ldc, Ct,
+                                            ldct);
 }
 
 
@@ -314,6 +382,8 @@ hipError_t launch_gemm_nt_bf16(const void* P, int ldp, const void* Q, int ldq, i
     if ((stride_p | stride_q | stride_dt | stride_c | stride_ct) % 8 || stride_p < 0 || stride_q < 0 || stride_dt < 0 ||
         stride_c < 0 || stride_ct < 0)
         return hipErrorInvalidValue;
+    auto misaligned = [](const void* a) { return (reinterpret_cast<uintptr_t>(a) & 15u) != 0; };      // 16-byte vector accesses
+    if (misaligned(P) || misaligned(Q) || misaligned(Dt) || misaligned(C) || misaligned(Ct)) return hipErrorInvalidValue;
     if (symmetric && (M != N || P != Q || stride_p != stride_q || !Ct || (C && (C != Ct || stride_c != stride_ct))))
         return hipErrorInvalidValue;
     const uint16_t *p = static_cast<const uint16_t*>(P), *q = static_cast<const uint16_t*>(Q), *dt = static_cast<const uint16_t*>(Dt);

@@ -156,6 +156,12 @@ def test_matrix_core_product_rejects_shapes_it_does_not_tile():
         assert e.value.code == B.ADAGC_ERR_INVALID_ARG
     with pytest.raises(B.AdagcError):
         B.adagc_muon_gemm_nt(z, z, 1.0, 0.0, None, None, None)
+    # every access is a 16-byte vector: an operand that starts 8 bytes into an allocation is refused
+    shifted = torch.zeros(128 * 128 + 8, dtype=torch.bfloat16, device=DEV)[4:4 + 128 * 128].view(128, 128)
+    for args in [(shifted, z, None, out), (z, z, shifted, out), (z, z, None, shifted)]:
+        with pytest.raises(B.AdagcError) as e:
+            B.adagc_muon_gemm_nt(args[0], args[1], 1.0, 0.0, args[2], args[3], None)
+        assert e.value.code == B.ADAGC_ERR_INVALID_ARG
 
 
 # --------------------------------------------------------------------------- the Muon step

@@ -106,6 +106,18 @@ __device__ __forceinline__ TilePlace place_tile(int b, int all_tiles, int M, int
 // nothing is moved across this point by the compiler's instruction scheduler
 #define ADAGC_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// 16 bytes per lane from global memory straight into LDS: lane i's data lands at lds_dst + 16 i (lds_dst: the same in
+// all lanes).  The instruction takes the LDS byte address from M0, and wants one wait state after M0 is written.
+// Written as inline assembly rather than through the compiler's builtin so that the compiler does not track these
+// loads: it would count each as outstanding in both of its memory counters ("flat" access) and, while one is, turn
+// every wait for an LDS read into a wait for all LDS reads, which serialises the fragment reads with the
+// multiplications.  The waits for these loads are explicit (ADAGC_WAIT_VMEM) wherever their data is needed.
+__device__ __forceinline__ void load_to_lds_16(const void* src, const uint16_t* lds_dst)
+{
+    const uint32_t lds_addr = (uint32_t)reinterpret_cast<uintptr_t>(lds_dst);      // low half of the flat address = LDS offset
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory", "m0");
+}
+
 // Epilogue of a workgroup: bf16(alpha acc + beta D) to Ct and C, staged through LDS so that every global access is a
 // 16-byte vector per lane along a row of the array it touches.  (In the accumulator layout a lane holds 4 consecutive
 // rows of one column and 32 lanes hold 32 columns: stored directly, that is 8 bytes per lane for Ct and D, each in a
@@ -143,7 +155,7 @@ __device__ __forceinline__ void store_result(uint16_t* T, const f32x16 (&acc)[kM
             const int first = (u * kWaves + wave) * kRowsPerInst;
             const int c = first + rw_row;
             const int g = rw_pos ^ f(c);
-            __builtin_amdgcn_global_load_lds(Dt + (col0_g + c) * lddt + row0_g + g * 8, T + first * BT, 16, 0, 0);
+            load_to_lds_16(Dt + (col0_g + c) * lddt + row0_g + g * 8, T + first * BT);
         }
         ADAGC_WAIT_VMEM(0);
         __syncthreads();
@@ -275,13 +287,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_bf16_kernel(
         for (int u = 0; u < kLoads; ++u) {
             const int first = (u * kWaves + wave) * kRowsPerLoad;
             const char* row0 = reinterpret_cast<const char*>(Pt + (size_t)first * ldp + kt * kBK);
-            __builtin_amdgcn_global_load_lds(row0 + lane_off_p, bp + first * kBK, 16, 0, 0);
+            load_to_lds_16(row0 + lane_off_p, bp + first * kBK);
         }
 #pragma unroll
         for (int u = 0; u < kLoads; ++u) {
             const int first = (u * kWaves + wave) * kRowsPerLoad;
             const char* row0 = reinterpret_cast<const char*>(Qt + (size_t)first * ldq + kt * kBK);
-            __builtin_amdgcn_global_load_lds(row0 + lane_off_q, bq + first * kBK, 16, 0, 0);
+            load_to_lds_16(row0 + lane_off_q, bq + first * kBK);
         }
     };
     // Fragment addressing: lane l holds row l mod 32 of its 32-row block and the 16-byte vector 2 kk + l / 32 of that

@@ -18,6 +18,7 @@ namespace adagc {
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
 {
@@ -50,12 +51,15 @@ __device__ __forceinline__ double wave_sum(double x)
 }
 
 // One workgroup per chunk (positions b, b+grid, ... of the list): momentum update and the chunk's sum of U^2.
+// Tensors whose pointers allow it are walked in 128-bit vectors (4 elements per lane and access, streaming loads
+// and stores: every element is touched once per kernel); the others, and the last len mod 4 elements, one by one.
 template <bool BF16>
 __global__ __launch_bounds__(kBlock) void muon_momentum_kernel(DeviceTables t, double mu, int nesterov)
 {
     __shared__ double wave_sums[kWavesPerBlock];
     const int tid = threadIdx.x;
-    for (uint32_t c = blockIdx.x; c < t.n_chunks; c += gridDim.x) {
+    for (uint32_t k = blockIdx.x; k < t.n_chunks; k += gridDim.x) {
+        const uint32_t c = t.schedule ? t.schedule[k] : k;     // the visiting order of the norm kernel (XCD-aware)
         const ChunkRef ck = t.chunks[c];
         const TensorArgs& ta = t.targs[ck.tensor];
         const int64_t first = (int64_t)ck.index * kChunkElems;
@@ -64,7 +68,57 @@ __global__ __launch_bounds__(kBlock) void muon_momentum_kernel(DeviceTables t, d
         const double h = t.coef64[ck.tensor];
         float* m = reinterpret_cast<float*>(ta.exp_avg) + first;
         double acc = 0.0;
-        for (int j = tid; j < len; j += kBlock) {
+        int done = 0;
+        if (ta.vec_ok) {
+            const int groups = len / 4;
+            f32x4* m4 = reinterpret_cast<f32x4*>(m);
+            auto load_g = [&](int j, float (&g)[4]) {
+                if constexpr (BF16) {
+                    const u32x2 w = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(ta.grad) + first) + j);
+                    g[0] = __uint_as_float(w.x << 16);
+                    g[1] = __uint_as_float(w.x & 0xFFFF0000u);
+                    g[2] = __uint_as_float(w.y << 16);
+                    g[3] = __uint_as_float(w.y & 0xFFFF0000u);
+                } else {
+                    const f32x4 w = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(ta.grad) + first) + j);
+                    g[0] = w.x; g[1] = w.y; g[2] = w.z; g[3] = w.w;
+                }
+            };
+            auto update4 = [&](int j, const float (&g)[4], const f32x4 mp) {
+                f32x4 mn;
+                float e;
+                double u = momentum_elem(h, mu, nesterov, g[0], mp.x, &e); mn.x = e; acc = fma(u, u, acc);
+                u = momentum_elem(h, mu, nesterov, g[1], mp.y, &e); mn.y = e; acc = fma(u, u, acc);
+                u = momentum_elem(h, mu, nesterov, g[2], mp.z, &e); mn.z = e; acc = fma(u, u, acc);
+                u = momentum_elem(h, mu, nesterov, g[3], mp.w, &e); mn.w = e; acc = fma(u, u, acc);
+                __builtin_nontemporal_store(mn, m4 + j);
+            };
+            if (len == kChunkElems) {
+                // a full chunk is 16 vectors per lane: 8 of each array in flight at a time
+                constexpr int kPerLane = kChunkElems / 4 / kBlock, kFlight = 8;
+                static_assert(kPerLane % kFlight == 0, "chunk size and block size");
+#pragma unroll
+                for (int base = 0; base < kPerLane; base += kFlight) {
+                    float g[kFlight][4];
+                    f32x4 mp[kFlight];
+#pragma unroll
+                    for (int v = 0; v < kFlight; ++v) {
+                        load_g((base + v) * kBlock + tid, g[v]);
+                        mp[v] = __builtin_nontemporal_load(m4 + (base + v) * kBlock + tid);
+                    }
+#pragma unroll
+                    for (int v = 0; v < kFlight; ++v) update4((base + v) * kBlock + tid, g[v], mp[v]);
+                }
+            } else {
+                for (int j = tid; j < groups; j += kBlock) {
+                    float g[4];
+                    load_g(j, g);
+                    update4(j, g, __builtin_nontemporal_load(m4 + j));
+                }
+            }
+            done = groups * 4;
+        }
+        for (int j = done + tid; j < len; j += kBlock) {
             float m_new;
             const double u = momentum_elem(h, mu, nesterov, grad_at<BF16>(ta.grad, first + j), m[j], &m_new);
             m[j] = m_new;
@@ -120,18 +174,43 @@ __global__ __launch_bounds__(256) void muon_normalise_kernel(const void* g, cons
 }
 
 // theta <- theta - lr (wd theta + scale O) on one matrix; O is bf16 with leading dimension ld_o.
-template <bool COPY>
+// VEC: cols is a multiple of 4 and theta (and the copy) are 16-byte (8-byte) aligned: 4 elements per lane and access.
+template <bool COPY, bool VEC>
 __global__ __launch_bounds__(256) void muon_apply_kernel(float* theta, const uint16_t* o, int64_t ld_o, int64_t rows, int64_t cols,
                                                           double lr, double wd, double scale, uint16_t* copy)
 {
     const int64_t r = blockIdx.x;
-    for (int64_t c = (int64_t)blockIdx.y * 256 + threadIdx.x; c < cols; c += (int64_t)gridDim.y * 256) {
-        const int64_t j = r * cols + c;
-        const double th = (double)theta[j];
-        const double ov = (double)__uint_as_float((uint32_t)o[r * ld_o + c] << 16);
-        const float out = (float)(th - lr * (wd * th + scale * ov));
-        theta[j] = out;
-        if constexpr (COPY) copy[j] = (uint16_t)f32_to_bf16_bits(out);
+    auto one = [&](float th_f, uint32_t o_bits) {
+        const double th = (double)th_f;
+        const double ov = (double)__uint_as_float(o_bits << 16);
+        return (float)(th - lr * (wd * th + scale * ov));
+    };
+    if constexpr (VEC) {
+        const int64_t groups = cols / 4;
+        for (int64_t q = (int64_t)blockIdx.y * 256 + threadIdx.x; q < groups; q += (int64_t)gridDim.y * 256) {
+            const int64_t j = r * cols + q * 4;
+            const f32x4 th = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(theta + j));
+            const u32x2 ow = *reinterpret_cast<const u32x2*>(o + r * ld_o + q * 4);
+            f32x4 out;
+            out.x = one(th.x, ow.x & 0xFFFFu);
+            out.y = one(th.y, ow.x >> 16);
+            out.z = one(th.z, ow.y & 0xFFFFu);
+            out.w = one(th.w, ow.y >> 16);
+            __builtin_nontemporal_store(out, reinterpret_cast<f32x4*>(theta + j));
+            if constexpr (COPY) {
+                u32x2 cw;
+                cw.x = f32_to_bf16_bits(out.x) | (f32_to_bf16_bits(out.y) << 16);
+                cw.y = f32_to_bf16_bits(out.z) | (f32_to_bf16_bits(out.w) << 16);
+                __builtin_nontemporal_store(cw, reinterpret_cast<u32x2*>(copy + j));
+            }
+        }
+    } else {
+        for (int64_t c = (int64_t)blockIdx.y * 256 + threadIdx.x; c < cols; c += (int64_t)gridDim.y * 256) {
+            const int64_t j = r * cols + c;
+            const float out = one(theta[j], o[r * ld_o + c]);
+            theta[j] = out;
+            if constexpr (COPY) copy[j] = (uint16_t)f32_to_bf16_bits(out);
+        }
     }
 }
 
@@ -164,15 +243,19 @@ hipError_t launch_muon_normalise(const void* g, const void* m, int64_t rows, int
 hipError_t launch_muon_apply(void* theta, const void* o, int64_t ld_o, int64_t rows, int64_t cols, double lr, double wd,
                              double scale, void* copy, hipStream_t stream)
 {
-    int64_t col_blocks = (cols + 255) / 256;
+    auto misaligned = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
+    const bool vec = cols % 4 == 0 && !misaligned(theta, 16) && !misaligned(o, 8) && ld_o % 4 == 0 && !(copy && misaligned(copy, 8));
+    const int64_t per_row = vec ? cols / 4 : cols;
+    int64_t col_blocks = (per_row + 255) / 256;
     if (col_blocks > 64) col_blocks = 64;
     const dim3 grid((uint32_t)rows, (uint32_t)col_blocks);
-    if (copy)
-        muon_apply_kernel<true><<<grid, dim3(256), 0, stream>>>(static_cast<float*>(theta), static_cast<const uint16_t*>(o), ld_o, rows,
-                                                                cols, lr, wd, scale, static_cast<uint16_t*>(copy));
-    else
-        muon_apply_kernel<false><<<grid, dim3(256), 0, stream>>>(static_cast<float*>(theta), static_cast<const uint16_t*>(o), ld_o, rows,
-                                                                 cols, lr, wd, scale, nullptr);
+    float* th = static_cast<float*>(theta);
+    const uint16_t* ob = static_cast<const uint16_t*>(o);
+    uint16_t* cp = static_cast<uint16_t*>(copy);
+    if (copy && vec) muon_apply_kernel<true, true><<<grid, dim3(256), 0, stream>>>(th, ob, ld_o, rows, cols, lr, wd, scale, cp);
+    else if (copy) muon_apply_kernel<true, false><<<grid, dim3(256), 0, stream>>>(th, ob, ld_o, rows, cols, lr, wd, scale, cp);
+    else if (vec) muon_apply_kernel<false, true><<<grid, dim3(256), 0, stream>>>(th, ob, ld_o, rows, cols, lr, wd, scale, nullptr);
+    else muon_apply_kernel<false, false><<<grid, dim3(256), 0, stream>>>(th, ob, ld_o, rows, cols, lr, wd, scale, nullptr);
     return hipGetLastError();
 }
 

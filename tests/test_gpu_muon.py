@@ -430,9 +430,10 @@ def _sampled_rows_check(name, P, Q, alpha, beta, D, got, rows):
 
 
 def test_newton_schulz_products_at_llama3_8b_ffn_shape():
-    """One step's three products at the size of a 4096 x 14336 weight, in the tile configuration the step uses there
-    (symmetric products on 128 x 128 tiles, the last product on 256 x 256): each checked on sampled rows that the
-    oracle computes one by one from the GPU's own operands, and the symmetric ones for exact symmetry."""
+    """One step's three products at the size of a 4096 x 14336 weight, on the 256 x 256 tiles the step uses there (the
+    step runs them batched over equal-shaped matrices; a batched product equals the single one bit for bit, which
+    test_batched_matrix_core_product_equals_the_single_ones checks): each checked on sampled rows that the oracle
+    computes one by one from the GPU's own operands, and the symmetric ones for exact symmetry."""
     m, n = 4096, 14336
     gen = torch.Generator(device=DEV).manual_seed(9)
     x = (torch.randn(m, n, device=DEV, generator=gen) * (1.0 / np.sqrt(m * n)) * 3.0).to(torch.bfloat16)      # like a normalised U

@@ -475,3 +475,39 @@ def test_muon_step_at_llama3_8b_attention_shapes():
         if s[0] < s[1]:
             sv, sv_ref = np.linalg.svd(O[i], compute_uv=False), np.linalg.svd(o_ref, compute_uv=False)
             assert np.abs(sv - sv_ref).max() <= 0.01 and 0.6 < sv.min() and sv.max() < 1.25
+
+
+def test_muon_batch_of_32_at_llama3_8b_attention_shape():
+    """The launch configuration the benchmark times for the attention matrices: 32 matrices of 4096 x 4096 iterated in one
+    batch (symmetric products 32 x 136 tiles of 256 x 256).  The first and the last matrix of the batch must be, bit
+    for bit, what a context holding one matrix produces, and the last one is compared with the oracle's five steps."""
+    shape, count = (4096, 4096), 32
+    gen = torch.Generator(device=DEV).manual_seed(33)
+    sig = torch.exp(torch.empty(count, device=DEV).uniform_(-6.0, -2.0, generator=gen))
+    g = [torch.randn(shape[0] * shape[1], device=DEV, generator=gen) * sig[i] for i in range(count)]
+    m = [torch.randn(shape[0] * shape[1], device=DEV, generator=gen) * sig[i] * 0.5 for i in range(count)]
+    th = [torch.zeros(shape[0] * shape[1], device=DEV) for _ in range(count)]
+    hp = B.make_hyper(lr=1.0, weight_decay=0.0, t_start=0)
+    mh = B.make_muon_hyper()
+    m_before = {i: to_numpy(m[i]).reshape(shape) for i in (0, count - 1)}
+    g_host = {i: to_numpy(g[i]).reshape(shape) for i in (0, count - 1)}
+    ctx = B.AdaGC([shape[0] * shape[1]] * count, B.ADAGC_OPT_MUON, B.ADAGC_GRAD_F32)
+    ctx.muon_attach([shape] * count)
+    assert ctx.muon_workspace_bytes() == count * 6 * 4096 * 4096 * 2
+    gamma = torch.full((count,), 1e9, dtype=torch.float32, device=DEV)
+    ctx.muon_step(th, g, m, gamma, hp, mh, 3)
+    torch.cuda.synchronize()
+    ctx.close()
+    for i in (0, count - 1):
+        alone = _gpu_muon([shape], [g_host[i]], [m_before[i]], [np.zeros(shape, np.float32)], np.full(1, 1e9, np.float32), hp, mh, 3)
+        assert np.array_equal(to_numpy(th[i]).reshape(shape).view(np.uint32), alone[0][0].view(np.uint32)), "matrix %d of the batch" % i
+        assert np.array_equal(to_numpy(m[i]).reshape(shape).view(np.uint32), alone[1][0].view(np.uint32))
+    i = count - 1
+    O = OM.to_bf16(-(to_numpy(th[i]).reshape(shape).astype(np.float64)))
+    th_ref, m_ref = np.zeros(shape, np.float32), m_before[i].copy()
+    o_ref = OM.muon_update(th_ref, g_host[i], m_ref, 1.0, lr=1.0, weight_decay=0.0, mu=0.95)
+    rms = np.sqrt(np.mean(o_ref ** 2))
+    diff = np.sqrt(np.mean((O - o_ref) ** 2))
+    say("matrix %d of a batch of %d at %s: rms difference %.2e of rms %.2e, %.1f %% of the values identical"
+        % (i, count, shape, diff, rms, 100 * float((O == o_ref).mean())))
+    assert diff <= 0.01 * rms

@@ -7,7 +7,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadagc.so")
 SOURCES = ["api.cpp", "segment_table.cpp", "kernels.hip", "static_step.hip", "muon_gemm.hip", "muon.hip"]
-HEADERS = [os.path.join(ROOT, "include", "adagc.h"), os.path.join(CSRC, "adagc_internal.h")]
+HEADERS = [os.path.join(ROOT, "include", "adagc.h"), os.path.join(CSRC, "adagc_internal.h"), os.path.join(CSRC, "muon_internal.h")]
 
 
 def hipcc():

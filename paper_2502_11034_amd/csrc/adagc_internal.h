@@ -159,22 +159,8 @@ hipError_t launch_update(const DeviceTables& t, const UpdateArgs& u, int optimiz
 // per tensor turns them into the tensor's update coefficient.
 hipError_t launch_update_clip_rule(const DeviceTables& t, const UpdateArgs& u, const RuleArgs& r, int optimizer,
                                    int grad_bf16, int items_per_chunk, int nt, int grid, hipStream_t stream);
-// bf16 matrix-core GEMM of the Newton-Schulz iteration (muon_gemm.hip): C = bf16(alpha P Q^T + beta D), D given
-// through its transpose Dt, result written row-major (C), transposed (Ct) or both; batch products of one shape per
-// launch, matrix z of each array at base + z * stride elements.
-hipError_t launch_gemm_nt_bf16(const void* P, int ldp, const void* Q, int ldq, int M, int N, int K, float alpha,
-                               float beta, const void* Dt, int lddt, void* C, int ldc, void* Ct, int ldct,
-                               hipStream_t stream, bool symmetric = false, int batch = 1, int64_t stride_p = 0,
-                               int64_t stride_q = 0, int64_t stride_dt = 0, int64_t stride_c = 0, int64_t stride_ct = 0);
-// Muon (muon.hip): per-tensor sums of the per-chunk partials into t.sumsq; momentum update with the clipped
-// gradient and the partial sums of squares of U; X0 of one matrix into the padded workspace; the parameter update.
+// Per-tensor sums of the per-chunk partials into t.sumsq (K2's fixed order); used by the Muon path for ||U||^2.
 hipError_t launch_tensor_sumsq(const DeviceTables& t, hipStream_t stream);
-hipError_t launch_muon_momentum(const DeviceTables& t, double mu, int nesterov, int grad_bf16, int grid, hipStream_t stream);
-hipError_t launch_muon_normalise(const void* g, const void* m, int64_t rows, int64_t cols, int64_t rows_p, int64_t cols_p,
-                                 const double* coef, const double* sumsq, double mu, int nesterov, int grad_bf16,
-                                 void* same, int64_t ld_same, void* trans, int64_t ld_trans, hipStream_t stream);
-hipError_t launch_muon_apply(void* theta, const void* o, int64_t ld_o, int64_t rows, int64_t cols, double lr, double wd,
-                             double scale, void* copy, hipStream_t stream);
 // Rule stage of adagc_step_graph: scalars from device-resident step parameters, then the per-tensor
 // sums, the model-wide rule (a no-op outside warm-up and the global modes) and the per-tensor rule.
 hipError_t launch_rules_from_device(const DeviceTables& t, float* ema, const adagc_step_params* params,

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "adagc_internal.h"
+#include "muon_internal.h"
 
 using namespace adagc;
 

@@ -12,7 +12,7 @@
 // (kernels.hip); the Newton-Schulz products run in muon_gemm.hip.  Arithmetic is double with one rounding per
 // stored value, as in the other update kernels; reductions are in fixed order.
 
-#include "adagc_internal.h"
+#include "muon_internal.h"
 
 namespace adagc {
 namespace {

@@ -27,7 +27,7 @@
 // slice overlap the current slice's multiplications.  Workgroups are dealt to the 8 XCDs in turn, so block ids are
 // remapped to give each XCD (one L2 each) a contiguous band of output tiles.
 
-#include "adagc_internal.h"
+#include "muon_internal.h"
 
 namespace adagc {
 namespace {

@@ -51,5 +51,20 @@ def build(force=True, verbose=False, extra_flags=(), out=None):
     return out
 
 
+def build_probe():
+    """libadagc_probe.so: the memory-system probe (csrc/memory_probe.hip), a measurement tool outside the library."""
+    out = os.path.join(HERE, "libadagc_probe.so")
+    tmp = out + ".tmp.%d" % os.getpid()
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wextra", "-x", "hip",
+           os.path.join(CSRC, "memory_probe.hip"), "-o", tmp]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr)
+    os.replace(tmp, out)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
+    print(build_probe())

@@ -107,7 +107,8 @@ __device__ __forceinline__ TilePlace place_tile(int b, int all_tiles, int M, int
 #define ADAGC_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // 16 bytes per lane from global memory straight into LDS: lane i's data lands at lds_dst + 16 i (lds_dst: the same in
-// all lanes).  The instruction takes the LDS byte address from M0, and wants one wait state after M0 is written.
+// all lanes).  The instruction takes the LDS byte address from M0, and wants one wait state after M0 is written; M0 is
+// put back afterwards, so the compiler's own uses of it are not disturbed.
 // Written as inline assembly rather than through the compiler's builtin so that the compiler does not track these
 // loads: it would count each as outstanding in both of its memory counters ("flat" access) and, while one is, turn
 // every wait for an LDS read into a wait for all LDS reads, which serialises the fragment reads with the
@@ -115,7 +116,11 @@ __device__ __forceinline__ TilePlace place_tile(int b, int all_tiles, int M, int
 __device__ __forceinline__ void load_to_lds_16(const void* src, const uint16_t* lds_dst)
 {
     const uint32_t lds_addr = (uint32_t)reinterpret_cast<uintptr_t>(lds_dst);      // low half of the flat address = LDS offset
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory", "m0");
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "s"(lds_addr), "v"(src)
+                 : "memory");
 }
 
 // Epilogue of a workgroup: bf16(alpha acc + beta D) to Ct and C, staged through LDS so that every global access is a

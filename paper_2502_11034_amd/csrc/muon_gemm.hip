@@ -10,11 +10,10 @@
 //   B  = b A + c A A          P = Q = A (A is symmetric)      (alpha c, beta b, D = A)
 //   X' = a X + B X            P = B, Q = Y = X^T              (alpha 1, beta a, D = X)
 // The result is written row-major (C), transposed (Ct, N x M), or both; D is read through its transpose
-// Dt (N x M): in the accumulator layout a lane holds 4 consecutive rows of one column, which are 4
-// consecutive elements of a transposed array, so those accesses are 8-byte vectors.
+// Dt (N x M).  The epilogue goes through LDS, so that all of these are 16-byte accesses along rows (store_result).
 //
 // A = X X^T and A A are symmetric: for those only the tiles on and below the diagonal are computed and each is
-// written twice, to its place and to its mirror image, which saves a third of a step's multiplications.
+// written twice, to its place and to its mirror image, which saves about a quarter of a step's multiplications.
 //
 // M and N are multiples of the 128 x 128 block tile and K of 128 (two 64-deep tiles): the caller (muon.hip) keeps every matrix
 // in zero-padded workspace buffers, and zero rows and columns stay zero through the iteration.
@@ -46,7 +45,7 @@ struct GemmBatch {
 #define ADAGC_GEMM_GROUP_M 8
 #endif
 #ifndef ADAGC_GEMM_BIG_THREADS
-#define ADAGC_GEMM_BIG_THREADS 512      // lanes of a 256 x 256 workgroup: 8 waves (512) measured 5-7 % faster than 4 (256)
+#define ADAGC_GEMM_BIG_THREADS 512      // lanes of a 256 x 256 workgroup: 8 waves; 4 waves (256) measured no better overall
 #endif
 constexpr int kBK = 64;
 constexpr int kVecPerRow = kBK / 8;                    // 16-byte vectors per tile row

@@ -141,35 +141,82 @@ __global__ __launch_bounds__(kBlock) void muon_momentum_kernel(DeviceTables t, d
 // tiles of its extent padded to (rows_p, cols_p); every element of the padded extent is written: zeros outside
 // the matrix.  same[r][c] (leading dimension ld_same) receives the tile as is, trans[c][r] (ld_trans) its
 // transpose, through LDS so that both are written along their rows.
-template <bool BF16>
+// VEC (cols a multiple of 4, g and m 16-byte aligned; bf16 g 8-byte): a lane handles 4 consecutive elements of a
+// row on the way in and 4 consecutive elements of a transposed row on the way out: 16-byte loads, 8-byte stores.
+template <bool BF16, bool VEC>
 __global__ __launch_bounds__(256) void muon_normalise_kernel(const void* g, const float* m, int64_t rows, int64_t cols,
                                                               int64_t rows_p, int64_t cols_p, const double* coef,
                                                               const double* sumsq, double mu, int nesterov,
                                                               uint16_t* same, int64_t ld_same, uint16_t* trans, int64_t ld_trans)
 {
-    __shared__ uint16_t tile[64][66];
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    constexpr int kTileLd = VEC ? 68 : 66;                 // u16 per LDS row (VEC: rows stay 8-byte aligned)
+    __shared__ __attribute__((aligned(8))) uint16_t tile[64 * kTileLd];
     const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
     const double h = *coef;
     const double denom = sqrt(*sumsq) + 1e-7;
-#pragma unroll 4
-    for (int k = 0; k < 16; ++k) {
-        const int64_t r = r0 + ty + 4 * k, c = c0 + tx;
-        uint16_t bits = 0;
-        if (r < rows && c < cols) {
-            const int64_t j = r * cols + c;
-            const double gh = h * (double)grad_at<BF16>(g, j);
-            const double u = nesterov ? gh + mu * (double)m[j] : (double)m[j];     // m already holds this step's momentum
-            bits = (uint16_t)f32_to_bf16_bits((float)(u / denom));
+    auto x0_bits = [&](float gv, float mv) {
+        const double gh = h * (double)gv;
+        const double u = nesterov ? gh + mu * (double)mv : (double)mv;         // m already holds this step's momentum
+        return f32_to_bf16_bits((float)(u / denom));
+    };
+    if constexpr (VEC) {
+        const int q = (threadIdx.x & 15) * 4, p = threadIdx.x >> 4;            // 16 lanes per row, 16 rows per pass
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int tr = p + 16 * k;
+            const int64_t r = r0 + tr, c = c0 + q;
+            u32x2 bits = {0u, 0u};
+            if (r < rows && c < cols) {
+                const int64_t j = r * cols + c;
+                float gv[4];
+                if constexpr (BF16) {
+                    const u32x2 w = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(g) + j);
+                    gv[0] = __uint_as_float(w.x << 16);
+                    gv[1] = __uint_as_float(w.x & 0xFFFF0000u);
+                    gv[2] = __uint_as_float(w.y << 16);
+                    gv[3] = __uint_as_float(w.y & 0xFFFF0000u);
+                } else {
+                    const f32x4 w = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(g) + j);
+                    gv[0] = w.x; gv[1] = w.y; gv[2] = w.z; gv[3] = w.w;
+                }
+                const f32x4 mv = *reinterpret_cast<const f32x4*>(m + j);
+                bits.x = x0_bits(gv[0], mv.x) | (x0_bits(gv[1], mv.y) << 16);
+                bits.y = x0_bits(gv[2], mv.z) | (x0_bits(gv[3], mv.w) << 16);
+            }
+            *reinterpret_cast<u32x2*>(&tile[tr * kTileLd + q]) = bits;
+            if (r < rows_p && c < cols_p) *reinterpret_cast<u32x2*>(same + r * ld_same + c) = bits;
         }
-        tile[ty + 4 * k][tx] = bits;
-        if (r < rows_p && c < cols_p) same[r * ld_same + c] = bits;
-    }
-    __syncthreads();
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int tc = p + 16 * k;                                         // column of the tile = row of the transpose
+            const int64_t c = c0 + tc, r = r0 + q;
+            if (r < rows_p && c < cols_p) {
+                u32x2 bits;
+                bits.x = (uint32_t)tile[(q + 0) * kTileLd + tc] | ((uint32_t)tile[(q + 1) * kTileLd + tc] << 16);
+                bits.y = (uint32_t)tile[(q + 2) * kTileLd + tc] | ((uint32_t)tile[(q + 3) * kTileLd + tc] << 16);
+                *reinterpret_cast<u32x2*>(trans + c * ld_trans + r) = bits;
+            }
+        }
+    } else {
+        const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
 #pragma unroll 4
-    for (int k = 0; k < 16; ++k) {
-        const int64_t c = c0 + ty + 4 * k, r = r0 + tx;
-        if (r < rows_p && c < cols_p) trans[c * ld_trans + r] = tile[tx][ty + 4 * k];
+        for (int k = 0; k < 16; ++k) {
+            const int64_t r = r0 + ty + 4 * k, c = c0 + tx;
+            uint16_t bits = 0;
+            if (r < rows && c < cols) {
+                const int64_t j = r * cols + c;
+                bits = (uint16_t)x0_bits(grad_at<BF16>(g, j), m[j]);
+            }
+            tile[(ty + 4 * k) * kTileLd + tx] = bits;
+            if (r < rows_p && c < cols_p) same[r * ld_same + c] = bits;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int k = 0; k < 16; ++k) {
+            const int64_t c = c0 + ty + 4 * k, r = r0 + tx;
+            if (r < rows_p && c < cols_p) trans[c * ld_trans + r] = tile[tx * kTileLd + ty + 4 * k];
+        }
     }
 }
 
@@ -229,14 +276,19 @@ hipError_t launch_muon_normalise(const void* g, const void* m, int64_t rows, int
 {
     const dim3 grid((uint32_t)(cols_p / 64), (uint32_t)(rows_p / 64));
     if (grid.y > 65535u) return hipErrorInvalidValue;
-    if (grad_bf16)
-        muon_normalise_kernel<true><<<grid, dim3(256), 0, stream>>>(g, static_cast<const float*>(m), rows, cols, rows_p, cols_p, coef,
-                                                                    sumsq, mu, nesterov, static_cast<uint16_t*>(same), ld_same,
-                                                                    static_cast<uint16_t*>(trans), ld_trans);
-    else
-        muon_normalise_kernel<false><<<grid, dim3(256), 0, stream>>>(g, static_cast<const float*>(m), rows, cols, rows_p, cols_p, coef,
-                                                                     sumsq, mu, nesterov, static_cast<uint16_t*>(same), ld_same,
-                                                                     static_cast<uint16_t*>(trans), ld_trans);
+    auto misaligned = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
+    // the padded extents are multiples of 64 and the workspace rows of 128 elements, so only the caller's arrays decide
+    const bool vec = cols % 4 == 0 && !misaligned(g, grad_bf16 ? 8 : 16) && !misaligned(m, 16) && !misaligned(same, 8) &&
+                     !misaligned(trans, 8) && ld_same % 4 == 0 && ld_trans % 4 == 0;
+    const float* mf = static_cast<const float*>(m);
+    uint16_t *sp = static_cast<uint16_t*>(same), *tp = static_cast<uint16_t*>(trans);
+#define ADAGC_NORMALISE(B, V) \
+    muon_normalise_kernel<B, V><<<grid, dim3(256), 0, stream>>>(g, mf, rows, cols, rows_p, cols_p, coef, sumsq, mu, nesterov, sp, ld_same, tp, ld_trans)
+    if (grad_bf16 && vec) ADAGC_NORMALISE(true, true);
+    else if (grad_bf16) ADAGC_NORMALISE(true, false);
+    else if (vec) ADAGC_NORMALISE(false, true);
+    else ADAGC_NORMALISE(false, false);
+#undef ADAGC_NORMALISE
     return hipGetLastError();
 }
 

@@ -2,13 +2,21 @@
 the published algorithm written out there is pinned to the mathematics: the exact Newton-Schulz iteration is an
 odd polynomial acting on the singular values (checked through the library's SVD), its fixed-point region, the
 invariances of the iteration, the bf16 rounding against the library cast, hand-worked momentum steps."""
+import importlib.util
 import math
+import os
 
 import numpy as np
 import torch
 
 import oracle
 from oracle import muon as M
+
+if os.environ.get("ADAGC_MUON_ORACLE_SRC"):
+    # tests/test_muon_pins_catch_planted_mistakes.py runs this file against altered copies of the oracle's source
+    _spec = importlib.util.spec_from_file_location("muon_under_test", os.environ["ADAGC_MUON_ORACLE_SRC"])
+    M = importlib.util.module_from_spec(_spec)
+    _spec.loader.exec_module(M)
 
 
 def test_bf16_rounding_matches_the_library_cast():
@@ -117,3 +125,20 @@ def test_muon_update_hand_worked():
     th, mo = np.zeros((8, 2), np.float32), np.zeros((8, 2), np.float32)
     o = M.muon_update(th, gt, mo, 1.0, lr=1.0, weight_decay=0.0, mu=0.0, storage="exact")
     np.testing.assert_allclose(th, (-2.0 * o).astype(np.float32), rtol=0, atol=0)
+
+
+def test_coefficients_are_the_published_ones():
+    """(a, b, c) and the guard are constants of the published algorithm (the paper prints none of them): kept as a
+    text fixture with its citation, and checked for what the publication says of them: slope a at zero, and a band
+    around one that five steps reach from 0.02 upwards."""
+    vals = {}
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "muon_published.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            vals[k.strip()] = float(v)
+    assert M.NS_COEFFS == (vals["ns_a"], vals["ns_b"], vals["ns_c"]) and M.NS_EPS == vals["ns_eps"]
+    a, b, c = M.NS_COEFFS
+    one_step = lambda s: a * s + b * s ** 3 + c * s ** 5
+    assert abs(one_step(1e-9) / 1e-9 - a) < 1e-6
+    assert abs(one_step(1.0) - (a + b + c)) < 1e-15 and 0.69 < a + b + c < 0.71

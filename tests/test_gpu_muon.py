@@ -517,3 +517,79 @@ def test_muon_batch_of_32_at_llama3_8b_shapes(shape, with_oracle):
     say("matrix %d of a batch of %d at %s: rms difference %.2e of rms %.2e, %.1f %% of the values identical"
         % (i, count, shape, diff, rms, 100 * float((O == o_ref).mean())))
     assert diff <= 0.01 * rms
+
+
+# --------------------------------------------------------------------------- the comparisons have teeth
+
+def _oracle_with_mistake(k):
+    """oracle/muon.py with mistake k of tests/test_muon_pins_catch_planted_mistakes.py planted (None: unmodified), as a module."""
+    import types
+    import test_muon_pins_catch_planted_mistakes as planted_muon
+    mod = types.ModuleType("muon_with_mistake")
+    exec(compile(planted_muon._mutated(k), "muon_with_mistake.py", "exec"), mod.__dict__)
+    return mod
+
+
+def _compare_one_newton_schulz_step(om, x0, x1):
+    """The bar of test_muon_newton_schulz_step_by_step for the first step."""
+    for i in range(len(x0)):
+        ref = om.ns_iterate(x0[i], 1)
+        d = _bf16_ulps(x1[i], ref)
+        rel = np.abs(x1[i] - ref) / np.abs(ref).max(axis=1, keepdims=True)
+        assert ((d <= 4) | (rel <= 2.0 ** -9)).all() and (d > 0).mean() < 0.02, "tensor %d" % i
+
+
+def _compare_step_without_iteration(om, shapes, g, m, th, coefs, gpu_theta, gpu_m):
+    """The bars of test_muon_momentum_normalisation_and_update_without_iteration: momentum to 1e-5, parameters through
+    X0 = bf16(U / ||U||) to one bf16 step of X0."""
+    lr, wd = float(np.float32(0.02)), float(np.float32(0.1))
+    for i, s in enumerate(shapes):
+        th_ref, m_ref = th[i].copy(), m[i].copy()
+        o_ref = om.muon_update(th_ref, g[i], m_ref, float(coefs[i]), lr=0.02, weight_decay=0.1, mu=0.95, steps=0)
+        assert (np.abs(gpu_m[i].astype(np.float64) - m_ref) <= 1e-5 * np.abs(m_ref)).all(), "momentum of tensor %d" % i
+        bound = 1e-5 * np.abs(th_ref) + lr * om.update_scale(*s) * 2.0 ** -7 * np.abs(o_ref) + 1e-12
+        assert (np.abs(gpu_theta[i].astype(np.float64) - th_ref) <= bound).all(), "parameters of tensor %d" % i
+
+
+def test_muon_comparisons_notice_a_wrong_oracle():
+    """Mistakes planted in a copy of the Muon oracle (on the CPU; the GPU library is the one under test, unaltered):
+    the comparisons used above must fail against every one of them, and pass against the unmodified copy."""
+    import test_muon_pins_catch_planted_mistakes as planted_muon
+    names = [n for n, _, _ in planted_muon.MISTAKES]
+    g, m, th = _inputs(6)
+    gamma = np.array([oracle.l2_norm(x.reshape(-1)) for x in g], np.float32)
+    gamma[::2] *= np.float32(0.5)
+    # one Newton-Schulz step: X0 and X1 from the GPU
+    big = np.full(len(SHAPES), 1e9, np.float32)
+    X = []
+    for k in (0, 1):
+        O, _ = _direction(SHAPES, g, m, big, dict(t_start=0), B.make_muon_hyper(ns_steps=k), 3)
+        X.append([o.T if s[0] > s[1] else o for o, s in zip(O, SHAPES)])
+    # a step without iteration, every other tensor clipped
+    hp = B.make_hyper(lr=0.02, weight_decay=0.1, t_start=0)
+    res = _gpu_muon(SHAPES, g, m, th, gamma, hp, B.make_muon_hyper(ns_steps=0), 7)
+    lam, beta = float(np.float32(1.04)), float(np.float32(0.99))
+    coefs = [oracle.adagc_rule(oracle.l2_norm(g[i].reshape(-1)), float(gamma[i]), lam, beta)[0] for i in range(len(SHAPES))]
+    assert sum(c < 1.0 for c in coefs) >= 3
+    clean = _oracle_with_mistake(None)
+    _compare_one_newton_schulz_step(clean, X[0], X[1])
+    _compare_step_without_iteration(clean, SHAPES, g, m, th, coefs, res[0], res[1])
+    # (where a stored value is rounded -- "A not rounded when stored", "A A from the unrounded A" -- moves results by less
+    # than the fp32-against-exact accumulation slack of these comparisons; the oracle's own pins fix those points)
+    in_step = ["b and c exchanged", "a dropped from the update of X", "polynomial applied from the right", "one step short"]
+    in_update = ["spectral norm instead of Frobenius", "Nesterov term without the momentum factor", "Nesterov and plain momentum exchanged",
+                 "clip coefficient dropped", "momentum as an average", "update scale without the root", "update scale upside down",
+                 "decay outside the learning rate", "tall matrices not transposed", "result of a tall matrix not transposed back"]
+    unnoticed = []
+    for name in in_step + in_update:
+        om = _oracle_with_mistake(names.index(name))
+        try:
+            if name in in_step:
+                _compare_one_newton_schulz_step(om, X[0], X[1])
+            else:
+                _compare_step_without_iteration(om, SHAPES, g, m, th, coefs, res[0], res[1])
+            unnoticed.append(name)
+        except (AssertionError, ValueError):          # ValueError: a shape mismatch the mistake causes
+            pass
+    say("Muon comparisons: %d of %d planted oracle mistakes noticed" % (len(in_step) + len(in_update) - len(unnoticed), len(in_step) + len(in_update)))
+    assert not unnoticed, unnoticed

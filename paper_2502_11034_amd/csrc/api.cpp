@@ -582,6 +582,11 @@ extern "C" int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* 
                                              bf16g, x + z * mn, np, y + z * mn, mp, stream);
             if (g != hipSuccess) return ADAGC_ERR_HIP;
         }
+        bool any_tall = false, any_wide = false;
+        for (int64_t i : bt.members) {
+            if (ctx->shapes[(size_t)i].rows > ctx->shapes[(size_t)i].cols) any_tall = true;
+            else any_wide = true;
+        }
         for (int k = 0; k < mh->ns_steps; ++k) {
             // A = X X^T (symmetric: its transposed store is itself)
             if (launch_gemm_nt_bf16(x, np, x, np, mp, mp, np, 1.0f, 0.0f, nullptr, 0, nullptr, 0, wa, mp, stream, true, count, mn, mn,
@@ -591,9 +596,13 @@ extern "C" int adagc_muon_step(adagc_ctx* ctx, void* const* params, const void* 
             if (launch_gemm_nt_bf16(wa, mp, wa, mp, mp, mp, mp, ns_c, ns_b, wa, mp, nullptr, 0, wb, mp, stream, true, count, mm, mm, mm,
                                     mm, mm) != hipSuccess)
                 return ADAGC_ERR_HIP;
-            // X' = a X + B X, written as X' and as Y' = X'^T; (B X)[i][j] = sum_k B[i][k] Y[j][k]
-            if (launch_gemm_nt_bf16(wb, mp, y, mp, mp, np, mp, 1.0f, ns_a, y, mp, x2, np, y2, mp, stream, false, count, mm, mn, mn, mn,
-                                    mn) != hipSuccess)
+            // X' = a X + B X, written as X' and as Y' = X'^T; (B X)[i][j] = sum_k B[i][k] Y[j][k].  After the last step
+            // only the orientation the update reads is needed: X' for wide matrices, Y' for tall ones.
+            const bool last = k + 1 == mh->ns_steps;
+            uint16_t* out_x = (last && !any_wide) ? nullptr : x2;
+            uint16_t* out_y = (last && !any_tall) ? nullptr : y2;
+            if (launch_gemm_nt_bf16(wb, mp, y, mp, mp, np, mp, 1.0f, ns_a, y, mp, out_x, np, out_y, mp, stream, false, count, mm, mn, mn,
+                                    mn, mn) != hipSuccess)
                 return ADAGC_ERR_HIP;
             uint16_t* s = x; x = x2; x2 = s;
             s = y; y = y2; y2 = s;

@@ -593,3 +593,43 @@ def test_muon_comparisons_notice_a_wrong_oracle():
             pass
     say("Muon comparisons: %d of %d planted oracle mistakes noticed" % (len(in_step) + len(in_update) - len(unnoticed), len(in_step) + len(in_update)))
     assert not unnoticed, unnoticed
+
+
+def test_muon_with_bf16_gradients():
+    """Gradients handed over as bf16 (widened exactly in the kernels): the oracle gets the same values as float32.
+    Without iteration the momentum and X0 are held to the strict bars; with five steps the result to 1 % rms."""
+    shapes = SHAPES + [(96, 130)]
+    g, m, th = _inputs(9, shapes)
+    g = [OM.to_bf16(x).astype(np.float32) for x in g]                    # bf16-representable values
+    gamma = np.array([oracle.l2_norm(x.reshape(-1)) for x in g], np.float32)
+    gamma[::2] *= np.float32(0.5)
+    lam, beta = float(np.float32(1.04)), float(np.float32(0.99))
+    for ns_steps in (0, 5):
+        ctx = B.AdaGC([r * c for r, c in shapes], B.ADAGC_OPT_MUON, B.ADAGC_GRAD_BF16)
+        ctx.muon_attach(shapes)
+        dg = [torch.from_numpy(x.reshape(-1).copy()).to(torch.bfloat16).to(DEV) for x in g]
+        dm = _dev(m)
+        dth = _dev([np.zeros(s, np.float32) for s in shapes])
+        dgam = torch.from_numpy(gamma.copy()).to(DEV)
+        ctx.muon_step(dth, dg, dm, dgam, B.make_hyper(lr=1.0, weight_decay=0.0, t_start=0), B.make_muon_hyper(ns_steps=ns_steps), 5)
+        norms, coefs, flags = ctx.get_norms()
+        ctx.close()
+        clipped = 0
+        for i, s in enumerate(shapes):
+            n = oracle.l2_norm(g[i].reshape(-1))
+            h, _, c = oracle.adagc_rule(n, float(gamma[i]), lam, beta)
+            np.testing.assert_allclose(norms[i], n, rtol=1e-5)
+            np.testing.assert_allclose(coefs[i], h, rtol=1e-5)
+            assert flags[i] == c
+            clipped += c
+            th_ref, m_ref = np.zeros(s, np.float32), m[i].copy()
+            o_ref = OM.muon_update(th_ref, g[i], m_ref, h, lr=1.0, weight_decay=0.0, mu=0.95, steps=ns_steps)
+            gm = to_numpy(dm[i]).reshape(s)
+            assert (np.abs(gm.astype(np.float64) - m_ref) <= 1e-5 * np.abs(m_ref)).all(), "momentum of tensor %d" % i
+            O = OM.to_bf16(-(to_numpy(dth[i]).reshape(s).astype(np.float64)) / OM.update_scale(*s))
+            if ns_steps == 0:
+                d = _bf16_ulps(O, o_ref)
+                assert d.max() <= 1 and (d > 0).mean() < 0.01, "X0 of tensor %d" % i
+            else:
+                assert np.sqrt(np.mean((O - o_ref) ** 2)) <= 0.01 * np.sqrt(np.mean(o_ref ** 2)), "tensor %d" % i
+        assert clipped >= 3

@@ -1,4 +1,6 @@
 """GPU parity of the Muon path against the numpy oracle (oracle/muon.py), through the C ABI."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -633,3 +635,46 @@ def test_muon_with_bf16_gradients():
             else:
                 assert np.sqrt(np.mean((O - o_ref) ** 2)) <= 0.01 * np.sqrt(np.mean(o_ref ** 2)), "tensor %d" % i
         assert clipped >= 3
+
+
+@pytest.mark.parametrize("mode", [B.ADAGC_MODE_GLOBALGC, B.ADAGC_MODE_GLOBAL_ADAGC, B.ADAGC_MODE_ZCLIP])
+def test_muon_with_the_global_clipping_rules(mode):
+    """Muon takes its clip coefficient from the same rule kernels as AdamW and Lion: the model-wide rules (GlobalGC on
+    every step, Global AdaGC, ZClip) over four steps with a spike on the last; norms, coefficients, flags and the rule's
+    state against the C oracle's list step (run with Lion on scratch arrays: the rule does not depend on the optimizer),
+    the momentum against the Muon oracle with that coefficient."""
+    shapes = SHAPES
+    n = len(shapes)
+    grads = [[x * (np.float32(6.0) if step == 4 else np.float32(1.0)) for x in _inputs(40 + step, shapes)[0]] for step in (1, 2, 3, 4)]
+    global_norm = math.sqrt(sum(oracle.l2_norm(x.reshape(-1)) ** 2 for x in grads[0]))
+    kw = dict(lr=0.02, weight_decay=0.1, lambda_abs=0.8 * global_norm, t_start=2, clip_mode=mode,
+              ema_beta=0.97 if mode == B.ADAGC_MODE_ZCLIP else 0.99)
+    hp = B.make_hyper(**kw)
+    oh = oracle.Hyper(optimizer=oracle.LION, **kw)
+    mh = B.make_muon_hyper()
+    ctx = B.AdaGC([r * c for r, c in shapes], B.ADAGC_OPT_MUON, B.ADAGC_GRAD_F32)
+    ctx.muon_attach(shapes)
+    _, _, th0 = _inputs(5, shapes)
+    dm, dth = _dev([np.zeros(s, np.float32) for s in shapes]), _dev(th0)
+    dgam = torch.zeros(max(n, 2), dtype=torch.float32, device=DEV)
+    h_gam = np.zeros(max(n, 2), np.float32)
+    h_m = [np.zeros(s, np.float32) for s in shapes]
+    h_th = [t.copy() for t in th0]
+    scratch_th = [np.zeros(r * c, np.float32) for r, c in shapes]
+    scratch_m = [np.zeros(r * c, np.float32) for r, c in shapes]
+    clipped_steps = 0
+    for step, g in zip((1, 2, 3, 4), grads):
+        ctx.muon_step(dth, _dev(g), dm, dgam, hp, mh, step)
+        norms, coefs, flags = ctx.get_norms()
+        o_norms, o_coefs, o_flags = oracle.adagc_step(scratch_th, [x.reshape(-1) for x in g], scratch_m, None, h_gam, oh, step)
+        np.testing.assert_allclose(norms, o_norms, rtol=1e-5)
+        np.testing.assert_allclose(coefs, o_coefs, rtol=1e-5)
+        assert np.array_equal(flags, o_flags)
+        np.testing.assert_allclose(to_numpy(dgam), h_gam, rtol=1e-5)
+        clipped_steps += int(o_flags.any())
+        for i, s in enumerate(shapes):
+            OM.muon_update(h_th[i], g[i], h_m[i], float(o_coefs[i]), lr=0.02, weight_decay=0.1, mu=0.95)
+            gm = to_numpy(dm[i]).reshape(s)
+            assert (np.abs(gm.astype(np.float64) - h_m[i]) <= 1e-5 * np.abs(h_m[i])).all(), "step %d tensor %d" % (step, i)
+    assert clipped_steps >= 1 and o_flags.all()          # the spike step clips the whole model
+    ctx.close()

@@ -678,3 +678,27 @@ def test_muon_with_the_global_clipping_rules(mode):
             assert (np.abs(gm.astype(np.float64) - h_m[i]) <= 1e-5 * np.abs(h_m[i])).all(), "step %d tensor %d" % (step, i)
     assert clipped_steps >= 1 and o_flags.all()          # the spike step clips the whole model
     ctx.close()
+
+
+def test_muon_step_on_a_side_stream_equals_the_default_stream():
+    """Every launch of the step goes to the caller's stream: a step enqueued on a side stream (after an event that orders
+    it behind the inputs' uploads) gives, bit for bit, the default stream's result."""
+    shapes = [(64, 200), (300, 100), (128, 128), (128, 128)]
+    g, m, th = _inputs(12, shapes)
+    gamma = np.array([oracle.l2_norm(x.reshape(-1)) for x in g], np.float32) * np.float32(0.7)
+    hp = B.make_hyper(lr=0.02, weight_decay=0.1, t_start=0)
+    mh = B.make_muon_hyper()
+    ref = _gpu_muon(shapes, g, m, th, gamma, hp, mh, 4)
+    ctx = B.AdaGC([r * c for r, c in shapes], B.ADAGC_OPT_MUON, B.ADAGC_GRAD_F32)
+    ctx.muon_attach(shapes)
+    dg, dm, dth = _dev(g), _dev(m), _dev(th)
+    dgam = torch.from_numpy(gamma.copy()).to(DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    ctx.muon_step(dth, dg, dm, dgam, hp, mh, 4, stream=side.cuda_stream)
+    side.synchronize()
+    for i, s in enumerate(shapes):
+        assert np.array_equal(to_numpy(dth[i]).reshape(s).view(np.uint32), ref[0][i].view(np.uint32))
+        assert np.array_equal(to_numpy(dm[i]).reshape(s).view(np.uint32), ref[1][i].view(np.uint32))
+    assert np.array_equal(to_numpy(dgam), ref[2])
+    ctx.close()

@@ -361,8 +361,8 @@ typedef struct {
 /*
  * Give the context the matrices' shapes and allocate the Newton-Schulz workspace.  Once per context.
  * Matrices whose extents, rounded up to multiples of 128, are equal are iterated together, up to 32 at a time
- * (fewer if 32 would need more than 24 GiB), by batched launches of the matrix-core product: one launch over many
- * matrices fills the GPU where one matrix has too few tiles.  The workspace (bf16) holds the largest such batch: per
+ * (fewer if 32 would need more than 24 GiB, or more than the device can give), by batched launches of the
+ * matrix-core product: one launch over many matrices fills the GPU where one matrix has too few tiles.  The workspace (bf16) holds the largest such batch: per
  * matrix four copies of its padded min x max extent and two of min x min (adagc_muon_workspace_bytes tells the
  * total).  A matrix's result does not depend on which others share its batch.
  *   shapes  HOST  n_tensors entries, copied

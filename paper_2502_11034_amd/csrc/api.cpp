@@ -464,7 +464,6 @@ extern "C" int adagc_muon_attach(adagc_ctx* ctx, const adagc_matrix_shape* shape
     if (!ctx || !shapes) return ADAGC_ERR_INVALID_ARG;
     if (ctx->cfg.optimizer != ADAGC_OPT_MUON || ctx->muon_ws) return ADAGC_ERR_STATE;
     std::vector<adagc_ctx::MuonBatch> groups, batches;
-    int64_t ws_elems = 0;
     try {
         for (int64_t i = 0; i < ctx->n_tensors; ++i) {
             const int64_t r = shapes[i].rows, c = shapes[i].cols;
@@ -480,37 +479,54 @@ extern "C" int adagc_muon_attach(adagc_ctx* ctx, const adagc_matrix_shape* shape
             }
             groups[g].members.push_back(i);
         }
-        // cut every group into batches of equal size (to one matrix), as large as the limits allow
-        for (const adagc_ctx::MuonBatch& grp : groups) {
-            const int64_t per_matrix = muon_ws_elems(grp.mp, grp.np) * (int64_t)sizeof(uint16_t);
-            int64_t cap = kMuonWorkspaceBudget / per_matrix;
-            if (cap > kMuonMaxBatch) cap = kMuonMaxBatch;
-            if (cap < 1) cap = 1;
-            const int64_t count = (int64_t)grp.members.size();
-            const int64_t n_batches = (count + cap - 1) / cap;
-            const int64_t size = (count + n_batches - 1) / n_batches;
-            for (int64_t first = 0; first < count; first += size) {
-                const int64_t n = count - first < size ? count - first : size;
-                batches.emplace_back();
-                batches.back().mp = grp.mp;
-                batches.back().np = grp.np;
-                batches.back().members.assign(grp.members.begin() + first, grp.members.begin() + first + n);
-                const int64_t need = n * muon_ws_elems(grp.mp, grp.np);
-                if (need > ws_elems) ws_elems = need;
-            }
-        }
         ctx->shapes.assign(shapes, shapes + ctx->n_tensors);
     } catch (const std::bad_alloc&) { return ADAGC_ERR_OOM; }
     DeviceGuard guard(ctx->device);
-    if (!guard.ok) return ADAGC_ERR_HIP;
-    const size_t bytes = (size_t)ws_elems * sizeof(uint16_t);
-    const hipError_t e = hipMalloc(&ctx->muon_ws, bytes);
-    if (e != hipSuccess) {
-        ctx->muon_ws = nullptr;
+    if (!guard.ok) {
         ctx->shapes.clear();
-        return e == hipErrorOutOfMemory ? ADAGC_ERR_OOM : ADAGC_ERR_HIP;
+        return ADAGC_ERR_HIP;
     }
-    ctx->muon_ws_bytes = bytes;
+    // Cut every group into batches of equal size (to one matrix), as large as the limits allow, and allocate the
+    // workspace for the largest batch.  If the device cannot give that much, try again with half the batch limit.
+    for (int64_t limit = kMuonMaxBatch;; limit /= 2) {
+        int64_t ws_elems = 0;
+        try {
+            batches.clear();
+            for (const adagc_ctx::MuonBatch& grp : groups) {
+                const int64_t per_matrix = muon_ws_elems(grp.mp, grp.np) * (int64_t)sizeof(uint16_t);
+                int64_t cap = kMuonWorkspaceBudget / per_matrix;
+                if (cap > limit) cap = limit;
+                if (cap < 1) cap = 1;
+                const int64_t count = (int64_t)grp.members.size();
+                const int64_t n_batches = (count + cap - 1) / cap;
+                const int64_t size = (count + n_batches - 1) / n_batches;
+                for (int64_t first = 0; first < count; first += size) {
+                    const int64_t n = count - first < size ? count - first : size;
+                    batches.emplace_back();
+                    batches.back().mp = grp.mp;
+                    batches.back().np = grp.np;
+                    batches.back().members.assign(grp.members.begin() + first, grp.members.begin() + first + n);
+                    const int64_t need = n * muon_ws_elems(grp.mp, grp.np);
+                    if (need > ws_elems) ws_elems = need;
+                }
+            }
+        } catch (const std::bad_alloc&) {
+            ctx->shapes.clear();
+            return ADAGC_ERR_OOM;
+        }
+        const size_t bytes = (size_t)ws_elems * sizeof(uint16_t);
+        const hipError_t e = hipMalloc(&ctx->muon_ws, bytes);
+        if (e == hipSuccess) {
+            ctx->muon_ws_bytes = bytes;
+            break;
+        }
+        ctx->muon_ws = nullptr;
+        (void)hipGetLastError();          // the failed allocation is handled here: do not leave its error for the next call
+        if (e != hipErrorOutOfMemory || limit == 1) {
+            ctx->shapes.clear();
+            return e == hipErrorOutOfMemory ? ADAGC_ERR_OOM : ADAGC_ERR_HIP;
+        }
+    }
     ctx->muon_batches.swap(batches);
     return ADAGC_OK;
 }

@@ -702,3 +702,28 @@ def test_muon_step_on_a_side_stream_equals_the_default_stream():
         assert np.array_equal(to_numpy(dm[i]).reshape(s).view(np.uint32), ref[1][i].view(np.uint32))
     assert np.array_equal(to_numpy(dgam), ref[2])
     ctx.close()
+
+
+def test_muon_attach_takes_smaller_batches_when_memory_is_short():
+    """32 matrices of 14336 x 4096 want 17.2 GB of workspace; with about 12 GB free the attach settles for batches of 16
+    (8.6 GB) instead of failing.  Only the context is created: attach needs no tensor."""
+    shape, count = (14336, 4096), 32
+    per_matrix = (4 * 4096 * 14336 + 2 * 4096 * 4096) * 2
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    leave = 12 << 30
+    if free < leave + (1 << 30):
+        pytest.skip("not enough free device memory to stage the shortage")
+    hog = torch.empty(free - leave, dtype=torch.uint8, device=DEV)
+    try:
+        ctx = B.AdaGC([shape[0] * shape[1]] * count, B.ADAGC_OPT_MUON, B.ADAGC_GRAD_F32)
+        ctx.muon_attach([shape] * count)
+        assert ctx.muon_workspace_bytes() == 16 * per_matrix
+        ctx.close()
+    finally:
+        del hog
+        torch.cuda.empty_cache()
+    ctx = B.AdaGC([shape[0] * shape[1]] * count, B.ADAGC_OPT_MUON, B.ADAGC_GRAD_F32)
+    ctx.muon_attach([shape] * count)
+    assert ctx.muon_workspace_bytes() == 32 * per_matrix
+    ctx.close()
